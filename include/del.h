@@ -1,0 +1,162 @@
+/*
+ * del.h - C ABI of the MI355X (gfx950) library for the greedy self-speculative
+ * decode round with DEL (Dynamic Exit Layer, arXiv 2504.05598).
+ *
+ * One context = one Llama-style decoder resident on one GPU, one KV cache,
+ * one sequence (batch 1).  The call order is
+ *     del_create -> del_load_weights (until every tensor is loaded)
+ *                -> del_prefill -> del_round* [-> del_prefill -> ...]
+ * Every entry point returns a del_status, never throws and never aborts.
+ * Unless a parameter says "device", pointers are HOST pointers owned by the
+ * caller; outputs are caller-allocated.  A context is not thread-safe.  All GPU
+ * work of a context runs on the stream given to del_create and every call has
+ * completed its GPU work when it returns.
+ *
+ * Layer numbering follows the paper (Section 2): layers 1..L, h^0 is the
+ * embedding of the input token, h^l the output of layer l.  Exit layer E is
+ * the number of layers the draft runs.
+ */
+#ifndef DEL_H
+#define DEL_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct del_ctx del_ctx; /* opaque; owned by the library */
+
+typedef enum {
+  DEL_OK = 0,
+  DEL_E_ARG = 1,      /* null pointer, value out of range                      */
+  DEL_E_STATE = 2,    /* call out of order (e.g. round before prefill)         */
+  DEL_E_CAPACITY = 3, /* KV cache would exceed max_context; state unchanged    */
+  DEL_E_SHAPE = 4,    /* tensor shape does not match the configuration         */
+  DEL_E_DEVICE = 5,   /* a HIP call failed; del_last_error_text has the detail */
+  DEL_E_NOMEM = 6     /* device or host allocation failed                      */
+} del_status;
+
+enum { DEL_DTYPE_FP32 = 0, DEL_DTYPE_BF16 = 1 };
+enum { DEL_MEM_HOST = 0, DEL_MEM_DEVICE = 1 };
+
+/* Model shape and DEL hyper-parameters. */
+typedef struct {
+  int32_t n_layers;        /* L                                                     */
+  int32_t d_model;
+  int32_t n_q_heads;
+  int32_t n_kv_heads;      /* divides n_q_heads; q head j reads kv head j/(nq/nkv)  */
+  int32_t head_dim;        /* multiple of 16; n_q_heads*head_dim need not = d_model */
+  int32_t d_ffn;           /* multiple of 8                                         */
+  int32_t vocab;
+  float rope_theta;
+  float rms_eps;
+  int32_t tied_embeddings; /* 1: the LM head is the embedding matrix                */
+  int32_t weight_dtype;    /* DEL_DTYPE_*; matrices only, norm gains are fp32.
+                              The KV cache is stored in the same type.              */
+  int32_t max_context;     /* KV rows per layer; >= prompt + generated + d_max + 1  */
+  int32_t d_max;           /* cap on the speculation length gamma (Section 4.3)     */
+  int32_t prefill_window;  /* prompt positions that seed the statistics (App. B.2)  */
+  double omega;            /* decay of the weighted sum S (Section 4.2, App. B.2)   */
+  int32_t use_mfma;        /* 1: multi-row GEMMs on the matrix cores (bf16 weights);
+                              0: plain vector-ALU kernels everywhere                */
+} del_config;
+
+typedef enum {
+  DEL_T_EMBED = 0, DEL_T_LM_HEAD = 1, DEL_T_FINAL_NORM = 2,
+  DEL_T_ATTN_NORM = 3, DEL_T_WQ = 4, DEL_T_WK = 5, DEL_T_WV = 6, DEL_T_WO = 7,
+  DEL_T_FFN_NORM = 8, DEL_T_WG = 9, DEL_T_WU = 10, DEL_T_WD = 11
+} del_tensor_kind;
+
+/* One weight tensor, row-major [rows, cols] = [out_features, in_features]
+ * (norm gains: rows = 1).  Matrices are in cfg.weight_dtype, gains in fp32. */
+typedef struct {
+  int32_t layer;    /* 0..L-1; -1 for EMBED / LM_HEAD / FINAL_NORM            */
+  int32_t kind;     /* del_tensor_kind                                        */
+  int32_t location; /* DEL_MEM_HOST or DEL_MEM_DEVICE: where `data` lives     */
+  int32_t reserved;
+  const void* data; /* caller keeps ownership; copied before the call returns */
+  int64_t rows, cols;
+} del_tensor;
+
+/* Create a context: allocates weights, KV cache and work buffers on the
+ * current HIP device.  `hip_stream` is a hipStream_t (NULL = default stream). */
+del_status del_create(const del_config* cfg, void* hip_stream, del_ctx** out);
+void del_destroy(del_ctx* ctx);
+
+/* Copy `n` tensors into the context, re-tiling them into the layout the
+ * kernels stream (the decoder of Section 2, "Auto-regressive decoding"; the
+ * paper treats Transformer_l as a black box, the block is the pre-norm Llama
+ * block).  May be called repeatedly with subsets (one layer at a time for the
+ * largest shapes).  With tied embeddings LM_HEAD must not be loaded.
+ * Errors: DEL_E_SHAPE on a shape mismatch, DEL_E_ARG on bad layer/kind/pointer. */
+del_status del_load_weights(del_ctx* ctx, const del_tensor* tensors, int32_t n);
+
+/* Prefill (Section 4.3; Algorithm 1, initialisation; Appendix B.2): resets the KV
+ * cache and the statistics, runs all L layers over the `n_prompt` prompt tokens,
+ * seeds the per-layer acceptance statistics from the last
+ * min(prefill_window, n_prompt) positions (every layer's shadow token against
+ * layer L's), returns the first generated token and the first (E, gamma).
+ * Errors: DEL_E_STATE before all weights are loaded; DEL_E_CAPACITY if
+ * n_prompt + 1 > max_context; DEL_E_ARG for ids outside [0, vocab). */
+del_status del_prefill(del_ctx* ctx, const int32_t* prompt, int32_t n_prompt,
+                       int32_t* first_token, int32_t* next_E, int32_t* next_gamma);
+
+/* One greedy self-speculative round (Section 2, "Early-exit self-speculative
+ * decoding"; Algorithm 1, loop body without the confidence break):
+ *   draft   gamma tokens with layers 1..E + final norm + LM head + arg-max;
+ *   verify  the gamma+1 positions through layers E+1..L, reusing the exit-layer
+ *           hidden states and the KV cache, accept the longest matching prefix;
+ *   DEL     shadow tokens of every layer for the gamma+1 positions, u_r, c_r^l,
+ *           decayed sums, alpha_l, TPL arg-max (Sections 4.1-4.3, Eq. 1-2).
+ * 1 <= E <= L, 0 <= gamma <= d_max.  out_tokens has room for gamma+1 ids;
+ * *n_out in [1, gamma+1] = accepted drafts + 1 token of the target model.
+ * The selected (E, gamma) for the next round is read with del_layer_stats.
+ * Errors: DEL_E_STATE before prefill, DEL_E_ARG, DEL_E_CAPACITY (state unchanged). */
+del_status del_round(del_ctx* ctx, int32_t E, int32_t gamma, int32_t* out_tokens, int32_t* n_out);
+
+/* Per-layer statistics (Section 4.2; Eq. 2).  Arrays are caller-allocated and
+ * indexed by layer number 0..L (entry 0 unused).  Any array pointer may be NULL. */
+typedef struct {
+  int32_t n_layers, rounds;  /* rounds since prefill                               */
+  int32_t next_E, next_gamma;/* arg-max of TPL after the last update               */
+  int32_t last_E, last_gamma, last_u, last_n; /* last round: u_r and n_r = u_r + 1 */
+  double S_n;                /* decayed sum of valid-position counts               */
+  double* S_c;               /* [L+1] decayed sums of matched counts               */
+  double* alpha;             /* [L+1] S_c[l] / S_n                                 */
+  int32_t* last_c;           /* [L+1] c_r^l of the last round (or of the prefill)  */
+  int32_t* last_shadow;      /* [(L+1)*(d_max+1)] shadow ids, row-major by layer;
+                                row l, entries 0..last_gamma (prefill: not filled) */
+  int32_t* last_draft;       /* [d_max] drafted ids of the last round              */
+} del_stats;
+del_status del_layer_stats(const del_ctx* ctx, del_stats* out);
+/* Import S_n and S_c (resume, or re-synchronise a test harness); recomputes alpha
+ * and the next (E, gamma).  Only S_n and S_c are read. */
+del_status del_set_layer_stats(del_ctx* ctx, const del_stats* in);
+
+/* Wall time of the segments of the last round, from HIP events on the stream. */
+del_status del_last_timings(const del_ctx* ctx, float* draft_ms, float* verify_ms, float* shadow_ms);
+
+/* Test hooks.  Hidden state of layer `layer` (0..L), row `row` of the last
+ * round (0..gamma) or of the last prefill chunk, as d_model floats. */
+del_status del_debug_hidden(const del_ctx* ctx, int32_t layer, int32_t row, float* dst);
+/* Logits (vocab floats) of the LM head applied, after the final norm, to that row. */
+del_status del_debug_logits(del_ctx* ctx, int32_t layer, int32_t row, float* dst);
+/* Current KV length T and the pending input token. */
+del_status del_debug_state(const del_ctx* ctx, int32_t* kv_len, int32_t* pending_token);
+/* Replace the pending input token (the token the next round starts from).  A lock-step
+ * test harness uses it after re-prefilling on a context whose last prediction is a near-tie. */
+del_status del_debug_set_pending(del_ctx* ctx, int32_t token);
+
+/* Measurement hooks: a pure streaming read of `bytes` of the weight arena with
+ * the GEMV kernels' access pattern (sets the achievable-bandwidth ceiling), and
+ * the time of the last such call in ms. */
+del_status del_bench_stream_read(del_ctx* ctx, int64_t bytes, int32_t iters, float* ms_per_iter);
+
+const char* del_strerror(del_status s);
+const char* del_last_error_text(const del_ctx* ctx);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* DEL_H */

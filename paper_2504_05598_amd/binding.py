@@ -1,0 +1,267 @@
+"""ctypes binding of include/del.h: argument marshalling only.
+
+The module-level functions carry the C names (del_create, del_load_weights,
+del_prefill, del_round, del_layer_stats, ...); DelContext is a small
+convenience wrapper around them.  There is no CPU fallback: if the HIP library
+is missing, load_library raises.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+from typing import List, Optional, Sequence, Tuple
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+
+EXPORTS = ["del_create", "del_destroy", "del_load_weights", "del_prefill", "del_round",
+           "del_layer_stats", "del_set_layer_stats", "del_last_timings", "del_debug_hidden",
+           "del_debug_logits", "del_debug_state", "del_debug_set_pending", "del_bench_stream_read", "del_strerror",
+           "del_last_error_text"]
+
+DEL_DTYPE_FP32, DEL_DTYPE_BF16 = 0, 1
+DEL_MEM_HOST, DEL_MEM_DEVICE = 0, 1
+KIND_IDS = {"embed": 0, "lm_head": 1, "final_norm": 2, "attn_norm": 3, "wq": 4, "wk": 5, "wv": 6,
+            "wo": 7, "ffn_norm": 8, "wg": 9, "wu": 10, "wd": 11}
+
+
+class DelError(RuntimeError):
+    def __init__(self, status: int, text: str):
+        super().__init__(f"del status {status}: {text}")
+        self.status = status
+
+
+class del_config(C.Structure):
+    _fields_ = [("n_layers", C.c_int32), ("d_model", C.c_int32), ("n_q_heads", C.c_int32),
+                ("n_kv_heads", C.c_int32), ("head_dim", C.c_int32), ("d_ffn", C.c_int32),
+                ("vocab", C.c_int32), ("rope_theta", C.c_float), ("rms_eps", C.c_float),
+                ("tied_embeddings", C.c_int32), ("weight_dtype", C.c_int32),
+                ("max_context", C.c_int32), ("d_max", C.c_int32), ("prefill_window", C.c_int32),
+                ("omega", C.c_double), ("use_mfma", C.c_int32)]
+
+
+class del_tensor(C.Structure):
+    _fields_ = [("layer", C.c_int32), ("kind", C.c_int32), ("location", C.c_int32),
+                ("reserved", C.c_int32), ("data", C.c_void_p), ("rows", C.c_int64),
+                ("cols", C.c_int64)]
+
+
+class del_stats(C.Structure):
+    _fields_ = [("n_layers", C.c_int32), ("rounds", C.c_int32), ("next_E", C.c_int32),
+                ("next_gamma", C.c_int32), ("last_E", C.c_int32), ("last_gamma", C.c_int32),
+                ("last_u", C.c_int32), ("last_n", C.c_int32), ("S_n", C.c_double),
+                ("S_c", C.POINTER(C.c_double)), ("alpha", C.POINTER(C.c_double)),
+                ("last_c", C.POINTER(C.c_int32)), ("last_shadow", C.POINTER(C.c_int32)),
+                ("last_draft", C.POINTER(C.c_int32))]
+
+
+_lib = None
+
+
+def lib_path() -> str:
+    return os.path.join(_HERE, "libdel_hip.so")
+
+
+def load_library():
+    """dlopen the HIP library; raises if it has not been built (no fallback)."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    path = lib_path()
+    if not os.path.exists(path):
+        raise FileNotFoundError(f"{path} is missing: run `python -m paper_2504_05598_amd.build` "
+                                "(or __graft_entry__.build()) first")
+    lib = C.CDLL(path)
+    P = C.POINTER
+    lib.del_create.argtypes = [P(del_config), C.c_void_p, P(C.c_void_p)]
+    lib.del_destroy.argtypes = [C.c_void_p]
+    lib.del_destroy.restype = None
+    lib.del_load_weights.argtypes = [C.c_void_p, P(del_tensor), C.c_int32]
+    lib.del_prefill.argtypes = [C.c_void_p, P(C.c_int32), C.c_int32, P(C.c_int32), P(C.c_int32),
+                                P(C.c_int32)]
+    lib.del_round.argtypes = [C.c_void_p, C.c_int32, C.c_int32, P(C.c_int32), P(C.c_int32)]
+    lib.del_layer_stats.argtypes = [C.c_void_p, P(del_stats)]
+    lib.del_set_layer_stats.argtypes = [C.c_void_p, P(del_stats)]
+    lib.del_last_timings.argtypes = [C.c_void_p, P(C.c_float), P(C.c_float), P(C.c_float)]
+    lib.del_debug_hidden.argtypes = [C.c_void_p, C.c_int32, C.c_int32, P(C.c_float)]
+    lib.del_debug_logits.argtypes = [C.c_void_p, C.c_int32, C.c_int32, P(C.c_float)]
+    lib.del_debug_state.argtypes = [C.c_void_p, P(C.c_int32), P(C.c_int32)]
+    lib.del_debug_set_pending.argtypes = [C.c_void_p, C.c_int32]
+    lib.del_bench_stream_read.argtypes = [C.c_void_p, C.c_int64, C.c_int32, P(C.c_float)]
+    lib.del_strerror.argtypes = [C.c_int]
+    lib.del_strerror.restype = C.c_char_p
+    lib.del_last_error_text.argtypes = [C.c_void_p]
+    lib.del_last_error_text.restype = C.c_char_p
+    for name in EXPORTS:
+        if name not in ("del_destroy", "del_strerror", "del_last_error_text"):
+            getattr(lib, name).restype = C.c_int
+    _lib = lib
+    return lib
+
+
+def _check(status: int, ctx=None) -> None:
+    if status != 0:
+        lib = load_library()
+        text = lib.del_strerror(status).decode()
+        if ctx:
+            extra = lib.del_last_error_text(ctx).decode()
+            if extra:
+                text += " (" + extra + ")"
+        raise DelError(status, text)
+
+
+# ---- functions with the C names -------------------------------------------------------
+def del_create(cfg: del_config, stream: int = 0) -> C.c_void_p:
+    ctx = C.c_void_p()
+    _check(load_library().del_create(C.byref(cfg), C.c_void_p(stream), C.byref(ctx)))
+    return ctx
+
+
+def del_destroy(ctx) -> None:
+    load_library().del_destroy(ctx)
+
+
+def del_load_weights(ctx, tensors: Sequence[Tuple[int, str, int, int, int, int]]) -> None:
+    """tensors: (layer, kind name, data pointer, location, rows, cols)."""
+    arr = (del_tensor * len(tensors))()
+    for i, (layer, kind, ptr, loc, rows, cols) in enumerate(tensors):
+        arr[i] = del_tensor(layer, KIND_IDS[kind], loc, 0, ptr, rows, cols)
+    _check(load_library().del_load_weights(ctx, arr, len(tensors)), ctx)
+
+
+def del_prefill(ctx, prompt: Sequence[int]) -> Tuple[int, int, int]:
+    n = len(prompt)
+    buf = (C.c_int32 * n)(*prompt)
+    first, E, g = C.c_int32(), C.c_int32(), C.c_int32()
+    _check(load_library().del_prefill(ctx, buf, n, C.byref(first), C.byref(E), C.byref(g)), ctx)
+    return first.value, E.value, g.value
+
+
+def del_round(ctx, E: int, gamma: int) -> List[int]:
+    out = (C.c_int32 * (gamma + 1))()
+    n = C.c_int32()
+    _check(load_library().del_round(ctx, E, gamma, out, C.byref(n)), ctx)
+    return list(out[:n.value])
+
+
+def del_layer_stats(ctx, n_layers: int, d_max: int) -> dict:
+    L = n_layers
+    S_c = (C.c_double * (L + 1))()
+    alpha = (C.c_double * (L + 1))()
+    last_c = (C.c_int32 * (L + 1))()
+    shadow = (C.c_int32 * ((L + 1) * (d_max + 1)))()
+    draft = (C.c_int32 * max(1, d_max))()
+    st = del_stats()
+    st.S_c = C.cast(S_c, C.POINTER(C.c_double))
+    st.alpha = C.cast(alpha, C.POINTER(C.c_double))
+    st.last_c = C.cast(last_c, C.POINTER(C.c_int32))
+    st.last_shadow = C.cast(shadow, C.POINTER(C.c_int32))
+    st.last_draft = C.cast(draft, C.POINTER(C.c_int32))
+    _check(load_library().del_layer_stats(ctx, C.byref(st)), ctx)
+    g = st.last_gamma
+    return {
+        "rounds": st.rounds, "next_E": st.next_E, "next_gamma": st.next_gamma,
+        "last_E": st.last_E, "last_gamma": g, "last_u": st.last_u, "last_n": st.last_n,
+        "S_n": st.S_n, "S_c": list(S_c), "alpha": list(alpha), "last_c": list(last_c),
+        "last_shadow": [list(shadow[l * (d_max + 1): l * (d_max + 1) + g + 1]) for l in range(L + 1)],
+        "last_draft": list(draft[:g]),
+    }
+
+
+def del_set_layer_stats(ctx, S_c: Sequence[float], S_n: float) -> None:
+    arr = (C.c_double * len(S_c))(*S_c)
+    st = del_stats()
+    st.S_c = C.cast(arr, C.POINTER(C.c_double))
+    st.S_n = S_n
+    _check(load_library().del_set_layer_stats(ctx, C.byref(st)), ctx)
+
+
+def del_last_timings(ctx) -> Tuple[float, float, float]:
+    a, b, c = C.c_float(), C.c_float(), C.c_float()
+    _check(load_library().del_last_timings(ctx, C.byref(a), C.byref(b), C.byref(c)), ctx)
+    return a.value, b.value, c.value
+
+
+# ---- convenience wrapper ----------------------------------------------------------------
+def make_config(cfg, use_mfma: bool = True, max_context: Optional[int] = None) -> del_config:
+    """del_config from a synthdata.ModelConfig-like object."""
+    return del_config(cfg.n_layers, cfg.d_model, cfg.n_q_heads, cfg.n_kv_heads, cfg.head_dim,
+                      cfg.d_ffn, cfg.vocab, cfg.rope_theta, cfg.rms_eps,
+                      int(cfg.tied_embeddings),
+                      DEL_DTYPE_BF16 if cfg.weight_dtype == "bf16" else DEL_DTYPE_FP32,
+                      max_context or cfg.max_context, cfg.d_max, cfg.prefill_window, cfg.omega,
+                      int(use_mfma))
+
+
+class DelContext:
+    """RAII wrapper: create / load / prefill / round / stats through the C ABI."""
+
+    def __init__(self, cfg, use_mfma: bool = True, max_context: Optional[int] = None, stream: int = 0):
+        self.cfg = cfg
+        self.ccfg = make_config(cfg, use_mfma, max_context)
+        self.ctx = del_create(self.ccfg, stream)
+
+    def close(self) -> None:
+        if self.ctx:
+            del_destroy(self.ctx)
+            self.ctx = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+    def __enter__(self):
+        return self
+
+    def __exit__(self, *a):
+        self.close()
+
+    def load_tensor(self, layer: int, kind: str, tensor) -> None:
+        """tensor: a contiguous torch tensor on the CPU or on the GPU (pointer + shape only)."""
+        t = tensor.contiguous()
+        loc = DEL_MEM_DEVICE if t.is_cuda else DEL_MEM_HOST
+        rows, cols = (1, t.numel()) if kind.endswith("norm") else (t.shape[0], t.shape[1])
+        del_load_weights(self.ctx, [(layer, kind, t.data_ptr(), loc, rows, cols)])
+
+    def prefill(self, prompt: Sequence[int]) -> Tuple[int, int, int]:
+        return del_prefill(self.ctx, prompt)
+
+    def round(self, E: int, gamma: int) -> List[int]:
+        return del_round(self.ctx, E, gamma)
+
+    def stats(self) -> dict:
+        return del_layer_stats(self.ctx, self.cfg.n_layers, self.cfg.d_max)
+
+    def set_stats(self, S_c: Sequence[float], S_n: float) -> None:
+        del_set_layer_stats(self.ctx, S_c, S_n)
+
+    def timings(self) -> Tuple[float, float, float]:
+        return del_last_timings(self.ctx)
+
+    def hidden(self, layer: int, row: int):
+        import numpy as np
+        buf = np.empty(self.cfg.d_model, dtype=np.float32)
+        _check(load_library().del_debug_hidden(self.ctx, layer, row,
+                                               buf.ctypes.data_as(C.POINTER(C.c_float))), self.ctx)
+        return buf
+
+    def logits(self, layer: int, row: int):
+        import numpy as np
+        buf = np.empty(self.cfg.vocab, dtype=np.float32)
+        _check(load_library().del_debug_logits(self.ctx, layer, row,
+                                               buf.ctypes.data_as(C.POINTER(C.c_float))), self.ctx)
+        return buf
+
+    def state(self) -> Tuple[int, int]:
+        a, b = C.c_int32(), C.c_int32()
+        _check(load_library().del_debug_state(self.ctx, C.byref(a), C.byref(b)), self.ctx)
+        return a.value, b.value
+
+    def set_pending(self, token: int) -> None:
+        _check(load_library().del_debug_set_pending(self.ctx, token), self.ctx)
+
+    def stream_read_gbps(self, nbytes: int, iters: int = 20) -> float:
+        ms = C.c_float()
+        _check(load_library().del_bench_stream_read(self.ctx, nbytes, iters, C.byref(ms)), self.ctx)
+        return nbytes / (ms.value * 1e-3) / 1e9

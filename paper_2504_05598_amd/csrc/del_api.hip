@@ -1,0 +1,718 @@
+// Host side of the library: context, weight loading, prefill, the round driver and the DEL
+// policy (statistics + Token-per-Layer selection).  See include/del.h for the contract.
+#include <hip/hip_runtime.h>
+
+#include <algorithm>
+#include <cmath>
+#include <cstdio>
+#include <cstdlib>
+#include <cstring>
+#include <new>
+#include <string>
+#include <vector>
+
+#include "../../include/del.h"
+#include "del_kernels.h"
+
+using namespace del;
+
+namespace {
+
+// ---- DEL policy (Sections 4.1-4.3) -----------------------------------------------------
+// Decayed sums are kept as running values: S <- omega * S + a, which equals the paper's
+// S(a) = sum_i omega^(r-i-1) a[i] (newest entry has weight 1).
+struct Policy {
+  int L = 0, d_max = 0;
+  double omega = 0.95;
+  std::vector<double> Sc;  // [L+1]
+  double Sn = 0.0;
+  std::vector<double> alpha;
+  int next_E = 1, next_gamma = 0;
+
+  void reset(int L_, int d_max_, double omega_) {
+    L = L_; d_max = d_max_; omega = omega_;
+    Sc.assign(L + 1, 0.0);
+    alpha.assign(L + 1, 0.0);
+    Sn = 0.0; next_E = 1; next_gamma = 0;
+  }
+  void update(const int* c, int n) {  // c indexed by layer number 1..L
+    for (int l = 1; l <= L; ++l) Sc[l] = omega * Sc[l] + (double)c[l];
+    Sn = omega * Sn + (double)n;
+    select();
+  }
+  // alpha_l = S(c^l)/S(n) (Eq. 2 with n_r = u_r + 1 valid positions);
+  // (E, gamma) = argmax_{l in [1,L), d in [0,d_max]} TPL(l, d) (Eq. 1, Section 4.3).
+  // TPL numerator as the sum of alpha^i, i = 0..d; first maximum in l-major order wins.
+  void select() {
+    for (int l = 1; l <= L; ++l) alpha[l] = Sn > 0.0 ? Sc[l] / Sn : 0.0;
+    double best = -1.0;
+    int bl = 1, bd = 0;
+    for (int l = 1; l < L; ++l) {
+      const double a = alpha[l];
+      double num = 0.0, pw = 1.0;
+      for (int d = 0; d <= d_max; ++d) {
+        num += pw;
+        pw *= a;
+        const double v = num / (double)(d * l + L);
+        if (v > best) { best = v; bl = l; bd = d; }
+      }
+    }
+    next_E = bl; next_gamma = bd;
+  }
+};
+
+inline int ceil_div(int64_t a, int64_t b) { return (int)((a + b - 1) / b); }
+
+}  // namespace
+
+struct del_ctx {
+  del_config cfg{};
+  hipStream_t stream = nullptr;
+  std::string err;
+  // shape
+  int L = 0, d = 0, nq = 0, nkv = 0, hd = 0, f = 0, V = 0, wd = 0, esize = 0, KPL = 0, TK = 0;
+  int qdim = 0, kvdim = 0, dpad = 0, qpad = 0, fpad = 0;
+  int KTd = 0, KTq = 0, KTf = 0, NBqkv = 0, NBd = 0, NBgu = 0, NBv = 0;
+  int maxrows = 0, Tcap = 0;
+  // device memory
+  char* arena = nullptr;
+  size_t off_qkv = 0, off_o = 0, off_gu = 0, off_dn = 0, layer_stride = 0, arena_bytes = 0;
+  char* embed_t = nullptr; char* head_t = nullptr; size_t vocab_bytes = 0;
+  float* gains = nullptr;  // [L][2][gpad], then final [gpad]
+  int gpad = 0;
+  char* kc = nullptr; char* vc = nullptr; size_t kv_layer_bytes = 0;
+  float2* rope = nullptr;
+  float* hid = nullptr; float* q = nullptr; float* attn = nullptr; float* act = nullptr;
+  uint16_t* xs_layer = nullptr; uint16_t* xs_shadow = nullptr; float* rowscale = nullptr;
+  float* PM = nullptr; float* PL = nullptr; float* PA = nullptr; int nch_max = 0;
+  float* pval = nullptr; int* pidx = nullptr;
+  int* state = nullptr; int* draft_ids = nullptr; int* shadow_ids = nullptr; int* result = nullptr;
+  int* ids_dev = nullptr; int* result_host = nullptr;
+  float* logits_dbg = nullptr; float* sink = nullptr;
+  void* stage = nullptr; size_t stage_bytes = 0;
+  hipEvent_t ev[4] = {nullptr, nullptr, nullptr, nullptr};
+  // host state
+  std::vector<uint8_t> loaded;  // [(L+1)*12]
+  int phase = 0;                // 0 created, 1 prefilled
+  int T = 0, pending = -1, rounds = 0;
+  int last_rows = 0;            // valid rows of hid from the last pass
+  Policy pol;
+  int last_E = 0, last_gamma = 0, last_u = 0, last_n = 0;
+  std::vector<int> last_c, last_shadow, last_draft;
+  float t_draft = 0, t_verify = 0, t_shadow = 0;
+  int target_waves = 4096;
+
+  del_status fail(hipError_t e, const char* what) {
+    err = std::string(what) + ": " + hipGetErrorString(e);
+    return e == hipErrorOutOfMemory ? DEL_E_NOMEM : DEL_E_DEVICE;
+  }
+  float* hid_row(int layer, int row) const { return hid + ((size_t)layer * maxrows + row) * dpad; }
+  float* gain_attn(int li) const { return gains + ((size_t)li * 2) * gpad; }
+  float* gain_ffn(int li) const { return gains + ((size_t)li * 2 + 1) * gpad; }
+  float* gain_final() const { return gains + (size_t)L * 2 * gpad; }
+  bool all_loaded() const {
+    for (int l = -1; l < L; ++l)
+      for (int k = 0; k < 12; ++k) {
+        const bool global = k <= DEL_T_FINAL_NORM;
+        if ((l == -1) != global) continue;
+        if (k == DEL_T_LM_HEAD && cfg.tied_embeddings) continue;
+        if (!loaded[(size_t)(l + 1) * 12 + k]) return false;
+      }
+    return true;
+  }
+  int pick_waves(int NB, int KT) const {
+    int w = 1;
+    while (w < 16 && NB * w < target_waves) w <<= 1;
+    while (w > 1 && KT < w) w >>= 1;
+    return w;
+  }
+};
+
+#define HIPCHK(call)                                              \
+  do {                                                            \
+    hipError_t e_ = (call);                                       \
+    if (e_ != hipSuccess) return ctx->fail(e_, #call);            \
+  } while (0)
+
+namespace {
+
+template <typename T>
+hipError_t dmalloc(T** p, size_t bytes) { return hipMalloc((void**)p, bytes ? bytes : 16); }
+
+// One GEMM of the path: on the matrix cores (split the fp32 rows first) or as vector-ALU
+// groups of 8/4/2/1 rows.
+del_status gemm(del_ctx* ctx, GemmP p, int epi, int m, bool mfma) {
+  const int waves = ctx->pick_waves(p.NB, p.KT);
+  if (mfma) {
+    HIPCHK(launch_prep_split(p.X, m, m, 0, p.ldx, p.K, p.KT, p.gain, p.rms, p.eps, ctx->xs_layer, ctx->rowscale,
+                             ctx->stream));
+    p.Xs = ctx->xs_layer;
+    p.rowscale = p.rms ? ctx->rowscale : nullptr;
+    p.M = m;
+    HIPCHK(launch_gemm_mfma(p, epi, waves, 1, ctx->stream));
+    return DEL_OK;
+  }
+  int off = 0;
+  while (off < m) {
+    int g = 8;
+    while (g > m - off) g >>= 1;
+    GemmP q = p;
+    q.M = g;
+    q.X = p.X + (size_t)off * p.ldx;
+    if (q.Y) q.Y = p.Y + (size_t)off * p.ldy;
+    if (q.R) q.R = p.R + (size_t)off * p.ldr;
+    if (q.Q) q.Q = p.Q + (size_t)off * p.ldq;
+    if (q.ACT) q.ACT = p.ACT + (size_t)off * p.ldact;
+    q.row_off = p.row_off + off;
+    q.prow0 = p.prow0 + off;
+    HIPCHK(launch_gemm_valu(q, epi, waves, ctx->stream));
+    off += g;
+  }
+  return DEL_OK;
+}
+
+GemmP base_gemm(const del_ctx* ctx) {
+  GemmP p;
+  memset(&p, 0, sizeof(p));
+  p.wdtype = ctx->wd;
+  p.eps = ctx->cfg.rms_eps;
+  return p;
+}
+
+// Transformer_l on rows [row0, row0+m) of the hidden buffer; positions T + row0 + i.
+del_status run_layer(del_ctx* ctx, int l, int row0, int m) {
+  const int li = l - 1;
+  const bool mf = ctx->cfg.use_mfma && ctx->wd == DEL_DTYPE_BF16 && m > 1;
+  char* base = ctx->arena + (size_t)li * ctx->layer_stride;
+  float* hin = ctx->hid_row(l - 1, row0);
+  float* hout = ctx->hid_row(l, row0);
+  // 1. RMSNorm + fused QKV + rotary + KV append
+  GemmP p = base_gemm(ctx);
+  p.Wt = base + ctx->off_qkv; p.NB = ctx->NBqkv; p.KT = ctx->KTd; p.N = ctx->NBqkv * 16; p.K = ctx->d;
+  p.X = hin; p.ldx = ctx->dpad; p.gain = ctx->gain_attn(li); p.rms = 1;
+  p.Q = ctx->q; p.ldq = ctx->qpad;
+  p.Kc = ctx->kc + (size_t)li * ctx->kv_layer_bytes; p.Vc = ctx->vc + (size_t)li * ctx->kv_layer_bytes;
+  p.n_q = ctx->nq; p.n_kv = ctx->nkv; p.hd = ctx->hd; p.Tcap = ctx->Tcap;
+  p.state = ctx->state; p.row_off = row0; p.rope = ctx->rope;
+  del_status st = gemm(ctx, p, EPI_QKV, m, mf);
+  if (st != DEL_OK) return st;
+  // 2. attention over the cache (split over the context) + combine
+  AttnP a;
+  memset(&a, 0, sizeof(a));
+  a.Q = ctx->q; a.ldq = ctx->qpad; a.Kc = p.Kc; a.Vc = p.Vc; a.kvdtype = ctx->wd;
+  a.n_q = ctx->nq; a.n_kv = ctx->nkv; a.hd = ctx->hd; a.Tcap = ctx->Tcap; a.m = m;
+  a.state = ctx->state; a.row_off = row0;
+  a.PM = ctx->PM; a.PL = ctx->PL; a.PA = ctx->PA; a.nch_max = ctx->nch_max;
+  a.O = ctx->attn; a.ldo = ctx->qpad;
+  HIPCHK(launch_attention(a, ctx->stream));
+  // 3. output projection + residual
+  p = base_gemm(ctx);
+  p.Wt = base + ctx->off_o; p.NB = ctx->NBd; p.KT = ctx->KTq; p.N = ctx->d; p.K = ctx->qdim;
+  p.X = ctx->attn; p.ldx = ctx->qpad;
+  p.R = hin; p.ldr = ctx->dpad; p.Y = hout; p.ldy = ctx->dpad;
+  st = gemm(ctx, p, EPI_RESID, m, mf);
+  if (st != DEL_OK) return st;
+  // 4. RMSNorm + fused gate/up + SiLU(gate) * up
+  p = base_gemm(ctx);
+  p.Wt = base + ctx->off_gu; p.NB = ctx->NBgu; p.KT = ctx->KTd; p.N = ctx->NBgu * 16; p.K = ctx->d;
+  p.X = hout; p.ldx = ctx->dpad; p.gain = ctx->gain_ffn(li); p.rms = 1;
+  p.ACT = ctx->act; p.ldact = ctx->fpad; p.d_ffn = ctx->f;
+  st = gemm(ctx, p, EPI_SWIGLU, m, mf);
+  if (st != DEL_OK) return st;
+  // 5. down projection + residual (in place: this row now holds h^l)
+  p = base_gemm(ctx);
+  p.Wt = base + ctx->off_dn; p.NB = ctx->NBd; p.KT = ctx->KTf; p.N = ctx->d; p.K = ctx->f;
+  p.X = ctx->act; p.ldx = ctx->fpad;
+  p.R = hout; p.ldr = ctx->dpad; p.Y = hout; p.ldy = ctx->dpad;
+  return gemm(ctx, p, EPI_RESID, m, mf);
+}
+
+GemmP head_gemm(const del_ctx* ctx) {
+  GemmP p = base_gemm(ctx);
+  p.Wt = ctx->head_t; p.NB = ctx->NBv; p.KT = ctx->KTd; p.N = ctx->V; p.K = ctx->d;
+  p.ldx = ctx->dpad; p.gain = ctx->gain_final(); p.rms = 1;
+  p.pval = ctx->pval; p.pidx = ctx->pidx;
+  return p;
+}
+
+// Final norm + LM head + arg-max on one row of the hidden buffer (the draft's head).
+del_status head_one(del_ctx* ctx, int layer, int row, int* out_id) {
+  GemmP p = head_gemm(ctx);
+  p.X = ctx->hid_row(layer, row);
+  del_status st = gemm(ctx, p, EPI_ARGMAX, 1, false);
+  if (st != DEL_OK) return st;
+  HIPCHK(launch_argmax_finish(ctx->pval, ctx->pidx, 1, ctx->NBv, out_id, ctx->stream));
+  return DEL_OK;
+}
+
+// Shadow tokens (Section 4.2): final norm + LM head + arg-max of rows 0..m-1 of every layer
+// 1..L, into shadow_ids[(l-1)*m + i].
+del_status shadow_head(del_ctx* ctx, int m) {
+  const int R = ctx->L * m;
+  const bool mf = ctx->cfg.use_mfma && ctx->wd == DEL_DTYPE_BF16;
+  if (mf) {
+    HIPCHK(launch_prep_split(ctx->hid_row(1, 0), R, m, (int64_t)ctx->maxrows * ctx->dpad, ctx->dpad, ctx->d,
+                             ctx->KTd, ctx->gain_final(), 1, ctx->cfg.rms_eps, ctx->xs_shadow, ctx->rowscale,
+                             ctx->stream));
+    GemmP p = head_gemm(ctx);
+    p.Xs = ctx->xs_shadow; p.rowscale = ctx->rowscale; p.M = R;
+    HIPCHK(launch_gemm_mfma(p, EPI_ARGMAX, ctx->pick_waves(p.NB * ceil_div(R, 16), p.KT), ceil_div(R, 16),
+                            ctx->stream));
+  } else {
+    for (int l = 1; l <= ctx->L; ++l) {
+      GemmP p = head_gemm(ctx);
+      p.X = ctx->hid_row(l, 0);
+      p.prow0 = (l - 1) * m;
+      del_status st = gemm(ctx, p, EPI_ARGMAX, m, false);
+      if (st != DEL_OK) return st;
+    }
+  }
+  HIPCHK(launch_argmax_finish(ctx->pval, ctx->pidx, R, ctx->NBv, ctx->shadow_ids, ctx->stream));
+  return DEL_OK;
+}
+
+void free_all(del_ctx* c) {
+  void* ptrs[] = {c->arena, c->embed_t, (c->head_t != c->embed_t) ? c->head_t : nullptr, c->gains, c->kc, c->vc,
+                  c->rope, c->hid, c->q, c->attn, c->act, c->xs_layer, c->xs_shadow, c->rowscale, c->PM, c->PL,
+                  c->PA, c->pval, c->pidx, c->state, c->draft_ids, c->shadow_ids, c->result, c->ids_dev,
+                  c->logits_dbg, c->sink, c->stage};
+  for (void* p : ptrs)
+    if (p) (void)hipFree(p);
+  if (c->result_host) (void)hipHostFree(c->result_host);
+  for (auto& e : c->ev)
+    if (e) (void)hipEventDestroy(e);
+}
+
+}  // namespace
+
+extern "C" {
+
+const char* del_strerror(del_status s) {
+  switch (s) {
+    case DEL_OK: return "ok";
+    case DEL_E_ARG: return "invalid argument";
+    case DEL_E_STATE: return "call out of order";
+    case DEL_E_CAPACITY: return "KV cache capacity exceeded";
+    case DEL_E_SHAPE: return "tensor shape does not match the configuration";
+    case DEL_E_DEVICE: return "HIP error";
+    case DEL_E_NOMEM: return "out of memory";
+  }
+  return "unknown status";
+}
+
+const char* del_last_error_text(const del_ctx* ctx) { return ctx ? ctx->err.c_str() : ""; }
+
+del_status del_create(const del_config* cfg, void* hip_stream, del_ctx** out) {
+  if (!cfg || !out) return DEL_E_ARG;
+  *out = nullptr;
+  if (cfg->n_layers < 1 || cfg->d_model < 1 || cfg->n_q_heads < 1 || cfg->n_kv_heads < 1 ||
+      cfg->n_q_heads % cfg->n_kv_heads != 0 || cfg->head_dim < 16 || cfg->head_dim > 128 ||
+      cfg->head_dim % 16 != 0 || cfg->d_ffn < 8 || cfg->d_ffn % 8 != 0 || cfg->vocab < 2 ||
+      (cfg->weight_dtype != DEL_DTYPE_FP32 && cfg->weight_dtype != DEL_DTYPE_BF16) || cfg->max_context < 2 ||
+      cfg->d_max < 0 || cfg->d_max > 63 || cfg->prefill_window < 1 || !(cfg->omega >= 0.0 && cfg->omega <= 1.0) ||
+      !(cfg->rope_theta > 0.f) || !(cfg->rms_eps >= 0.f))
+    return DEL_E_ARG;
+  del_ctx* ctx = new (std::nothrow) del_ctx();
+  if (!ctx) return DEL_E_NOMEM;
+  ctx->cfg = *cfg;
+  ctx->stream = (hipStream_t)hip_stream;
+  ctx->L = cfg->n_layers; ctx->d = cfg->d_model; ctx->nq = cfg->n_q_heads; ctx->nkv = cfg->n_kv_heads;
+  ctx->hd = cfg->head_dim; ctx->f = cfg->d_ffn; ctx->V = cfg->vocab; ctx->wd = cfg->weight_dtype;
+  ctx->esize = ctx->wd == DEL_DTYPE_BF16 ? 2 : 4;
+  ctx->KPL = kpl_of(ctx->wd); ctx->TK = tk_of(ctx->wd);
+  ctx->qdim = ctx->nq * ctx->hd; ctx->kvdim = ctx->nkv * ctx->hd;
+  ctx->KTd = ceil_div(ctx->d, ctx->TK); ctx->KTq = ceil_div(ctx->qdim, ctx->TK); ctx->KTf = ceil_div(ctx->f, ctx->TK);
+  // activation rows are padded to 32 floats so that either tile width reads whole tiles
+  ctx->dpad = ceil_div(ctx->d, 32) * 32; ctx->qpad = ceil_div(ctx->qdim, 32) * 32; ctx->fpad = ceil_div(ctx->f, 32) * 32;
+  ctx->NBqkv = (ctx->qdim + 2 * ctx->kvdim) / 16;
+  ctx->NBd = ceil_div(ctx->d, 16);
+  ctx->NBgu = ceil_div(ctx->f, 8);
+  ctx->NBv = ceil_div(ctx->V, 16);
+  ctx->maxrows = std::max(16, cfg->d_max + 1);
+  ctx->Tcap = cfg->max_context;
+  ctx->gpad = std::max(ctx->dpad, std::max(ctx->qpad, ctx->fpad));
+  ctx->loaded.assign((size_t)(ctx->L + 1) * 12, 0);
+  ctx->pol.reset(ctx->L, cfg->d_max, cfg->omega);
+  ctx->last_c.assign(ctx->L + 1, 0);
+  ctx->last_shadow.assign((size_t)(ctx->L + 1) * (cfg->d_max + 1), 0);
+  ctx->last_draft.assign(std::max(1, cfg->d_max), 0);
+  if (const char* tw = getenv("DEL_TARGET_WAVES")) {
+    const int v = atoi(tw);
+    if (v >= 64 && v <= 65536) ctx->target_waves = v;
+  }
+
+  const size_t tile = 1024;
+  auto al = [](size_t x) { return (x + 4095) & ~(size_t)4095; };
+  ctx->off_qkv = 0;
+  ctx->off_o = al(ctx->off_qkv + (size_t)ctx->NBqkv * ctx->KTd * tile);
+  ctx->off_gu = al(ctx->off_o + (size_t)ctx->NBd * ctx->KTq * tile);
+  ctx->off_dn = al(ctx->off_gu + (size_t)ctx->NBgu * ctx->KTd * tile);
+  ctx->layer_stride = al(ctx->off_dn + (size_t)ctx->NBd * ctx->KTf * tile);
+  ctx->arena_bytes = ctx->layer_stride * ctx->L;
+  ctx->vocab_bytes = (size_t)ctx->NBv * ctx->KTd * tile;
+  ctx->kv_layer_bytes = (size_t)ctx->nkv * ctx->Tcap * ctx->hd * ctx->esize;
+  ctx->nch_max = ceil_div(ctx->Tcap, ATTN_CT);
+  const int Rmax = ctx->L * ctx->maxrows;
+  const int KTmax = std::max(ctx->KTd, std::max(ctx->KTq, ctx->KTf));
+
+#define CK(call)                                                     \
+  do {                                                               \
+    hipError_t e_ = (call);                                          \
+    if (e_ != hipSuccess) {                                          \
+      del_status st_ = ctx->fail(e_, #call);                         \
+      fprintf(stderr, "del_create: %s\n", ctx->err.c_str());         \
+      free_all(ctx);                                                 \
+      delete ctx;                                                    \
+      return st_;                                                    \
+    }                                                                \
+  } while (0)
+  CK(dmalloc(&ctx->arena, ctx->arena_bytes));
+  CK(hipMemsetAsync(ctx->arena, 0, ctx->arena_bytes, ctx->stream));
+  CK(dmalloc(&ctx->embed_t, ctx->vocab_bytes));
+  CK(hipMemsetAsync(ctx->embed_t, 0, ctx->vocab_bytes, ctx->stream));
+  if (cfg->tied_embeddings) {
+    ctx->head_t = ctx->embed_t;
+  } else {
+    CK(dmalloc(&ctx->head_t, ctx->vocab_bytes));
+    CK(hipMemsetAsync(ctx->head_t, 0, ctx->vocab_bytes, ctx->stream));
+  }
+  const size_t gains_bytes = ((size_t)ctx->L * 2 + 1) * ctx->gpad * sizeof(float);
+  CK(dmalloc(&ctx->gains, gains_bytes));
+  CK(hipMemsetAsync(ctx->gains, 0, gains_bytes, ctx->stream));
+  CK(dmalloc(&ctx->kc, ctx->kv_layer_bytes * ctx->L));
+  CK(dmalloc(&ctx->vc, ctx->kv_layer_bytes * ctx->L));
+  CK(hipMemsetAsync(ctx->kc, 0, ctx->kv_layer_bytes * ctx->L, ctx->stream));
+  CK(hipMemsetAsync(ctx->vc, 0, ctx->kv_layer_bytes * ctx->L, ctx->stream));
+  {  // rotary table in double precision on the host: angle(p, j) = p * theta^(-2j/hd)
+    const int half = ctx->hd / 2;
+    std::vector<float2> tab((size_t)ctx->Tcap * half);
+    for (int j = 0; j < half; ++j) {
+      const double inv = std::pow((double)cfg->rope_theta, -2.0 * j / ctx->hd);
+      for (int p = 0; p < ctx->Tcap; ++p) {
+        const double a = (double)p * inv;
+        tab[(size_t)p * half + j] = make_float2((float)std::cos(a), (float)std::sin(a));
+      }
+    }
+    CK(dmalloc(&ctx->rope, tab.size() * sizeof(float2)));
+    CK(hipMemcpy(ctx->rope, tab.data(), tab.size() * sizeof(float2), hipMemcpyHostToDevice));
+  }
+  const size_t hid_bytes = (size_t)(ctx->L + 1) * ctx->maxrows * ctx->dpad * sizeof(float);
+  CK(dmalloc(&ctx->hid, hid_bytes));
+  CK(hipMemsetAsync(ctx->hid, 0, hid_bytes, ctx->stream));
+  CK(dmalloc(&ctx->q, (size_t)ctx->maxrows * ctx->qpad * 4));
+  CK(dmalloc(&ctx->attn, (size_t)ctx->maxrows * ctx->qpad * 4));
+  CK(dmalloc(&ctx->act, (size_t)ctx->maxrows * ctx->fpad * 4));
+  CK(hipMemsetAsync(ctx->q, 0, (size_t)ctx->maxrows * ctx->qpad * 4, ctx->stream));
+  CK(hipMemsetAsync(ctx->attn, 0, (size_t)ctx->maxrows * ctx->qpad * 4, ctx->stream));
+  CK(hipMemsetAsync(ctx->act, 0, (size_t)ctx->maxrows * ctx->fpad * 4, ctx->stream));
+  CK(dmalloc(&ctx->xs_layer, (size_t)KTmax * 2048));
+  CK(hipMemsetAsync(ctx->xs_layer, 0, (size_t)KTmax * 2048, ctx->stream));
+  const size_t xs_sh = (size_t)ceil_div(Rmax, 16) * ctx->KTd * 2048;
+  CK(dmalloc(&ctx->xs_shadow, xs_sh));
+  CK(hipMemsetAsync(ctx->xs_shadow, 0, xs_sh, ctx->stream));
+  CK(dmalloc(&ctx->rowscale, (size_t)(Rmax + 16) * 4));
+  const size_t prow = (size_t)ctx->maxrows * ctx->nq * ctx->nch_max;
+  CK(dmalloc(&ctx->PM, prow * 4));
+  CK(dmalloc(&ctx->PL, prow * 4));
+  CK(dmalloc(&ctx->PA, prow * ctx->hd * 4));
+  CK(dmalloc(&ctx->pval, (size_t)Rmax * ctx->NBv * 4));
+  CK(dmalloc(&ctx->pidx, (size_t)Rmax * ctx->NBv * 4));
+  CK(dmalloc(&ctx->state, 16));
+  CK(hipMemsetAsync(ctx->state, 0, 16, ctx->stream));
+  CK(dmalloc(&ctx->draft_ids, (size_t)(cfg->d_max + 1) * 4));
+  CK(dmalloc(&ctx->shadow_ids, (size_t)Rmax * 4));
+  CK(dmalloc(&ctx->result, (size_t)(3 + cfg->d_max + 1 + Rmax) * 4));
+  CK(dmalloc(&ctx->ids_dev, (size_t)ctx->Tcap * 4));
+  CK(hipHostMalloc((void**)&ctx->result_host, (size_t)(3 + cfg->d_max + 1 + Rmax) * 4, hipHostMallocDefault));
+  CK(dmalloc(&ctx->logits_dbg, (size_t)ctx->NBv * 16 * 4));
+  CK(dmalloc(&ctx->sink, 16));
+  for (auto& e : ctx->ev) CK(hipEventCreate(&e));
+  CK(hipStreamSynchronize(ctx->stream));
+#undef CK
+  *out = ctx;
+  return DEL_OK;
+}
+
+void del_destroy(del_ctx* ctx) {
+  if (!ctx) return;
+  (void)hipStreamSynchronize(ctx->stream);
+  free_all(ctx);
+  delete ctx;
+}
+
+del_status del_load_weights(del_ctx* ctx, const del_tensor* tensors, int32_t n) {
+  if (!ctx || (!tensors && n > 0) || n < 0) return DEL_E_ARG;
+  for (int i = 0; i < n; ++i) {
+    const del_tensor& t = tensors[i];
+    if (!t.data || t.kind < 0 || t.kind > DEL_T_WD) return DEL_E_ARG;
+    if (t.location != DEL_MEM_HOST && t.location != DEL_MEM_DEVICE) return DEL_E_ARG;
+    const bool global = t.kind <= DEL_T_FINAL_NORM;
+    if (global ? t.layer != -1 : (t.layer < 0 || t.layer >= ctx->L)) return DEL_E_ARG;
+    if (t.kind == DEL_T_LM_HEAD && ctx->cfg.tied_embeddings) return DEL_E_ARG;
+    int64_t rows = 0, cols = 0;
+    char* dst = nullptr;
+    int KT = 0, map = MAP_PLAIN, vbase = 0;
+    char* lbase = global ? nullptr : ctx->arena + (size_t)t.layer * ctx->layer_stride;
+    switch (t.kind) {
+      case DEL_T_EMBED: rows = ctx->V; cols = ctx->d; dst = ctx->embed_t; KT = ctx->KTd; break;
+      case DEL_T_LM_HEAD: rows = ctx->V; cols = ctx->d; dst = ctx->head_t; KT = ctx->KTd; break;
+      case DEL_T_FINAL_NORM: case DEL_T_ATTN_NORM: case DEL_T_FFN_NORM: rows = 1; cols = ctx->d; break;
+      case DEL_T_WQ: rows = ctx->qdim; cols = ctx->d; dst = lbase + ctx->off_qkv; KT = ctx->KTd; map = MAP_ROPE; break;
+      case DEL_T_WK: rows = ctx->kvdim; cols = ctx->d; dst = lbase + ctx->off_qkv; KT = ctx->KTd; map = MAP_ROPE;
+        vbase = ctx->qdim; break;
+      case DEL_T_WV: rows = ctx->kvdim; cols = ctx->d; dst = lbase + ctx->off_qkv; KT = ctx->KTd;
+        vbase = ctx->qdim + ctx->kvdim; break;
+      case DEL_T_WO: rows = ctx->d; cols = ctx->qdim; dst = lbase + ctx->off_o; KT = ctx->KTq; break;
+      case DEL_T_WG: rows = ctx->f; cols = ctx->d; dst = lbase + ctx->off_gu; KT = ctx->KTd; map = MAP_GATE; break;
+      case DEL_T_WU: rows = ctx->f; cols = ctx->d; dst = lbase + ctx->off_gu; KT = ctx->KTd; map = MAP_UP; break;
+      case DEL_T_WD: rows = ctx->d; cols = ctx->f; dst = lbase + ctx->off_dn; KT = ctx->KTf; break;
+    }
+    if (t.rows != rows || t.cols != cols) return DEL_E_SHAPE;
+    const bool is_gain = dst == nullptr;
+    const size_t es = is_gain ? 4 : (size_t)ctx->esize;
+    const size_t row_bytes = (size_t)cols * es;
+    // rows per staged piece: at most 256 MiB of host data in flight on the device
+    const int64_t piece = std::max<int64_t>(1, (int64_t)((256ull << 20) / row_bytes));
+    for (int64_t r0 = 0; r0 < rows; r0 += piece) {
+      const int64_t nr = std::min<int64_t>(piece, rows - r0);
+      const char* src = (const char*)t.data + (size_t)r0 * row_bytes;
+      if (t.location == DEL_MEM_HOST) {
+        const size_t need = (size_t)nr * row_bytes;
+        if (need > ctx->stage_bytes) {
+          if (ctx->stage) (void)hipFree(ctx->stage);
+          ctx->stage = nullptr; ctx->stage_bytes = 0;
+          HIPCHK(hipMalloc(&ctx->stage, need));
+          ctx->stage_bytes = need;
+        }
+        HIPCHK(hipMemcpyAsync(ctx->stage, src, need, hipMemcpyHostToDevice, ctx->stream));
+        src = (const char*)ctx->stage;
+      }
+      if (is_gain) {
+        float* g = t.kind == DEL_T_FINAL_NORM ? ctx->gain_final()
+                   : t.kind == DEL_T_ATTN_NORM ? ctx->gain_attn(t.layer) : ctx->gain_ffn(t.layer);
+        HIPCHK(launch_pad_gain((const float*)src, ctx->d, g, ctx->gpad, ctx->stream));
+      } else {
+        HIPCHK(launch_tile_scatter(src, ctx->wd, r0, nr, cols, map, vbase, ctx->hd, dst, KT, ctx->stream));
+      }
+      // the staging buffer (or the caller's buffer) is reused right after this call
+      HIPCHK(hipStreamSynchronize(ctx->stream));
+    }
+    ctx->loaded[(size_t)(t.layer + 1) * 12 + t.kind] = 1;
+  }
+  if (ctx->stage && ctx->all_loaded()) {
+    (void)hipFree(ctx->stage);
+    ctx->stage = nullptr; ctx->stage_bytes = 0;
+  }
+  return DEL_OK;
+}
+
+del_status del_prefill(del_ctx* ctx, const int32_t* prompt, int32_t n_prompt, int32_t* first_token, int32_t* next_E,
+                       int32_t* next_gamma) {
+  if (!ctx || !prompt || !first_token || !next_E || !next_gamma || n_prompt < 1) return DEL_E_ARG;
+  if (!ctx->all_loaded()) return DEL_E_STATE;
+  if (n_prompt + 1 > ctx->Tcap) return DEL_E_CAPACITY;
+  for (int i = 0; i < n_prompt; ++i)
+    if (prompt[i] < 0 || prompt[i] >= ctx->V) return DEL_E_ARG;
+  const int L = ctx->L, P = n_prompt;
+  ctx->phase = 0;
+  ctx->pol.reset(L, ctx->cfg.d_max, ctx->cfg.omega);
+  ctx->rounds = 0;
+  HIPCHK(hipMemcpyAsync(ctx->ids_dev, prompt, (size_t)P * 4, hipMemcpyHostToDevice, ctx->stream));
+  HIPCHK(launch_set_state(ctx->state, 0, 0, nullptr, -1, ctx->stream));
+  const int w = std::min(ctx->cfg.prefill_window, P);
+  std::vector<int> shadow((size_t)L * w, 0);  // [l-1][window position]
+  // chunks of up to 16 rows; a ragged chunk, if any, comes first so the last ones are full
+  const int CH = 16;
+  int start = 0;
+  while (start < P) {
+    const int mc = (start == 0 && P % CH != 0) ? P % CH : CH;
+    HIPCHK(launch_embed(ctx->embed_t, ctx->wd, ctx->KTd, ctx->V, ctx->ids_dev + start, mc, ctx->hid_row(0, 0),
+                        ctx->dpad, ctx->d, ctx->stream));
+    for (int l = 1; l <= L; ++l) {
+      del_status st = run_layer(ctx, l, 0, mc);
+      if (st != DEL_OK) return st;
+    }
+    if (start + mc > P - w) {  // overlaps the statistics window
+      del_status st = shadow_head(ctx, mc);
+      if (st != DEL_OK) return st;
+      HIPCHK(hipMemcpyAsync(ctx->result_host, ctx->shadow_ids, (size_t)L * mc * 4, hipMemcpyDeviceToHost,
+                            ctx->stream));
+      HIPCHK(hipStreamSynchronize(ctx->stream));
+      for (int i = 0; i < mc; ++i) {
+        const int pos = start + i;
+        if (pos < P - w) continue;
+        for (int l = 1; l <= L; ++l) shadow[(size_t)(l - 1) * w + (pos - (P - w))] = ctx->result_host[(l - 1) * mc + i];
+      }
+    }
+    HIPCHK(launch_set_state(ctx->state, mc, -1, nullptr, -1, ctx->stream));
+    ctx->last_rows = mc;
+    start += mc;
+  }
+  // pseudo-round over the window: every layer's shadow token against layer L's
+  std::vector<int> c(L + 1, 0);
+  for (int l = 1; l <= L; ++l)
+    for (int i = 0; i < w; ++i) c[l] += shadow[(size_t)(l - 1) * w + i] == shadow[(size_t)(L - 1) * w + i];
+  ctx->pol.update(c.data(), w);
+  const int first = shadow[(size_t)(L - 1) * w + (w - 1)];
+  HIPCHK(launch_set_state(ctx->state, 0, -1, nullptr, first, ctx->stream));
+  HIPCHK(hipStreamSynchronize(ctx->stream));
+  ctx->T = P; ctx->pending = first; ctx->phase = 1;
+  ctx->last_c = c; ctx->last_E = 0; ctx->last_gamma = 0; ctx->last_u = w - 1; ctx->last_n = w;
+  *first_token = first; *next_E = ctx->pol.next_E; *next_gamma = ctx->pol.next_gamma;
+  return DEL_OK;
+}
+
+del_status del_round(del_ctx* ctx, int32_t E, int32_t gamma, int32_t* out_tokens, int32_t* n_out) {
+  if (!ctx || !out_tokens || !n_out) return DEL_E_ARG;
+  if (ctx->phase != 1) return DEL_E_STATE;
+  const int L = ctx->L;
+  if (E < 1 || E > L || gamma < 0 || gamma > ctx->cfg.d_max) return DEL_E_ARG;
+  if (ctx->T + gamma + 1 > ctx->Tcap) return DEL_E_CAPACITY;
+  const int m = gamma + 1;
+  hipStream_t s = ctx->stream;
+  HIPCHK(hipEventRecord(ctx->ev[0], s));
+  // ---- draft: gamma auto-regressive steps through layers 1..E + head
+  for (int i = 0; i <= gamma; ++i) {
+    const int* tok = i == 0 ? ctx->state + 1 : ctx->draft_ids + (i - 1);
+    HIPCHK(launch_embed(ctx->embed_t, ctx->wd, ctx->KTd, ctx->V, tok, 1, ctx->hid_row(0, i), ctx->dpad, ctx->d, s));
+    for (int l = 1; l <= E; ++l) {
+      del_status st = run_layer(ctx, l, i, 1);
+      if (st != DEL_OK) return st;
+    }
+    if (i < gamma) {  // the last pending token needs no head: only its exit state and KV
+      del_status st = head_one(ctx, E, i, ctx->draft_ids + i);
+      if (st != DEL_OK) return st;
+    }
+  }
+  HIPCHK(hipEventRecord(ctx->ev[1], s));
+  // ---- verify: the gamma+1 exit states through layers E+1..L
+  for (int l = E + 1; l <= L; ++l) {
+    del_status st = run_layer(ctx, l, 0, m);
+    if (st != DEL_OK) return st;
+  }
+  HIPCHK(hipEventRecord(ctx->ev[2], s));
+  // ---- shadow tokens of every layer (row L = the target's tokens), acceptance on device
+  {
+    del_status st = shadow_head(ctx, m);
+    if (st != DEL_OK) return st;
+  }
+  HIPCHK(launch_accept(ctx->state, ctx->draft_ids, ctx->shadow_ids, L, m, E, gamma, ctx->result, s));
+  HIPCHK(hipEventRecord(ctx->ev[3], s));
+  const size_t nres = (size_t)3 + gamma + (size_t)L * m;
+  HIPCHK(hipMemcpyAsync(ctx->result_host, ctx->result, nres * 4, hipMemcpyDeviceToHost, s));
+  HIPCHK(hipStreamSynchronize(s));
+  (void)hipEventElapsedTime(&ctx->t_draft, ctx->ev[0], ctx->ev[1]);
+  (void)hipEventElapsedTime(&ctx->t_verify, ctx->ev[1], ctx->ev[2]);
+  (void)hipEventElapsedTime(&ctx->t_shadow, ctx->ev[2], ctx->ev[3]);
+  const int* res = ctx->result_host;
+  const int u = res[0];
+  const int* drafts = res + 3;
+  const int* sh = res + 3 + gamma;  // [L][m]
+  const int* target = sh + (size_t)(L - 1) * m;
+  // ---- statistics (Section 4.2): c^l over the valid positions 0..u, n = u + 1
+  std::vector<int> c(L + 1, 0);
+  for (int l = 1; l <= L; ++l)
+    for (int i = 0; i <= u; ++i) c[l] += sh[(size_t)(l - 1) * m + i] == target[i];
+  ctx->pol.update(c.data(), u + 1);
+  for (int i = 0; i <= u; ++i) out_tokens[i] = target[i];
+  *n_out = u + 1;
+  ctx->T = res[1]; ctx->pending = res[2];
+  ctx->rounds += 1; ctx->last_rows = m;
+  ctx->last_c = c; ctx->last_E = E; ctx->last_gamma = gamma; ctx->last_u = u; ctx->last_n = u + 1;
+  const int stride = ctx->cfg.d_max + 1;
+  std::fill(ctx->last_shadow.begin(), ctx->last_shadow.end(), 0);
+  for (int l = 1; l <= L; ++l)
+    for (int i = 0; i < m; ++i) ctx->last_shadow[(size_t)l * stride + i] = sh[(size_t)(l - 1) * m + i];
+  for (int i = 0; i < gamma; ++i) ctx->last_draft[i] = drafts[i];
+  return DEL_OK;
+}
+
+del_status del_layer_stats(const del_ctx* ctx, del_stats* out) {
+  if (!ctx || !out) return DEL_E_ARG;
+  const int L = ctx->L;
+  out->n_layers = L; out->rounds = ctx->rounds;
+  out->next_E = ctx->pol.next_E; out->next_gamma = ctx->pol.next_gamma;
+  out->last_E = ctx->last_E; out->last_gamma = ctx->last_gamma; out->last_u = ctx->last_u; out->last_n = ctx->last_n;
+  out->S_n = ctx->pol.Sn;
+  for (int l = 0; l <= L; ++l) {
+    if (out->S_c) out->S_c[l] = ctx->pol.Sc[l];
+    if (out->alpha) out->alpha[l] = ctx->pol.alpha[l];
+    if (out->last_c) out->last_c[l] = ctx->last_c[l];
+  }
+  if (out->last_shadow) memcpy(out->last_shadow, ctx->last_shadow.data(), ctx->last_shadow.size() * 4);
+  if (out->last_draft)
+    for (int i = 0; i < ctx->cfg.d_max; ++i) out->last_draft[i] = ctx->last_draft[i];
+  return DEL_OK;
+}
+
+del_status del_set_layer_stats(del_ctx* ctx, const del_stats* in) {
+  if (!ctx || !in || !in->S_c) return DEL_E_ARG;
+  if (!(in->S_n > 0.0)) return DEL_E_ARG;
+  for (int l = 1; l <= ctx->L; ++l)
+    if (!(in->S_c[l] >= 0.0)) return DEL_E_ARG;
+  for (int l = 1; l <= ctx->L; ++l) ctx->pol.Sc[l] = in->S_c[l];
+  ctx->pol.Sn = in->S_n;
+  ctx->pol.select();
+  return DEL_OK;
+}
+
+del_status del_last_timings(const del_ctx* ctx, float* draft_ms, float* verify_ms, float* shadow_ms) {
+  if (!ctx) return DEL_E_ARG;
+  if (draft_ms) *draft_ms = ctx->t_draft;
+  if (verify_ms) *verify_ms = ctx->t_verify;
+  if (shadow_ms) *shadow_ms = ctx->t_shadow;
+  return DEL_OK;
+}
+
+del_status del_debug_hidden(const del_ctx* c, int32_t layer, int32_t row, float* dst) {
+  del_ctx* ctx = const_cast<del_ctx*>(c);
+  if (!ctx || !dst || layer < 0 || layer > ctx->L || row < 0 || row >= ctx->maxrows) return DEL_E_ARG;
+  HIPCHK(hipStreamSynchronize(ctx->stream));
+  HIPCHK(hipMemcpy(dst, ctx->hid_row(layer, row), (size_t)ctx->d * 4, hipMemcpyDeviceToHost));
+  return DEL_OK;
+}
+
+del_status del_debug_logits(del_ctx* ctx, int32_t layer, int32_t row, float* dst) {
+  if (!ctx || !dst || layer < 0 || layer > ctx->L || row < 0 || row >= ctx->maxrows) return DEL_E_ARG;
+  if (!ctx->all_loaded()) return DEL_E_STATE;
+  GemmP p = head_gemm(ctx);
+  p.X = ctx->hid_row(layer, row);
+  p.Y = ctx->logits_dbg; p.ldy = ctx->NBv * 16;
+  del_status st = gemm(ctx, p, EPI_STORE, 1, false);
+  if (st != DEL_OK) return st;
+  HIPCHK(hipStreamSynchronize(ctx->stream));
+  HIPCHK(hipMemcpy(dst, ctx->logits_dbg, (size_t)ctx->V * 4, hipMemcpyDeviceToHost));
+  return DEL_OK;
+}
+
+del_status del_debug_state(const del_ctx* ctx, int32_t* kv_len, int32_t* pending_token) {
+  if (!ctx) return DEL_E_ARG;
+  if (kv_len) *kv_len = ctx->T;
+  if (pending_token) *pending_token = ctx->pending;
+  return DEL_OK;
+}
+
+del_status del_debug_set_pending(del_ctx* ctx, int32_t token) {
+  if (!ctx || token < 0 || token >= ctx->V) return DEL_E_ARG;
+  if (ctx->phase != 1) return DEL_E_STATE;
+  HIPCHK(launch_set_state(ctx->state, 0, -1, nullptr, token, ctx->stream));
+  HIPCHK(hipStreamSynchronize(ctx->stream));
+  ctx->pending = token;
+  return DEL_OK;
+}
+
+del_status del_bench_stream_read(del_ctx* ctx, int64_t bytes, int32_t iters, float* ms_per_iter) {
+  if (!ctx || !ms_per_iter || iters < 1 || bytes < 1024) return DEL_E_ARG;
+  if ((size_t)bytes > ctx->arena_bytes) bytes = (int64_t)ctx->arena_bytes;
+  HIPCHK(launch_stream_read(ctx->arena, bytes, ctx->sink, ctx->stream));  // warm-up
+  HIPCHK(hipEventRecord(ctx->ev[0], ctx->stream));
+  for (int i = 0; i < iters; ++i) HIPCHK(launch_stream_read(ctx->arena, bytes, ctx->sink, ctx->stream));
+  HIPCHK(hipEventRecord(ctx->ev[1], ctx->stream));
+  HIPCHK(hipStreamSynchronize(ctx->stream));
+  float ms = 0.f;
+  HIPCHK(hipEventElapsedTime(&ms, ctx->ev[0], ctx->ev[1]));
+  *ms_per_iter = ms / iters;
+  return DEL_OK;
+}
+
+}  // extern "C"

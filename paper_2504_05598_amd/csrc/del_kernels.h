@@ -1,0 +1,89 @@
+// Internal launcher interface between the host state machine (del_api.hip) and the
+// gfx950 kernels (del_kernels.hip).  Not part of the public ABI.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace del {
+
+// ---- weight tiling -------------------------------------------------------------------
+// A matrix [N, K] is stored as tiles of 16 rows x TK input features, 1 KiB each, in the
+// order a 64-lane wavefront consumes them: lane l of tile (nb, kt) holds the KPL
+// consecutive elements W[row(nb, l%16)][kt*TK + (l/16)*KPL ...].  bf16: KPL=8, TK=32 (this is
+// also the A-operand layout of v_mfma_f32_16x16x32_bf16); fp32: KPL=4, TK=16.
+// Rows and K are zero-padded to full tiles.
+inline int kpl_of(int dtype) { return dtype == 1 ? 8 : 4; }
+inline int tk_of(int dtype) { return 4 * kpl_of(dtype); }
+
+// Row maps applied while tiling: which "virtual" row of the fused matrix a source row lands on.
+enum RowMap {
+  MAP_PLAIN = 0,  // v = base + n
+  MAP_ROPE = 1,   // per head: strip t holds j = 8t..8t+7 (rows 0-7) and j + hd/2 (rows 8-15)
+  MAP_GATE = 2,   // v = (n/8)*16 + n%8
+  MAP_UP = 3      // v = (n/8)*16 + 8 + n%8
+};
+
+enum Epi { EPI_STORE = 0, EPI_RESID = 1, EPI_QKV = 2, EPI_SWIGLU = 3, EPI_ARGMAX = 4 };
+
+struct GemmP {
+  // weights
+  const void* Wt;  // tiled
+  int NB, KT;      // 16-row blocks, k tiles
+  int N, K;        // valid rows / input features
+  int wdtype;      // 0 fp32, 1 bf16
+  // activations, vector-ALU path: fp32 rows [M][ldx]; optional gain [KT*TK]; optional RMS norm
+  const float* X;
+  int ldx, M;
+  const float* gain;
+  int rms;
+  float eps;
+  // activations, matrix-core path: hi/lo bf16 split tiles, per-row scale (nullable)
+  const uint16_t* Xs;
+  const float* rowscale;
+  // epilogue
+  float* Y; int ldy;            // STORE / RESID destination (first row of this call)
+  const float* R; int ldr;      // RESID: residual source
+  float* Q; int ldq;            // QKV: rotated queries [M][n_q*hd]
+  void* Kc; void* Vc;           // QKV: this layer's caches [n_kv][Tcap][hd] (weight dtype)
+  int n_q, n_kv, hd, Tcap;
+  const int* state;             // state[0] = KV length T
+  int row_off;                  // position of row mi is state[0] + row_off + mi
+  const float2* rope;           // [Tcap][hd/2] (cos, sin)
+  float* ACT; int ldact; int d_ffn;  // SWIGLU
+  float* pval; int* pidx;       // ARGMAX partials [rows][NB]
+  int prow0;                    // first partial row of this call
+};
+
+struct AttnP {
+  const float* Q; int ldq;      // [m][n_q*hd]
+  const void* Kc; const void* Vc;  // this layer's caches
+  int kvdtype;
+  int n_q, n_kv, hd, Tcap, m;
+  const int* state; int row_off;
+  float* PM; float* PL; float* PA;  // partials [(mi*n_q+h)][nch_max] (+[hd])
+  int nch_max;
+  float* O; int ldo;            // combined output [m][n_q*hd]
+};
+
+hipError_t launch_gemm_valu(const GemmP& p, int epi, int waves, hipStream_t s);
+hipError_t launch_gemm_mfma(const GemmP& p, int epi, int waves, int col_blocks, hipStream_t s);
+hipError_t launch_prep_split(const float* src, int rows, int rows_per_group, int64_t group_stride,
+                             int ld, int K, int KT, const float* gain, int rms, float eps,
+                             uint16_t* Xs, float* rowscale, hipStream_t s);
+hipError_t launch_attention(const AttnP& p, hipStream_t s);
+hipError_t launch_embed(const void* Et, int wdtype, int KT, int vocab, const int* ids, int m,
+                        float* out, int ld, int d_model, hipStream_t s);
+hipError_t launch_argmax_finish(const float* pval, const int* pidx, int rows, int NB,
+                                int* out_ids, hipStream_t s);
+hipError_t launch_accept(int* state, const int* draft_ids, int* shadow_ids, int L, int m, int E,
+                         int gamma, int* result, hipStream_t s);
+hipError_t launch_set_state(int* state, int add_T, int set_T, const int* pending_src,
+                            int pending_val, hipStream_t s);
+hipError_t launch_tile_scatter(const void* src, int wdtype, int64_t row0, int64_t nrows, int64_t cols,
+                               int map, int vbase, int hd, void* dst, int KT, hipStream_t s);
+hipError_t launch_pad_gain(const float* src, int K, float* dst, int Kpad, hipStream_t s);
+hipError_t launch_stream_read(const void* base, int64_t bytes, float* sink, hipStream_t s);
+
+constexpr int ATTN_CT = 64;  // context rows per attention work-group
+
+}  // namespace del

@@ -1,0 +1,688 @@
+// gfx950 (CDNA4) kernels of the greedy self-speculative decode round.
+//
+// Everything here is bound by HBM traffic except the multi-row GEMMs, which use the matrix
+// cores.  Weights are streamed exactly once per launch in 1 KiB wave-sized tiles (see
+// del_kernels.h); activations stay fp32 on the vector path and are split into bf16 hi + lo
+// halves (16 mantissa bits together) on the matrix-core path, accumulating in fp32.
+#include "del_kernels.h"
+
+namespace del {
+
+typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8;
+typedef __attribute__((__vector_size__(4 * sizeof(float)))) float floatx4;
+
+constexpr int MAXW = 16;  // waves per work-group at most
+constexpr int CT = ATTN_CT;
+constexpr int QB = 32;    // query rows per attention batch
+
+__device__ __forceinline__ float bf16_bits_to_f32(uint32_t h) { return __uint_as_float(h << 16); }
+__device__ __forceinline__ uint16_t f32_to_bf16_rne(float f) {
+  uint32_t u = __float_as_uint(f);
+  u += 0x7FFFu + ((u >> 16) & 1u);
+  return (uint16_t)(u >> 16);
+}
+
+template <int KPL> struct WDec;
+template <> struct WDec<8> {  // 8 bf16 in a uint4
+  static __device__ __forceinline__ void dec(const uint4& w, float* f) {
+    f[0] = __uint_as_float(w.x << 16); f[1] = __uint_as_float(w.x & 0xFFFF0000u);
+    f[2] = __uint_as_float(w.y << 16); f[3] = __uint_as_float(w.y & 0xFFFF0000u);
+    f[4] = __uint_as_float(w.z << 16); f[5] = __uint_as_float(w.z & 0xFFFF0000u);
+    f[6] = __uint_as_float(w.w << 16); f[7] = __uint_as_float(w.w & 0xFFFF0000u);
+  }
+};
+template <> struct WDec<4> {  // 4 fp32 in a uint4
+  static __device__ __forceinline__ void dec(const uint4& w, float* f) {
+    f[0] = __uint_as_float(w.x); f[1] = __uint_as_float(w.y);
+    f[2] = __uint_as_float(w.z); f[3] = __uint_as_float(w.w);
+  }
+};
+
+template <bool BF16> __device__ __forceinline__ void kv_store(void* base, size_t idx, float v) {
+  if (BF16) ((uint16_t*)base)[idx] = f32_to_bf16_rne(v);
+  else ((float*)base)[idx] = v;
+}
+
+// ---------------------------------------------------------------------------------------
+// Epilogues.  fin[mi][r] holds the finished 16 outputs of row-block nb for token row mi.
+// ---------------------------------------------------------------------------------------
+template <int EPI, bool BF16KV>
+__device__ __forceinline__ void epilogue(const GemmP& p, int nb, float (*fin)[16], int m, int rowbase) {
+  const int nthr = blockDim.x;
+  if (EPI == EPI_STORE || EPI == EPI_RESID) {
+    for (int tid = threadIdx.x; tid < m * 16; tid += nthr) {
+      const int mi = tid >> 4, r = tid & 15, n = nb * 16 + r;
+      if (n < p.N) {
+        float v = fin[mi][r];
+        if (EPI == EPI_RESID) v += p.R[(size_t)(rowbase + mi) * p.ldr + n];
+        p.Y[(size_t)(rowbase + mi) * p.ldy + n] = v;
+      }
+    }
+  } else if (EPI == EPI_QKV) {
+    for (int tid = threadIdx.x; tid < m * 16; tid += nthr) {
+      const int mi = tid >> 4, r = tid & 15;
+      const int hd = p.hd, half = hd >> 1;
+      const int v0 = nb * 16;
+      const int hh = v0 / hd, s0 = v0 - hh * hd;
+      const int pos = p.state[0] + p.row_off + rowbase + mi;
+      if (hh < p.n_q + p.n_kv) {  // rotary heads: rows r and r+8 are the pair (j, j + hd/2)
+        if (r < 8) {
+          const int j = (s0 >> 4) * 8 + r;
+          const float a = fin[mi][r], b = fin[mi][r + 8];
+          const float2 cs = p.rope[(size_t)pos * half + j];
+          const float ar = a * cs.x - b * cs.y;
+          const float br = b * cs.x + a * cs.y;
+          if (hh < p.n_q) {
+            float* q = p.Q + (size_t)(rowbase + mi) * p.ldq + hh * hd;
+            q[j] = ar;
+            q[j + half] = br;
+          } else {
+            const size_t base = ((size_t)(hh - p.n_q) * p.Tcap + pos) * hd;
+            kv_store<BF16KV>(p.Kc, base + j, ar);
+            kv_store<BF16KV>(p.Kc, base + j + half, br);
+          }
+        }
+      } else {
+        const size_t base = ((size_t)(hh - p.n_q - p.n_kv) * p.Tcap + pos) * hd;
+        kv_store<BF16KV>(p.Vc, base + s0 + r, fin[mi][r]);
+      }
+    }
+  } else if (EPI == EPI_SWIGLU) {
+    for (int tid = threadIdx.x; tid < m * 8; tid += nthr) {
+      const int mi = tid >> 3, r = tid & 7, j = nb * 8 + r;
+      if (j < p.d_ffn) {
+        const float gt = fin[mi][r], up = fin[mi][r + 8];
+        p.ACT[(size_t)(rowbase + mi) * p.ldact + j] = gt / (1.0f + expf(-gt)) * up;
+      }
+    }
+  } else if (EPI == EPI_ARGMAX) {
+    for (int tid = threadIdx.x; tid < m; tid += nthr) {
+      const int mi = tid;
+      float best = -INFINITY;
+      int bi = 0x7FFFFFFF;
+      for (int r = 0; r < 16; ++r) {
+        const int n = nb * 16 + r;
+        const float v = fin[mi][r];
+        if (n < p.N && v > best) { best = v; bi = n; }  // strict >: lowest index wins ties
+      }
+      const size_t o = (size_t)(p.prow0 + rowbase + mi) * p.NB + nb;
+      p.pval[o] = best;
+      p.pidx[o] = bi;
+    }
+  }
+}
+
+// ---------------------------------------------------------------------------------------
+// Vector-ALU GEMV / skinny GEMM: one work-group per 16-row block, its waves interleave over
+// the k tiles, each lane accumulates one weight row for M token rows in fp32.
+// ---------------------------------------------------------------------------------------
+template <int KPL, int M, int EPI>
+__global__ void __launch_bounds__(1024) gemm_valu_k(GemmP p) {
+  constexpr int TK = 4 * KPL;
+  constexpr int U = 4;
+  __shared__ float red[MAXW][M][16];
+  __shared__ float ssr[MAXW][M];
+  __shared__ float fin[16][16];
+  const int tid = threadIdx.x, nw = blockDim.x >> 6, wave = tid >> 6, lane = tid & 63;
+  const int g = lane >> 4;
+  const int nb = blockIdx.x;
+  float acc[M], ss[M];
+#pragma unroll
+  for (int m = 0; m < M; ++m) { acc[m] = 0.f; ss[m] = 0.f; }
+  const uint4* wp = (const uint4*)p.Wt + (size_t)nb * p.KT * 64 + lane;
+  const bool has_gain = p.gain != nullptr;
+  for (int kt0 = wave; kt0 < p.KT; kt0 += nw * U) {
+    uint4 wv[U];
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      const int kt = kt0 + u * nw;
+      wv[u] = kt < p.KT ? wp[(size_t)kt * 64] : make_uint4(0, 0, 0, 0);
+    }
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      const int kt = kt0 + u * nw;
+      if (kt < p.KT) {
+        float wf[KPL], gn[KPL];
+        WDec<KPL>::dec(wv[u], wf);
+        const int k0 = kt * TK + g * KPL;
+#pragma unroll
+        for (int e = 0; e < KPL; e += 4) {
+          float4 t = has_gain ? *(const float4*)(p.gain + k0 + e) : make_float4(1.f, 1.f, 1.f, 1.f);
+          gn[e] = t.x; gn[e + 1] = t.y; gn[e + 2] = t.z; gn[e + 3] = t.w;
+        }
+#pragma unroll
+        for (int m = 0; m < M; ++m) {
+          const float* xr = p.X + (size_t)m * p.ldx + k0;
+#pragma unroll
+          for (int e = 0; e < KPL; e += 4) {
+            const float4 t = *(const float4*)(xr + e);
+            ss[m] += t.x * t.x + t.y * t.y + t.z * t.z + t.w * t.w;
+            acc[m] += wf[e] * (t.x * gn[e]);
+            acc[m] += wf[e + 1] * (t.y * gn[e + 1]);
+            acc[m] += wf[e + 2] * (t.z * gn[e + 2]);
+            acc[m] += wf[e + 3] * (t.w * gn[e + 3]);
+          }
+        }
+      }
+    }
+  }
+#pragma unroll
+  for (int m = 0; m < M; ++m) {
+    acc[m] += __shfl_xor(acc[m], 16);
+    acc[m] += __shfl_xor(acc[m], 32);
+    ss[m] += __shfl_xor(ss[m], 16);
+    ss[m] += __shfl_xor(ss[m], 32);
+  }
+  if (lane < 16) {
+#pragma unroll
+    for (int m = 0; m < M; ++m) red[wave][m][lane] = acc[m];
+  }
+  if (lane == 0) {
+#pragma unroll
+    for (int m = 0; m < M; ++m) ssr[wave][m] = ss[m];
+  }
+  __syncthreads();
+  for (int t = tid; t < M * 16; t += blockDim.x) {
+    const int mi = t >> 4, r = t & 15;
+    float s = 0.f;
+    for (int w = 0; w < nw; ++w) s += red[w][mi][r];
+    if (p.rms) {
+      float q = 0.f;
+      for (int w = 0; w < nw; ++w) q += ssr[w][mi];
+      s *= 1.0f / sqrtf(q / (float)p.K + p.eps);
+    }
+    fin[mi][r] = s;
+  }
+  __syncthreads();
+  epilogue<EPI, KPL == 8>(p, nb, fin, M, 0);
+}
+
+// ---------------------------------------------------------------------------------------
+// Matrix-core skinny GEMM (bf16 weights): out[16 weight rows][16 token rows] per wave via
+// v_mfma_f32_16x16x32_bf16, weights as the A operand straight from the tiled layout, token
+// rows as the B operand from hi/lo split tiles ([cb][kt][hi|lo][lane][8], lane = 16*(k/8%4) +
+// token).  Two MFMAs per tile (hi, lo).  blockIdx.y selects a block of 16 token rows.
+// ---------------------------------------------------------------------------------------
+template <int EPI>
+__global__ void __launch_bounds__(1024) gemm_mfma_k(GemmP p) {
+  constexpr int U = 4;
+  __shared__ float red[MAXW][16][16];
+  __shared__ float fin[16][16];
+  const int tid = threadIdx.x, nw = blockDim.x >> 6, wave = tid >> 6, lane = tid & 63;
+  const int nb = blockIdx.x, cb = blockIdx.y;
+  const int mvalid = min(16, p.M - cb * 16);
+  const int token = lane & 15, g = lane >> 4;
+  const uint4* wp = (const uint4*)p.Wt + (size_t)nb * p.KT * 64 + lane;
+  const uint4* xp = (const uint4*)p.Xs + (size_t)cb * p.KT * 128 + lane;
+  const bool ld = token < mvalid;
+  floatx4 acc = {0.f, 0.f, 0.f, 0.f};
+  for (int kt0 = wave; kt0 < p.KT; kt0 += nw * U) {
+    uint4 a[U], bh[U], bl[U];
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      const int kt = kt0 + u * nw;
+      a[u] = bh[u] = bl[u] = make_uint4(0, 0, 0, 0);
+      if (kt < p.KT) {
+        a[u] = wp[(size_t)kt * 64];
+        if (ld) {
+          bh[u] = xp[(size_t)kt * 128];
+          bl[u] = xp[(size_t)kt * 128 + 64];
+        }
+      }
+    }
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      const bf16x8 av = __builtin_bit_cast(bf16x8, a[u]);
+      acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(av, __builtin_bit_cast(bf16x8, bh[u]), acc, 0, 0, 0);
+      acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(av, __builtin_bit_cast(bf16x8, bl[u]), acc, 0, 0, 0);
+    }
+  }
+  // D layout: lane holds D[4*(lane/16) + j][lane%16], j = 0..3 (rows = weight rows, cols = tokens)
+#pragma unroll
+  for (int j = 0; j < 4; ++j) red[wave][token][4 * g + j] = acc[j];
+  __syncthreads();
+  for (int t = tid; t < 256; t += blockDim.x) {
+    const int mi = t >> 4, r = t & 15;
+    if (mi < mvalid) {
+      float s = 0.f;
+      for (int w = 0; w < nw; ++w) s += red[w][mi][r];
+      if (p.rowscale) s *= p.rowscale[cb * 16 + mi];
+      fin[mi][r] = s;
+    }
+  }
+  __syncthreads();
+  epilogue<EPI, true>(p, nb, fin, mvalid, cb * 16);
+}
+
+// ---------------------------------------------------------------------------------------
+// fp32 rows -> bf16 hi/lo split tiles (+ optional gain and inverse RMS per row).
+// One work-group per row.
+// ---------------------------------------------------------------------------------------
+__global__ void __launch_bounds__(256) prep_split_k(const float* src, int rows_per_group, long long group_stride,
+                                                    int ld, int K, int KT, const float* gain, int rms, float eps,
+                                                    uint16_t* Xs, float* rowscale) {
+  __shared__ float part[4];
+  const int row = blockIdx.x, tid = threadIdx.x;
+  const int grp = row / rows_per_group, i = row - grp * rows_per_group;
+  const float* x = src + (size_t)grp * group_stride + (size_t)i * ld;
+  if (rms) {
+    float ss = 0.f;
+    for (int k = tid; k < K; k += 256) ss += x[k] * x[k];
+    for (int o = 32; o > 0; o >>= 1) ss += __shfl_xor(ss, o);
+    if ((tid & 63) == 0) part[tid >> 6] = ss;
+    __syncthreads();
+    if (tid == 0) rowscale[row] = 1.0f / sqrtf((part[0] + part[1] + part[2] + part[3]) / (float)K + eps);
+  } else if (tid == 0) {
+    rowscale[row] = 1.0f;
+  }
+  const int cb = row >> 4, token = row & 15;
+  uint16_t* out = Xs + (size_t)cb * KT * 1024;
+  for (int k = tid; k < KT * 32; k += 256) {
+    float v = 0.f;
+    if (k < K) v = gain ? x[k] * gain[k] : x[k];
+    const uint16_t hi = f32_to_bf16_rne(v);
+    const uint16_t lo = f32_to_bf16_rne(v - bf16_bits_to_f32(hi));
+    const int kt = k >> 5, gg = (k & 31) >> 3, e = k & 7;
+    const size_t off = (size_t)kt * 1024 + (gg * 16 + token) * 8 + e;
+    out[off] = hi;
+    out[off + 512] = lo;
+  }
+}
+
+// ---------------------------------------------------------------------------------------
+// Attention over the KV cache, split over the context: one work-group per (chunk of CT cache
+// rows, kv head).  K and V of the chunk are staged in LDS once and shared by every query row
+// of the head group (m token rows x n_q/n_kv heads).  Emits softmax partials (max, sum,
+// weighted values); attn_combine_k merges the chunks.  Caches are [n_kv][Tcap][hd].
+// ---------------------------------------------------------------------------------------
+template <typename KVT>
+__global__ void __launch_bounds__(256) attn_partial_k(AttnP p) {
+  extern __shared__ __align__(16) unsigned char smem[];
+  constexpr int EPW = 4 / sizeof(KVT);  // elements per 32-bit word
+  const int tid = threadIdx.x;
+  const int c = blockIdx.x, kvh = blockIdx.y;
+  const int T0 = p.state[0] + p.row_off;
+  const int T_end = T0 + p.m;
+  const int t0 = c * CT;
+  if (t0 >= T_end) return;
+  const int nt = min(CT, T_end - t0);
+  const int hd = p.hd, G = p.n_q / p.n_kv, QR = p.m * G;
+  const int wpr = hd / EPW;   // words per cache row
+  const int ksw = wpr + 1;    // padded LDS row stride in words
+  uint32_t* Ks = (uint32_t*)smem;
+  uint32_t* Vs = Ks + CT * ksw;
+  float* Qs = (float*)(Vs + CT * ksw);
+  float* Ss = Qs + QB * hd;
+  const uint32_t* Kg = (const uint32_t*)((const KVT*)p.Kc + ((size_t)kvh * p.Tcap + t0) * hd);
+  const uint32_t* Vg = (const uint32_t*)((const KVT*)p.Vc + ((size_t)kvh * p.Tcap + t0) * hd);
+  for (int i = tid; i < nt * wpr; i += 256) {
+    const int row = i / wpr, w = i - row * wpr;
+    Ks[row * ksw + w] = Kg[i];
+    Vs[row * ksw + w] = Vg[i];
+  }
+  const float scale = 1.0f / sqrtf((float)hd);
+  const int DPT = hd >> 3;  // value dims per thread in the PV step (<= 16)
+  for (int qb = 0; qb < QR; qb += QB) {
+    const int nq = min(QB, QR - qb);
+    __syncthreads();
+    for (int i = tid; i < nq * hd; i += 256) {
+      const int qi = i / hd, d = i - qi * hd;
+      const int qr = qb + qi, mi = qr / G, gi = qr - mi * G;
+      Qs[qi * hd + d] = p.Q[(size_t)mi * p.ldq + (kvh * G + gi) * hd + d] * scale;
+    }
+    __syncthreads();
+    for (int pi = tid; pi < nq * CT; pi += 256) {
+      const int qi = pi / CT, t = pi - qi * CT;
+      const int mi = (qb + qi) / G;
+      float s = -INFINITY;
+      if (t < nt && t0 + t <= T0 + mi) {
+        const uint32_t* kr = Ks + t * ksw;
+        const float* qv = Qs + qi * hd;
+        float a = 0.f;
+        if (sizeof(KVT) == 2) {
+          for (int w = 0; w < wpr; ++w) {
+            const uint32_t kk = kr[w];
+            a += qv[2 * w] * __uint_as_float(kk << 16);
+            a += qv[2 * w + 1] * __uint_as_float(kk & 0xFFFF0000u);
+          }
+        } else {
+          for (int w = 0; w < wpr; ++w) a += qv[w] * __uint_as_float(kr[w]);
+        }
+        s = a;
+      }
+      Ss[qi * CT + t] = s;
+    }
+    __syncthreads();
+    const int qi = tid >> 3, dg = tid & 7;
+    if (qi < nq) {
+      const float* sr = Ss + qi * CT;
+      float mx = -INFINITY;
+      for (int t = 0; t < nt; ++t) mx = fmaxf(mx, sr[t]);
+      float l = 0.f;
+      float acc[16];
+#pragma unroll
+      for (int e = 0; e < 16; ++e) acc[e] = 0.f;
+      if (mx > -INFINITY) {
+        for (int t = 0; t < nt; ++t) {
+          const float pr = expf(sr[t] - mx);  // masked entries are -inf -> 0
+          l += pr;
+          const uint32_t* vr = Vs + t * ksw + (dg * DPT) / EPW;
+          if (sizeof(KVT) == 2) {
+#pragma unroll
+            for (int w = 0; w < 8; ++w) {
+              if (2 * w < DPT) {
+                const uint32_t vv = vr[w];
+                acc[2 * w] += pr * __uint_as_float(vv << 16);
+                acc[2 * w + 1] += pr * __uint_as_float(vv & 0xFFFF0000u);
+              }
+            }
+          } else {
+#pragma unroll
+            for (int w = 0; w < 16; ++w)
+              if (w < DPT) acc[w] += pr * __uint_as_float(vr[w]);
+          }
+        }
+      }
+      const int qr = qb + qi, mi = qr / G, gi = qr - mi * G;
+      const size_t prow = ((size_t)mi * p.n_q + kvh * G + gi) * p.nch_max + c;
+      if (dg == 0) { p.PM[prow] = mx; p.PL[prow] = l; }
+      float* pa = p.PA + prow * hd + dg * DPT;
+#pragma unroll
+      for (int e = 0; e < 16; ++e)
+        if (e < DPT) pa[e] = acc[e];
+    }
+  }
+}
+
+__global__ void __launch_bounds__(128) attn_combine_k(AttnP p) {
+  const int row = blockIdx.x;  // mi * n_q + h
+  const int d = threadIdx.x;
+  if (d >= p.hd) return;
+  const int T_end = p.state[0] + p.row_off + p.m;
+  const int nch = (T_end + CT - 1) / CT;
+  const float* pm = p.PM + (size_t)row * p.nch_max;
+  const float* pl = p.PL + (size_t)row * p.nch_max;
+  float M = -INFINITY;
+  for (int c = 0; c < nch; ++c) M = fmaxf(M, pm[c]);
+  float L = 0.f, acc = 0.f;
+  for (int c = 0; c < nch; ++c) {
+    const float mc = pm[c];
+    if (mc > -INFINITY) {
+      const float w = expf(mc - M);
+      L += w * pl[c];
+      acc += w * p.PA[((size_t)row * p.nch_max + c) * p.hd + d];
+    }
+  }
+  const int mi = row / p.n_q, h = row - mi * p.n_q;
+  p.O[(size_t)mi * p.ldo + h * p.hd + d] = acc / L;
+}
+
+// ---------------------------------------------------------------------------------------
+// Small kernels
+// ---------------------------------------------------------------------------------------
+template <int KPL>
+__global__ void __launch_bounds__(256) embed_k(const void* Et, int KT, int vocab, const int* ids, float* out, int ld,
+                                               int d_model) {
+  constexpr int TK = 4 * KPL;
+  const int row = blockIdx.x;
+  int id = ids[row];
+  id = id < 0 ? 0 : (id >= vocab ? vocab - 1 : id);
+  const int nb = id >> 4, r = id & 15;
+  for (int k = threadIdx.x; k < d_model; k += 256) {
+    const int kt = k / TK, g = (k % TK) / KPL, e = k % KPL;
+    const size_t off = (((size_t)nb * KT + kt) * 64 + g * 16 + r) * KPL + e;
+    float v;
+    if (KPL == 8) v = bf16_bits_to_f32(((const uint16_t*)Et)[off]);
+    else v = ((const float*)Et)[off];
+    out[(size_t)row * ld + k] = v;
+  }
+}
+
+// Merge the per-row-block (max, index) partials of one logits row; lowest index wins ties.
+__global__ void __launch_bounds__(256) argmax_finish_k(const float* pval, const int* pidx, int NB, int* out_ids) {
+  __shared__ float sv[256];
+  __shared__ int si[256];
+  const int row = blockIdx.x, tid = threadIdx.x;
+  float best = -INFINITY;
+  int bi = 0x7FFFFFFF;
+  for (int b = tid; b < NB; b += 256) {
+    const float v = pval[(size_t)row * NB + b];
+    const int ix = pidx[(size_t)row * NB + b];
+    if (v > best || (v == best && ix < bi)) { best = v; bi = ix; }
+  }
+  sv[tid] = best; si[tid] = bi;
+  __syncthreads();
+  for (int s = 128; s > 0; s >>= 1) {
+    if (tid < s) {
+      const float v = sv[tid + s];
+      const int ix = si[tid + s];
+      if (v > sv[tid] || (v == sv[tid] && ix < si[tid])) { sv[tid] = v; si[tid] = ix; }
+    }
+    __syncthreads();
+  }
+  if (tid == 0) out_ids[row] = si[0];
+}
+
+// Greedy acceptance on the device (Section 2, greedy special case): u = first i < gamma
+// with draft[i] != target[i], else gamma; the KV length advances by u + 1 and the pending
+// input token becomes the target's token at u.  The drafted tokens are layer E's shadow
+// tokens by construction, so they overwrite that row (both were computed from the same
+// hidden state, but by different kernels).
+// result: [0]=u, [1]=new T, [2]=pending, [3..3+gamma) drafts, then shadow [L][m]
+__global__ void accept_k(int* state, const int* draft_ids, int* shadow_ids, int L, int m, int E, int gamma,
+                         int* result) {
+  if (threadIdx.x != 0 || blockIdx.x != 0) return;
+  int* srow = shadow_ids + (size_t)(E - 1) * m;
+  for (int i = 0; i < gamma; ++i) srow[i] = draft_ids[i];
+  const int* target = shadow_ids + (size_t)(L - 1) * m;
+  int u = gamma;
+  for (int i = 0; i < gamma; ++i) {
+    if (draft_ids[i] != target[i]) { u = i; break; }
+  }
+  const int T = state[0] + u + 1;
+  state[0] = T;
+  state[1] = target[u];
+  result[0] = u;
+  result[1] = T;
+  result[2] = target[u];
+  for (int i = 0; i < gamma; ++i) result[3 + i] = draft_ids[i];
+  for (int i = 0; i < L * m; ++i) result[3 + gamma + i] = shadow_ids[i];
+}
+
+__global__ void set_state_k(int* state, int add_T, int set_T, const int* pending_src, int pending_val) {
+  if (threadIdx.x != 0 || blockIdx.x != 0) return;
+  if (set_T >= 0) state[0] = set_T;
+  state[0] += add_T;
+  if (pending_src) state[1] = *pending_src;
+  else if (pending_val >= 0) state[1] = pending_val;
+}
+
+// Natural row-major [nrows, cols] (rows row0.. of the tensor) -> tiled layout, with the row map.
+template <int KPL, typename T>
+__global__ void __launch_bounds__(256) tile_scatter_k(const T* src, long long row0, long long nrows, long long cols,
+                                                      int map, int vbase, int hd, T* dst, int KT) {
+  const long long chunks_per_row = (cols + KPL - 1) / KPL;
+  const long long total = nrows * chunks_per_row;
+  for (long long i = (long long)blockIdx.x * 256 + threadIdx.x; i < total; i += (long long)gridDim.x * 256) {
+    const long long ln = i / chunks_per_row;
+    const int kc = (int)(i - ln * chunks_per_row);
+    const long long n = row0 + ln;
+    long long v;
+    if (map == MAP_ROPE) {
+      const int half = hd >> 1;
+      const long long head = n / hd;
+      const int j = (int)(n - head * hd);
+      const int b = j / half, jj = j - b * half;
+      v = vbase + head * hd + (jj >> 3) * 16 + b * 8 + (jj & 7);
+    } else if (map == MAP_GATE) {
+      v = (n >> 3) * 16 + (n & 7);
+    } else if (map == MAP_UP) {
+      v = (n >> 3) * 16 + 8 + (n & 7);
+    } else {
+      v = vbase + n;
+    }
+    const long long nb = v >> 4;
+    const int r = (int)(v & 15);
+    const int kt = kc >> 2, g = kc & 3;
+    T* d = dst + (((size_t)nb * KT + kt) * 64 + g * 16 + r) * KPL;
+    const T* s = src + (size_t)ln * cols + (size_t)kc * KPL;
+#pragma unroll
+    for (int e = 0; e < KPL; ++e) d[e] = ((long long)kc * KPL + e < cols) ? s[e] : (T)0;
+  }
+}
+
+__global__ void pad_gain_k(const float* src, int K, float* dst, int Kpad) {
+  const int k = blockIdx.x * 256 + threadIdx.x;
+  if (k < Kpad) dst[k] = k < K ? src[k] : 0.f;
+}
+
+// Pure streaming read with the GEMV access pattern (1 KiB per wave per load, 4 in flight).
+__global__ void __launch_bounds__(256) stream_read_k(const uint4* base, long long n_tiles, float* sink) {
+  const int lane = threadIdx.x & 63;
+  const long long wave = ((long long)blockIdx.x * 256 + threadIdx.x) >> 6;
+  const long long n_waves = ((long long)gridDim.x * 256) >> 6;
+  uint32_t acc = 0;
+  for (long long t = wave; t < n_tiles; t += n_waves * 4) {
+    uint4 v[4];
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+      const long long tt = t + u * n_waves;
+      v[u] = tt < n_tiles ? base[tt * 64 + lane] : make_uint4(0, 0, 0, 0);
+    }
+#pragma unroll
+    for (int u = 0; u < 4; ++u) acc ^= v[u].x ^ v[u].y ^ v[u].z ^ v[u].w;
+  }
+  if (acc == 0x9E3779B9u) sink[0] = 1.f;  // practically never; keeps the loads alive
+}
+
+// ---------------------------------------------------------------------------------------
+// Launchers
+// ---------------------------------------------------------------------------------------
+template <int KPL, int M>
+static hipError_t launch_valu_m(const GemmP& p, int epi, int waves, hipStream_t s) {
+  dim3 grid(p.NB), block(64 * waves);
+  switch (epi) {
+    case EPI_STORE: hipLaunchKernelGGL((gemm_valu_k<KPL, M, EPI_STORE>), grid, block, 0, s, p); break;
+    case EPI_RESID: hipLaunchKernelGGL((gemm_valu_k<KPL, M, EPI_RESID>), grid, block, 0, s, p); break;
+    case EPI_QKV: hipLaunchKernelGGL((gemm_valu_k<KPL, M, EPI_QKV>), grid, block, 0, s, p); break;
+    case EPI_SWIGLU: hipLaunchKernelGGL((gemm_valu_k<KPL, M, EPI_SWIGLU>), grid, block, 0, s, p); break;
+    case EPI_ARGMAX: hipLaunchKernelGGL((gemm_valu_k<KPL, M, EPI_ARGMAX>), grid, block, 0, s, p); break;
+    default: return hipErrorInvalidValue;
+  }
+  return hipGetLastError();
+}
+
+template <int KPL>
+static hipError_t launch_valu_k(const GemmP& p, int epi, int waves, hipStream_t s) {
+  switch (p.M) {
+    case 1: return launch_valu_m<KPL, 1>(p, epi, waves, s);
+    case 2: return launch_valu_m<KPL, 2>(p, epi, waves, s);
+    case 4: return launch_valu_m<KPL, 4>(p, epi, waves, s);
+    case 8: return launch_valu_m<KPL, 8>(p, epi, waves, s);
+    default: return hipErrorInvalidValue;
+  }
+}
+
+hipError_t launch_gemm_valu(const GemmP& p, int epi, int waves, hipStream_t s) {
+  if (waves < 1 || waves > MAXW || p.NB <= 0 || p.KT <= 0) return hipErrorInvalidValue;
+  return p.wdtype == 1 ? launch_valu_k<8>(p, epi, waves, s) : launch_valu_k<4>(p, epi, waves, s);
+}
+
+hipError_t launch_gemm_mfma(const GemmP& p, int epi, int waves, int col_blocks, hipStream_t s) {
+  if (waves < 1 || waves > MAXW || p.NB <= 0 || p.KT <= 0 || p.wdtype != 1 || col_blocks < 1 ||
+      p.M > col_blocks * 16 || p.M <= (col_blocks - 1) * 16)
+    return hipErrorInvalidValue;
+  dim3 grid(p.NB, col_blocks), block(64 * waves);
+  switch (epi) {
+    case EPI_STORE: hipLaunchKernelGGL((gemm_mfma_k<EPI_STORE>), grid, block, 0, s, p); break;
+    case EPI_RESID: hipLaunchKernelGGL((gemm_mfma_k<EPI_RESID>), grid, block, 0, s, p); break;
+    case EPI_QKV: hipLaunchKernelGGL((gemm_mfma_k<EPI_QKV>), grid, block, 0, s, p); break;
+    case EPI_SWIGLU: hipLaunchKernelGGL((gemm_mfma_k<EPI_SWIGLU>), grid, block, 0, s, p); break;
+    case EPI_ARGMAX: hipLaunchKernelGGL((gemm_mfma_k<EPI_ARGMAX>), grid, block, 0, s, p); break;
+    default: return hipErrorInvalidValue;
+  }
+  return hipGetLastError();
+}
+
+hipError_t launch_prep_split(const float* src, int rows, int rows_per_group, int64_t group_stride, int ld, int K,
+                             int KT, const float* gain, int rms, float eps, uint16_t* Xs, float* rowscale,
+                             hipStream_t s) {
+  if (rows <= 0) return hipErrorInvalidValue;
+  hipLaunchKernelGGL(prep_split_k, dim3(rows), dim3(256), 0, s, src, rows_per_group, (long long)group_stride, ld, K,
+                     KT, gain, rms, eps, Xs, rowscale);
+  return hipGetLastError();
+}
+
+static size_t attn_lds_bytes(int hd, int esize) {
+  const int wpr = hd * esize / 4;
+  return (size_t)2 * CT * (wpr + 1) * 4 + (size_t)QB * hd * 4 + (size_t)QB * CT * 4;
+}
+
+hipError_t launch_attention(const AttnP& p, hipStream_t s) {
+  if (p.hd > 128 || p.hd % 16 != 0 || p.m < 1 || p.n_q % p.n_kv != 0) return hipErrorInvalidValue;
+  dim3 grid(p.nch_max, p.n_kv), block(256);
+  if (p.kvdtype == 1)
+    hipLaunchKernelGGL((attn_partial_k<uint16_t>), grid, block, attn_lds_bytes(p.hd, 2), s, p);
+  else
+    hipLaunchKernelGGL((attn_partial_k<float>), grid, block, attn_lds_bytes(p.hd, 4), s, p);
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return e;
+  hipLaunchKernelGGL(attn_combine_k, dim3(p.m * p.n_q), dim3(128), 0, s, p);
+  return hipGetLastError();
+}
+
+hipError_t launch_embed(const void* Et, int wdtype, int KT, int vocab, const int* ids, int m, float* out, int ld,
+                        int d_model, hipStream_t s) {
+  if (wdtype == 1)
+    hipLaunchKernelGGL((embed_k<8>), dim3(m), dim3(256), 0, s, Et, KT, vocab, ids, out, ld, d_model);
+  else
+    hipLaunchKernelGGL((embed_k<4>), dim3(m), dim3(256), 0, s, Et, KT, vocab, ids, out, ld, d_model);
+  return hipGetLastError();
+}
+
+hipError_t launch_argmax_finish(const float* pval, const int* pidx, int rows, int NB, int* out_ids, hipStream_t s) {
+  hipLaunchKernelGGL(argmax_finish_k, dim3(rows), dim3(256), 0, s, pval, pidx, NB, out_ids);
+  return hipGetLastError();
+}
+
+hipError_t launch_accept(int* state, const int* draft_ids, int* shadow_ids, int L, int m, int E, int gamma,
+                         int* result, hipStream_t s) {
+  hipLaunchKernelGGL(accept_k, dim3(1), dim3(64), 0, s, state, draft_ids, shadow_ids, L, m, E, gamma, result);
+  return hipGetLastError();
+}
+
+hipError_t launch_set_state(int* state, int add_T, int set_T, const int* pending_src, int pending_val,
+                            hipStream_t s) {
+  hipLaunchKernelGGL(set_state_k, dim3(1), dim3(64), 0, s, state, add_T, set_T, pending_src, pending_val);
+  return hipGetLastError();
+}
+
+hipError_t launch_tile_scatter(const void* src, int wdtype, int64_t row0, int64_t nrows, int64_t cols, int map,
+                               int vbase, int hd, void* dst, int KT, hipStream_t s) {
+  const int kpl = wdtype == 1 ? 8 : 4;
+  const int64_t total = nrows * ((cols + kpl - 1) / kpl);
+  if (total <= 0) return hipSuccess;
+  const int64_t want = (total + 255) / 256;
+  const int blocks = (int)(want < 65535 * 4 ? want : 65535 * 4);
+  if (wdtype == 1)
+    hipLaunchKernelGGL((tile_scatter_k<8, uint16_t>), dim3(blocks), dim3(256), 0, s, (const uint16_t*)src,
+                       (long long)row0, (long long)nrows, (long long)cols, map, vbase, hd, (uint16_t*)dst, KT);
+  else
+    hipLaunchKernelGGL((tile_scatter_k<4, float>), dim3(blocks), dim3(256), 0, s, (const float*)src, (long long)row0,
+                       (long long)nrows, (long long)cols, map, vbase, hd, (float*)dst, KT);
+  return hipGetLastError();
+}
+
+hipError_t launch_pad_gain(const float* src, int K, float* dst, int Kpad, hipStream_t s) {
+  hipLaunchKernelGGL(pad_gain_k, dim3((Kpad + 255) / 256), dim3(256), 0, s, src, K, dst, Kpad);
+  return hipGetLastError();
+}
+
+hipError_t launch_stream_read(const void* base, int64_t bytes, float* sink, hipStream_t s) {
+  const long long n_tiles = bytes / 1024;
+  if (n_tiles <= 0) return hipErrorInvalidValue;
+  hipLaunchKernelGGL(stream_read_k, dim3(256 * 8), dim3(256), 0, s, (const uint4*)base, n_tiles, sink);
+  return hipGetLastError();
+}
+
+}  // namespace del

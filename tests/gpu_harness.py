@@ -1,0 +1,172 @@
+"""Lock-step parity harness: HIP library versus the CPU oracle on the same seeded inputs.
+
+Protocol.  Both sides prefill on the same prompt and then run the same rounds with the
+oracle's (E, gamma).  Token ids, acceptance counts and the selected (E, gamma) must be equal,
+except where the oracle's top-2 logit gap at that very (layer, row) is below GAP_TOL; hidden
+states must agree to HID_TOL (max abs difference over max abs oracle value, per layer).
+A tolerated flip makes the two contexts differ, so the harness then re-prefills the GPU
+context on prompt + oracle tokens and imports the oracle's statistics, and goes on.
+"""
+from __future__ import annotations
+
+import sys
+from dataclasses import dataclass, field
+from typing import List
+
+import numpy as np
+import torch
+
+from oracle.del_oracle import Oracle
+from paper_2504_05598_amd.binding import DelContext
+from synthdata import gen_tensor, iter_tensor_specs
+
+GAP_TOL = 1e-2     # oracle top-2 logit gap below which either of the top two ids is accepted
+HID_TOL = 2e-2     # bf16 weights, fp32 accumulation (stated by the benchmark contract)
+
+
+def log(*a):
+    print(*a, file=sys.stderr, flush=True)
+
+
+def gpu_context(cfg, use_mfma=True, max_context=None, keep_host=False):
+    """Generate the model on the GPU with the shared generator and load it through the C ABI.
+    Returns (ctx, host_weights or None)."""
+    ctx = DelContext(cfg, use_mfma=use_mfma, max_context=max_context)
+    host = {} if keep_host else None
+    for layer, kind in iter_tensor_specs(cfg):
+        t = gen_tensor(cfg, layer, kind, device="cuda")
+        ctx.load_tensor(layer, kind, t)
+        if keep_host:
+            host[(layer, kind)] = t.cpu()
+        del t
+    torch.cuda.synchronize()
+    return ctx, host
+
+
+@dataclass
+class ParityReport:
+    rounds: int = 0
+    compared_ids: int = 0
+    flips: int = 0
+    resyncs: int = 0
+    max_hidden_err: float = 0.0
+    tokens: List[int] = field(default_factory=list)
+
+
+def _rel_err(got: np.ndarray, want: np.ndarray) -> float:
+    return float(np.abs(got - want).max() / max(np.abs(want).max(), 1e-30))
+
+
+def _resync(ctx: DelContext, oracle: Oracle, prompt, emitted, rep: ParityReport):
+    """GPU context := prefill(prompt + all emitted tokens but the last), pending := last."""
+    first, _, _ = ctx.prefill(list(prompt) + emitted[:-1])
+    if first != emitted[-1]:
+        ctx.set_pending(emitted[-1])
+    L = oracle.L
+    ctx.set_stats([0.0] + [oracle.stats.S_c(l) for l in range(1, L + 1)], oracle.stats.S_n())
+    T, pend = ctx.state()
+    assert T == oracle.T and pend == oracle.pending
+    rep.resyncs += 1
+
+
+def lockstep(cfg, oracle: Oracle, ctx: DelContext, prompt, n_tokens, schedule=None,
+             check_hidden=True, max_rounds=None) -> ParityReport:
+    """schedule: None = DEL-selected (E, gamma) from the oracle; or a fixed (E, gamma)."""
+    rep = ParityReport()
+    L, d_max = cfg.n_layers, cfg.d_max
+    pre = oracle.prefill(prompt, keep_hidden=check_hidden)
+    first, gE, gg = ctx.prefill(prompt)
+    st = ctx.stats()
+    # ---- prefill: first token, window statistics, first (E, gamma)
+    near = [[g < GAP_TOL for g in row] for row in pre.gaps]
+    if first != pre.first_token:
+        assert pre.first_gap < GAP_TOL, f"first token {first} != {pre.first_token}, gap {pre.first_gap}"
+        rep.flips += 1
+    w = pre.window
+    for l in range(1, L + 1):
+        slack = sum(1 for i in range(w) if near[l][i] or near[L][i])
+        assert abs(st["last_c"][l] - pre.c[l]) <= slack, (l, st["last_c"][l], pre.c[l], slack)
+    exact = all(st["last_c"][l] == pre.c[l] for l in range(1, L + 1)) and first == pre.first_token
+    if check_hidden:
+        for l in (1, L // 2 + 1, L):
+            # the last prompt position is the last row of the last prefill chunk (<= 16 rows)
+            err = _rel_err(ctx.hidden(l, min(len(prompt), 16) - 1), pre.hidden[l, -1].float().numpy())
+            rep.max_hidden_err = max(rep.max_hidden_err, err)
+            assert err <= HID_TOL, ("prefill hidden", l, err)
+    emitted = [pre.first_token]
+    if exact:
+        assert (gE, gg) == (pre.next_E, pre.next_gamma)
+        for l in range(1, L + 1):
+            assert st["alpha"][l] == pre.alpha[l] or abs(st["alpha"][l] - pre.alpha[l]) < 1e-12
+    else:
+        _resync(ctx, oracle, prompt, emitted, rep)
+    E, gamma = (pre.next_E, pre.next_gamma) if schedule is None else schedule
+    while len(emitted) < n_tokens and (max_rounds is None or rep.rounds < max_rounds):
+        g = min(gamma, n_tokens - len(emitted) - 1)
+        r = oracle.round(E, g, keep_hidden=check_hidden)
+        out = ctx.round(E, g)
+        st = ctx.stats()
+        rep.rounds += 1
+        # rows whose inputs are the same on both sides: up to the first differing draft
+        same_rows = g + 1
+        for i in range(g):
+            if st["last_draft"][i] != r.draft_ids[i]:
+                same_rows = i + 1
+                break
+        flipped = False
+        for l in range(1, L + 1):
+            for i in range(same_rows):
+                rep.compared_ids += 1
+                if st["last_shadow"][l][i] != r.shadow[l][i]:
+                    assert r.gaps[l][i] < GAP_TOL, (
+                        f"round {rep.rounds} E={E} g={g} layer {l} row {i}: gpu {st['last_shadow'][l][i]} "
+                        f"oracle {r.shadow[l][i]} gap {r.gaps[l][i]}")
+                    rep.flips += 1
+                    flipped = True
+        if check_hidden:
+            for l in range(1, L + 1):
+                want = r.hidden[l, :same_rows].float().numpy()
+                got = np.stack([ctx.hidden(l, i) for i in range(same_rows)])
+                err = _rel_err(got, want)
+                rep.max_hidden_err = max(rep.max_hidden_err, err)
+                assert err <= HID_TOL, ("hidden", rep.rounds, l, err)
+        emitted.extend(r.out_tokens)
+        if not flipped and same_rows == g + 1:
+            # identical ids everywhere: counts, tokens, statistics and selection must be equal
+            assert out == r.out_tokens, (out, r.out_tokens)
+            assert st["last_u"] == r.u and st["last_n"] == r.n
+            assert st["last_c"][1:] == r.c[1:]
+            assert st["last_draft"] == r.draft_ids
+            for l in range(1, L + 1):
+                assert abs(st["S_c"][l] - r.S_c[l]) <= 1e-9 * max(1.0, r.S_c[l])
+                assert abs(st["alpha"][l] - r.alpha[l]) <= 1e-9
+            assert abs(st["S_n"] - r.S_n) <= 1e-9 * r.S_n
+            assert (st["next_E"], st["next_gamma"]) == (r.next_E, r.next_gamma)
+            T, pend = ctx.state()
+            assert T == oracle.T and pend == oracle.pending
+        else:
+            _resync(ctx, oracle, prompt, emitted, rep)
+        if schedule is None:
+            E, gamma = r.next_E, r.next_gamma
+    rep.tokens = emitted
+    return rep
+
+
+def gpu_generate(ctx: DelContext, prompt, n_tokens, schedule=None):
+    """Free-running generation through the C ABI with the library's own (E, gamma) choice
+    (or a fixed schedule).  Returns tokens and the per-round log."""
+    first, E, gamma = ctx.prefill(prompt)
+    if schedule is not None:
+        E, gamma = schedule
+    toks = [first]
+    rounds = []
+    while len(toks) < n_tokens:
+        g = min(gamma, n_tokens - len(toks) - 1)
+        out = ctx.round(E, g)
+        assert 1 <= len(out) <= g + 1
+        rounds.append((E, g, len(out)))
+        toks.extend(out)
+        if schedule is None:
+            st = ctx.stats()
+            E, gamma = st["next_E"], st["next_gamma"]
+    return toks, rounds
