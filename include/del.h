@@ -153,6 +153,20 @@ del_status del_debug_set_pending(del_ctx* ctx, int32_t token);
  * the time of the last such call in ms. */
 del_status del_bench_stream_read(del_ctx* ctx, int64_t bytes, int32_t iters, float* ms_per_iter);
 
+/* Per-kernel timing for the roofline report.  While enabled, del_round brackets every GEMM
+ * launch with a pair of HIP events on the context's stream and accumulates, per kernel class,
+ * the launch count and the summed duration (the events cost a few microseconds per launch, so
+ * throughput is measured with profiling off).  A class is one kernel instantiation:
+ * flavour (0 vector-ALU, 1 matrix-core), epilogue (0 store, 1 residual, 2 qkv+rotary,
+ * 3 swiglu, 4 argmax), rows m.  weight_bytes is what one launch of the class streams. */
+typedef struct {
+  int32_t flavour, epilogue, rows, launches;
+  double total_ms;
+  int64_t weight_bytes;    /* tile bytes streamed per launch (of the last launch seen) */
+} del_prof_entry;
+del_status del_profile_enable(del_ctx* ctx, int32_t on);   /* also clears the counters */
+del_status del_profile_read(const del_ctx* ctx, del_prof_entry* out, int32_t cap, int32_t* n);
+
 const char* del_strerror(del_status s);
 const char* del_last_error_text(const del_ctx* ctx);
 

@@ -15,7 +15,7 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 
 EXPORTS = ["del_create", "del_destroy", "del_load_weights", "del_prefill", "del_round",
            "del_layer_stats", "del_set_layer_stats", "del_last_timings", "del_debug_hidden",
-           "del_debug_logits", "del_debug_state", "del_debug_set_pending", "del_bench_stream_read", "del_strerror",
+           "del_debug_logits", "del_debug_state", "del_debug_set_pending", "del_profile_enable", "del_profile_read", "del_bench_stream_read", "del_strerror",
            "del_last_error_text"]
 
 DEL_DTYPE_FP32, DEL_DTYPE_BF16 = 0, 1
@@ -43,6 +43,11 @@ class del_tensor(C.Structure):
     _fields_ = [("layer", C.c_int32), ("kind", C.c_int32), ("location", C.c_int32),
                 ("reserved", C.c_int32), ("data", C.c_void_p), ("rows", C.c_int64),
                 ("cols", C.c_int64)]
+
+
+class del_prof_entry(C.Structure):
+    _fields_ = [("flavour", C.c_int32), ("epilogue", C.c_int32), ("rows", C.c_int32),
+                ("launches", C.c_int32), ("total_ms", C.c_double), ("weight_bytes", C.c_int64)]
 
 
 class del_stats(C.Structure):
@@ -86,6 +91,8 @@ def load_library():
     lib.del_debug_logits.argtypes = [C.c_void_p, C.c_int32, C.c_int32, P(C.c_float)]
     lib.del_debug_state.argtypes = [C.c_void_p, P(C.c_int32), P(C.c_int32)]
     lib.del_debug_set_pending.argtypes = [C.c_void_p, C.c_int32]
+    lib.del_profile_enable.argtypes = [C.c_void_p, C.c_int32]
+    lib.del_profile_read.argtypes = [C.c_void_p, P(del_prof_entry), C.c_int32, P(C.c_int32)]
     lib.del_bench_stream_read.argtypes = [C.c_void_p, C.c_int64, C.c_int32, P(C.c_float)]
     lib.del_strerror.argtypes = [C.c_int]
     lib.del_strerror.restype = C.c_char_p
@@ -260,6 +267,26 @@ class DelContext:
 
     def set_pending(self, token: int) -> None:
         _check(load_library().del_debug_set_pending(self.ctx, token), self.ctx)
+
+    def profile_enable(self, on: bool) -> None:
+        _check(load_library().del_profile_enable(self.ctx, int(on)), self.ctx)
+
+    def profile_read(self) -> List[dict]:
+        cap = 256
+        arr = (del_prof_entry * cap)()
+        n = C.c_int32()
+        _check(load_library().del_profile_read(self.ctx, arr, cap, C.byref(n)), self.ctx)
+        names = {0: "store", 1: "resid", 2: "qkv_rope", 3: "swiglu", 4: "argmax"}
+        out = []
+        for e in arr[:min(n.value, cap)]:
+            if e.launches:
+                kernel = (f"gemm_valu_k<8,{e.rows},{e.epilogue}>" if e.flavour == 0
+                          else f"gemm_mfma_k<{e.epilogue}>")
+                out.append({"kernel": kernel, "flavour": "valu" if e.flavour == 0 else "mfma",
+                            "epilogue": names[e.epilogue], "rows": e.rows, "launches": e.launches,
+                            "total_ms": e.total_ms, "avg_us": 1e3 * e.total_ms / e.launches,
+                            "weight_bytes": e.weight_bytes})
+        return out
 
     def stream_read_gbps(self, nbytes: int, iters: int = 20) -> float:
         ms = C.c_float()

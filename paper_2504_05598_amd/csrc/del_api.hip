@@ -101,6 +101,12 @@ struct del_ctx {
   std::vector<int> last_c, last_shadow, last_draft;
   float t_draft = 0, t_verify = 0, t_shadow = 0;
   int target_waves = 4096;
+  // per-kernel profiling (off by default)
+  bool prof_on = false;
+  std::vector<hipEvent_t> prof_ev;     // pairs
+  std::vector<int> prof_cls;           // class index of each recorded pair
+  int prof_used = 0;                   // pairs recorded since the last collect
+  std::vector<del_prof_entry> prof;
 
   del_status fail(hipError_t e, const char* what) {
     err = std::string(what) + ": " + hipGetErrorString(e);
@@ -139,17 +145,61 @@ namespace {
 template <typename T>
 hipError_t dmalloc(T** p, size_t bytes) { return hipMalloc((void**)p, bytes ? bytes : 16); }
 
+int prof_begin(del_ctx* ctx, int flavour, int epi, int rows, int64_t bytes) {
+  if (!ctx->prof_on) return -1;
+  int cls = -1;
+  for (size_t i = 0; i < ctx->prof.size(); ++i)
+    if (ctx->prof[i].flavour == flavour && ctx->prof[i].epilogue == epi && ctx->prof[i].rows == rows) cls = (int)i;
+  if (cls < 0) {
+    del_prof_entry e{flavour, epi, rows, 0, 0.0, bytes};
+    ctx->prof.push_back(e);
+    cls = (int)ctx->prof.size() - 1;
+  }
+  ctx->prof[cls].weight_bytes = bytes;
+  const int pair = ctx->prof_used;
+  if ((size_t)(2 * pair + 1) >= ctx->prof_ev.size()) {
+    hipEvent_t a = nullptr, b = nullptr;
+    if (hipEventCreate(&a) != hipSuccess || hipEventCreate(&b) != hipSuccess) return -1;
+    ctx->prof_ev.push_back(a);
+    ctx->prof_ev.push_back(b);
+    ctx->prof_cls.push_back(cls);
+  }
+  ctx->prof_cls[pair] = cls;
+  if (hipEventRecord(ctx->prof_ev[2 * pair], ctx->stream) != hipSuccess) return -1;
+  return pair;
+}
+
+void prof_end(del_ctx* ctx, int pair) {
+  if (pair < 0) return;
+  if (hipEventRecord(ctx->prof_ev[2 * pair + 1], ctx->stream) == hipSuccess) ctx->prof_used = pair + 1;
+}
+
+// after a stream synchronisation: fold the recorded pairs into the class totals
+void prof_collect(del_ctx* ctx) {
+  for (int i = 0; i < ctx->prof_used; ++i) {
+    float ms = 0.f;
+    if (hipEventElapsedTime(&ms, ctx->prof_ev[2 * i], ctx->prof_ev[2 * i + 1]) == hipSuccess) {
+      ctx->prof[ctx->prof_cls[i]].launches += 1;
+      ctx->prof[ctx->prof_cls[i]].total_ms += ms;
+    }
+  }
+  ctx->prof_used = 0;
+}
+
 // One GEMM of the path: on the matrix cores (split the fp32 rows first) or as vector-ALU
 // groups of 8/4/2/1 rows.
 del_status gemm(del_ctx* ctx, GemmP p, int epi, int m, bool mfma) {
   const int waves = ctx->pick_waves(p.NB, p.KT);
+  const int64_t wbytes = (int64_t)p.NB * p.KT * 1024;
   if (mfma) {
     HIPCHK(launch_prep_split(p.X, m, m, 0, p.ldx, p.K, p.KT, p.gain, p.rms, p.eps, ctx->xs_layer, ctx->rowscale,
                              ctx->stream));
     p.Xs = ctx->xs_layer;
     p.rowscale = p.rms ? ctx->rowscale : nullptr;
     p.M = m;
+    const int pr = prof_begin(ctx, 1, epi, m, wbytes);
     HIPCHK(launch_gemm_mfma(p, epi, waves, 1, ctx->stream));
+    prof_end(ctx, pr);
     return DEL_OK;
   }
   int off = 0;
@@ -165,7 +215,9 @@ del_status gemm(del_ctx* ctx, GemmP p, int epi, int m, bool mfma) {
     if (q.ACT) q.ACT = p.ACT + (size_t)off * p.ldact;
     q.row_off = p.row_off + off;
     q.prow0 = p.prow0 + off;
+    const int pr = prof_begin(ctx, 0, epi, g, wbytes);
     HIPCHK(launch_gemm_valu(q, epi, waves, ctx->stream));
+    prof_end(ctx, pr);
     off += g;
   }
   return DEL_OK;
@@ -256,8 +308,10 @@ del_status shadow_head(del_ctx* ctx, int m) {
                              ctx->stream));
     GemmP p = head_gemm(ctx);
     p.Xs = ctx->xs_shadow; p.rowscale = ctx->rowscale; p.M = R;
+    const int pr = prof_begin(ctx, 1, EPI_ARGMAX, R, (int64_t)p.NB * p.KT * 1024);
     HIPCHK(launch_gemm_mfma(p, EPI_ARGMAX, ctx->pick_waves(p.NB * ceil_div(R, 16), p.KT), ceil_div(R, 16),
                             ctx->stream));
+    prof_end(ctx, pr);
   } else {
     for (int l = 1; l <= ctx->L; ++l) {
       GemmP p = head_gemm(ctx);
@@ -280,6 +334,8 @@ void free_all(del_ctx* c) {
     if (p) (void)hipFree(p);
   if (c->result_host) (void)hipHostFree(c->result_host);
   for (auto& e : c->ev)
+    if (e) (void)hipEventDestroy(e);
+  for (auto& e : c->prof_ev)
     if (e) (void)hipEventDestroy(e);
 }
 
@@ -556,6 +612,7 @@ del_status del_prefill(del_ctx* ctx, const int32_t* prompt, int32_t n_prompt, in
   const int first = shadow[(size_t)(L - 1) * w + (w - 1)];
   HIPCHK(launch_set_state(ctx->state, 0, -1, nullptr, first, ctx->stream));
   HIPCHK(hipStreamSynchronize(ctx->stream));
+  prof_collect(ctx);
   ctx->T = P; ctx->pending = first; ctx->phase = 1;
   ctx->last_c = c; ctx->last_E = 0; ctx->last_gamma = 0; ctx->last_u = w - 1; ctx->last_n = w;
   *first_token = first; *next_E = ctx->pol.next_E; *next_gamma = ctx->pol.next_gamma;
@@ -601,6 +658,7 @@ del_status del_round(del_ctx* ctx, int32_t E, int32_t gamma, int32_t* out_tokens
   const size_t nres = (size_t)3 + gamma + (size_t)L * m;
   HIPCHK(hipMemcpyAsync(ctx->result_host, ctx->result, nres * 4, hipMemcpyDeviceToHost, s));
   HIPCHK(hipStreamSynchronize(s));
+  prof_collect(ctx);
   (void)hipEventElapsedTime(&ctx->t_draft, ctx->ev[0], ctx->ev[1]);
   (void)hipEventElapsedTime(&ctx->t_verify, ctx->ev[1], ctx->ev[2]);
   (void)hipEventElapsedTime(&ctx->t_shadow, ctx->ev[2], ctx->ev[3]);
@@ -689,6 +747,23 @@ del_status del_debug_state(const del_ctx* ctx, int32_t* kv_len, int32_t* pending
   if (!ctx) return DEL_E_ARG;
   if (kv_len) *kv_len = ctx->T;
   if (pending_token) *pending_token = ctx->pending;
+  return DEL_OK;
+}
+
+del_status del_profile_enable(del_ctx* ctx, int32_t on) {
+  if (!ctx) return DEL_E_ARG;
+  HIPCHK(hipStreamSynchronize(ctx->stream));
+  ctx->prof_on = on != 0;
+  ctx->prof.clear();
+  ctx->prof_used = 0;
+  return DEL_OK;
+}
+
+del_status del_profile_read(const del_ctx* ctx, del_prof_entry* out, int32_t cap, int32_t* n) {
+  if (!ctx || !n || (cap > 0 && !out)) return DEL_E_ARG;
+  const int have = (int)ctx->prof.size();
+  *n = have;
+  for (int i = 0; i < have && i < cap; ++i) out[i] = ctx->prof[i];
   return DEL_OK;
 }
 
