@@ -84,7 +84,7 @@ struct del_ctx {
   float2* rope = nullptr;
   float* hid = nullptr; float* q = nullptr; float* attn = nullptr; float* act = nullptr;
   uint16_t* xs_layer = nullptr; uint16_t* xs_shadow = nullptr; float* rowscale = nullptr;
-  float* PM = nullptr; float* PL = nullptr; float* PA = nullptr; int nch_max = 0;
+  float* PM = nullptr; float* PL = nullptr; float* PA = nullptr; int nch_max = 0, attn_ct = 64;
   float* pval = nullptr; int* pidx = nullptr;
   int* state = nullptr; int* draft_ids = nullptr; int* shadow_ids = nullptr; int* result = nullptr;
   int* ids_dev = nullptr; int* result_host = nullptr;
@@ -254,7 +254,7 @@ del_status run_layer(del_ctx* ctx, int l, int row0, int m) {
   a.Q = ctx->q; a.ldq = ctx->qpad; a.Kc = p.Kc; a.Vc = p.Vc; a.kvdtype = ctx->wd;
   a.n_q = ctx->nq; a.n_kv = ctx->nkv; a.hd = ctx->hd; a.Tcap = ctx->Tcap; a.m = m;
   a.state = ctx->state; a.row_off = row0;
-  a.PM = ctx->PM; a.PL = ctx->PL; a.PA = ctx->PA; a.nch_max = ctx->nch_max;
+  a.PM = ctx->PM; a.PL = ctx->PL; a.PA = ctx->PA; a.nch_max = ctx->nch_max; a.ct = ctx->attn_ct;
   a.O = ctx->attn; a.ldo = ctx->qpad;
   HIPCHK(launch_attention(a, ctx->stream));
   // 3. output projection + residual
@@ -407,7 +407,12 @@ del_status del_create(const del_config* cfg, void* hip_stream, del_ctx** out) {
   ctx->arena_bytes = ctx->layer_stride * ctx->L;
   ctx->vocab_bytes = (size_t)ctx->NBv * ctx->KTd * tile;
   ctx->kv_layer_bytes = (size_t)ctx->nkv * ctx->Tcap * ctx->hd * ctx->esize;
-  ctx->nch_max = ceil_div(ctx->Tcap, ATTN_CT);
+  // attention chunk: as large as the staging registers allow, smaller when that leaves the
+  // chip short of work-groups (few kv heads, short context)
+  ctx->attn_ct = 64;
+  while (ctx->attn_ct * ctx->hd * ctx->esize > 4 * 256 * 16) ctx->attn_ct -= 16;
+  while (ctx->attn_ct > 16 && ctx->nkv * ceil_div(ctx->Tcap, ctx->attn_ct) < 512) ctx->attn_ct -= 16;
+  ctx->nch_max = ceil_div(ctx->Tcap, ctx->attn_ct);
   const int Rmax = ctx->L * ctx->maxrows;
   const int KTmax = std::max(ctx->KTd, std::max(ctx->KTq, ctx->KTf));
 

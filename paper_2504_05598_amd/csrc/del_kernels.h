@@ -62,6 +62,7 @@ struct AttnP {
   const int* state; int row_off;
   float* PM; float* PL; float* PA;  // partials [(mi*n_q+h)][nch_max] (+[hd])
   int nch_max;
+  int ct;                       // cache rows per work-group (16, 32, 48 or 64)
   float* O; int ldo;            // combined output [m][n_q*hd]
 };
 
@@ -84,6 +85,5 @@ hipError_t launch_tile_scatter(const void* src, int wdtype, int64_t row0, int64_
 hipError_t launch_pad_gain(const float* src, int K, float* dst, int Kpad, hipStream_t s);
 hipError_t launch_stream_read(const void* base, int64_t bytes, float* sink, hipStream_t s);
 
-constexpr int ATTN_CT = 64;  // context rows per attention work-group
 
 }  // namespace del

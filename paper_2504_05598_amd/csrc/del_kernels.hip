@@ -12,7 +12,6 @@ typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8;
 typedef __attribute__((__vector_size__(4 * sizeof(float)))) float floatx4;
 
 constexpr int MAXW = 16;  // waves per work-group at most
-constexpr int CT = ATTN_CT;
 constexpr int QB = 32;    // query rows per attention batch
 
 __device__ __forceinline__ float bf16_bits_to_f32(uint32_t h) { return __uint_as_float(h << 16); }
@@ -113,13 +112,28 @@ __device__ __forceinline__ void epilogue(const GemmP& p, int nb, float (*fin)[16
 }
 
 // ---------------------------------------------------------------------------------------
-// Vector-ALU GEMV / skinny GEMM: one work-group per 16-row block, its waves interleave over
-// the k tiles, each lane accumulates one weight row for M token rows in fp32.
+// Weight streaming.  A weight tile is read exactly once per launch, so it is fetched with a
+// non-temporal load (no reuse: keeps the stream out of the way of the cached activations),
+// and every wave owns a contiguous span of the k tiles of its row block.
+// ---------------------------------------------------------------------------------------
+typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
+__device__ __forceinline__ uint4 ld_stream(const uint4* p) {
+  const u32x4 v = __builtin_nontemporal_load((const u32x4*)p);
+  return make_uint4(v.x, v.y, v.z, v.w);
+}
+
+constexpr int GU = 8;  // tiles in flight per wave and pipeline stage
+
+// ---------------------------------------------------------------------------------------
+// Vector-ALU GEMV (M = 1) / skinny GEMM (M = 2, 4, 8): one work-group per 16-row block; each
+// lane accumulates one weight row over its wave's span of k tiles, fp32 throughout.
+// M = 1 (the draft path): the gained input row is staged once in LDS (dynamic, KT*TK floats)
+// while the first weight tiles are already in flight; M > 1 reads the rows through the cache.
 // ---------------------------------------------------------------------------------------
 template <int KPL, int M, int EPI>
 __global__ void __launch_bounds__(1024) gemm_valu_k(GemmP p) {
   constexpr int TK = 4 * KPL;
-  constexpr int U = 4;
+  extern __shared__ __align__(16) float xs[];
   __shared__ float red[MAXW][M][16];
   __shared__ float ssr[MAXW][M];
   __shared__ float fin[16][16];
@@ -131,47 +145,79 @@ __global__ void __launch_bounds__(1024) gemm_valu_k(GemmP p) {
   for (int m = 0; m < M; ++m) { acc[m] = 0.f; ss[m] = 0.f; }
   const uint4* wp = (const uint4*)p.Wt + (size_t)nb * p.KT * 64 + lane;
   const bool has_gain = p.gain != nullptr;
-  for (int kt0 = wave; kt0 < p.KT; kt0 += nw * U) {
-    uint4 wv[U];
+  const int per = (p.KT + nw - 1) / nw;
+  const int kt_lo = wave * per, kt_hi = min(p.KT, kt_lo + per);
+  uint4 cur[GU], nxt[GU];
 #pragma unroll
-    for (int u = 0; u < U; ++u) {
-      const int kt = kt0 + u * nw;
-      wv[u] = kt < p.KT ? wp[(size_t)kt * 64] : make_uint4(0, 0, 0, 0);
+  for (int u = 0; u < GU; ++u) cur[u] = kt_lo + u < kt_hi ? ld_stream(wp + (size_t)(kt_lo + u) * 64) : make_uint4(0, 0, 0, 0);
+  if (M == 1) {
+    const int Kp = p.KT * TK;
+    for (int k = tid * 4; k < Kp; k += blockDim.x * 4) {
+      const float4 x = *(const float4*)(p.X + k);
+      float4 gg = has_gain ? *(const float4*)(p.gain + k) : make_float4(1.f, 1.f, 1.f, 1.f);
+      ss[0] += x.x * x.x + x.y * x.y + x.z * x.z + x.w * x.w;
+      *(float4*)(xs + k) = make_float4(x.x * gg.x, x.y * gg.y, x.z * gg.z, x.w * gg.w);
+    }
+    __syncthreads();
+  }
+  for (int kt0 = kt_lo; kt0 < kt_hi; kt0 += GU) {
+#pragma unroll
+    for (int u = 0; u < GU; ++u) {
+      const int kt = kt0 + GU + u;
+      nxt[u] = kt < kt_hi ? ld_stream(wp + (size_t)kt * 64) : make_uint4(0, 0, 0, 0);
     }
 #pragma unroll
-    for (int u = 0; u < U; ++u) {
-      const int kt = kt0 + u * nw;
-      if (kt < p.KT) {
-        float wf[KPL], gn[KPL];
-        WDec<KPL>::dec(wv[u], wf);
+    for (int u = 0; u < GU; ++u) {
+      const int kt = kt0 + u;
+      if (kt < kt_hi) {
+        float wf[KPL];
+        WDec<KPL>::dec(cur[u], wf);
         const int k0 = kt * TK + g * KPL;
-#pragma unroll
-        for (int e = 0; e < KPL; e += 4) {
-          float4 t = has_gain ? *(const float4*)(p.gain + k0 + e) : make_float4(1.f, 1.f, 1.f, 1.f);
-          gn[e] = t.x; gn[e + 1] = t.y; gn[e + 2] = t.z; gn[e + 3] = t.w;
-        }
-#pragma unroll
-        for (int m = 0; m < M; ++m) {
-          const float* xr = p.X + (size_t)m * p.ldx + k0;
+        if (M == 1) {
 #pragma unroll
           for (int e = 0; e < KPL; e += 4) {
-            const float4 t = *(const float4*)(xr + e);
-            ss[m] += t.x * t.x + t.y * t.y + t.z * t.z + t.w * t.w;
-            acc[m] += wf[e] * (t.x * gn[e]);
-            acc[m] += wf[e + 1] * (t.y * gn[e + 1]);
-            acc[m] += wf[e + 2] * (t.z * gn[e + 2]);
-            acc[m] += wf[e + 3] * (t.w * gn[e + 3]);
+            const float4 t = *(const float4*)(xs + k0 + e);
+            acc[0] += wf[e] * t.x;
+            acc[0] += wf[e + 1] * t.y;
+            acc[0] += wf[e + 2] * t.z;
+            acc[0] += wf[e + 3] * t.w;
+          }
+        } else {
+          float gn[KPL];
+#pragma unroll
+          for (int e = 0; e < KPL; e += 4) {
+            float4 t = has_gain ? *(const float4*)(p.gain + k0 + e) : make_float4(1.f, 1.f, 1.f, 1.f);
+            gn[e] = t.x; gn[e + 1] = t.y; gn[e + 2] = t.z; gn[e + 3] = t.w;
+          }
+#pragma unroll
+          for (int m = 0; m < M; ++m) {
+            const float* xr = p.X + (size_t)m * p.ldx + k0;
+#pragma unroll
+            for (int e = 0; e < KPL; e += 4) {
+              const float4 t = *(const float4*)(xr + e);
+              ss[m] += t.x * t.x + t.y * t.y + t.z * t.z + t.w * t.w;
+              acc[m] += wf[e] * (t.x * gn[e]);
+              acc[m] += wf[e + 1] * (t.y * gn[e + 1]);
+              acc[m] += wf[e + 2] * (t.z * gn[e + 2]);
+              acc[m] += wf[e + 3] * (t.w * gn[e + 3]);
+            }
           }
         }
       }
     }
+#pragma unroll
+    for (int u = 0; u < GU; ++u) cur[u] = nxt[u];
   }
 #pragma unroll
   for (int m = 0; m < M; ++m) {
     acc[m] += __shfl_xor(acc[m], 16);
     acc[m] += __shfl_xor(acc[m], 32);
-    ss[m] += __shfl_xor(ss[m], 16);
-    ss[m] += __shfl_xor(ss[m], 32);
+    if (M == 1) {  // every thread staged a distinct slice: reduce over the whole wave
+      for (int o = 1; o < 64; o <<= 1) ss[m] += __shfl_xor(ss[m], o);
+    } else {       // lanes of one 16-lane group read the same k range: reduce over the groups
+      ss[m] += __shfl_xor(ss[m], 16);
+      ss[m] += __shfl_xor(ss[m], 32);
+    }
   }
   if (lane < 16) {
 #pragma unroll
@@ -215,19 +261,27 @@ __global__ void __launch_bounds__(1024) gemm_mfma_k(GemmP p) {
   const uint4* wp = (const uint4*)p.Wt + (size_t)nb * p.KT * 64 + lane;
   const uint4* xp = (const uint4*)p.Xs + (size_t)cb * p.KT * 128 + lane;
   const bool ld = token < mvalid;
+  const int per = (p.KT + nw - 1) / nw;
+  const int kt_lo = wave * per, kt_hi = min(p.KT, kt_lo + per);
   floatx4 acc = {0.f, 0.f, 0.f, 0.f};
-  for (int kt0 = wave; kt0 < p.KT; kt0 += nw * U) {
-    uint4 a[U], bh[U], bl[U];
+  uint4 a[U], bh[U], bl[U], an[U], bhn[U], bln[U];
+#pragma unroll
+  for (int u = 0; u < U; ++u) {
+    const int kt = kt_lo + u;
+    a[u] = bh[u] = bl[u] = make_uint4(0, 0, 0, 0);
+    if (kt < kt_hi) {
+      a[u] = ld_stream(wp + (size_t)kt * 64);
+      if (ld) { bh[u] = xp[(size_t)kt * 128]; bl[u] = xp[(size_t)kt * 128 + 64]; }
+    }
+  }
+  for (int kt0 = kt_lo; kt0 < kt_hi; kt0 += U) {
 #pragma unroll
     for (int u = 0; u < U; ++u) {
-      const int kt = kt0 + u * nw;
-      a[u] = bh[u] = bl[u] = make_uint4(0, 0, 0, 0);
-      if (kt < p.KT) {
-        a[u] = wp[(size_t)kt * 64];
-        if (ld) {
-          bh[u] = xp[(size_t)kt * 128];
-          bl[u] = xp[(size_t)kt * 128 + 64];
-        }
+      const int kt = kt0 + U + u;
+      an[u] = bhn[u] = bln[u] = make_uint4(0, 0, 0, 0);
+      if (kt < kt_hi) {
+        an[u] = ld_stream(wp + (size_t)kt * 64);
+        if (ld) { bhn[u] = xp[(size_t)kt * 128]; bln[u] = xp[(size_t)kt * 128 + 64]; }
       }
     }
 #pragma unroll
@@ -236,7 +290,10 @@ __global__ void __launch_bounds__(1024) gemm_mfma_k(GemmP p) {
       acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(av, __builtin_bit_cast(bf16x8, bh[u]), acc, 0, 0, 0);
       acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(av, __builtin_bit_cast(bf16x8, bl[u]), acc, 0, 0, 0);
     }
+#pragma unroll
+    for (int u = 0; u < U; ++u) { a[u] = an[u]; bh[u] = bhn[u]; bl[u] = bln[u]; }
   }
+  (void)g;
   // D layout: lane holds D[4*(lane/16) + j][lane%16], j = 0..3 (rows = weight rows, cols = tokens)
 #pragma unroll
   for (int j = 0; j < 4; ++j) red[wave][token][4 * g + j] = acc[j];
@@ -290,38 +347,58 @@ __global__ void __launch_bounds__(256) prep_split_k(const float* src, int rows_p
 }
 
 // ---------------------------------------------------------------------------------------
-// Attention over the KV cache, split over the context: one work-group per (chunk of CT cache
-// rows, kv head).  K and V of the chunk are staged in LDS once and shared by every query row
-// of the head group (m token rows x n_q/n_kv heads).  Emits softmax partials (max, sum,
-// weighted values); attn_combine_k merges the chunks.  Caches are [n_kv][Tcap][hd].
+// Attention over the KV cache, split over the context: one work-group per (chunk of p.ct cache
+// rows, kv head).  K and V of the chunk are fetched with all loads in flight at once, staged
+// in LDS and shared by every query row of the head group (m token rows x n_q/n_kv heads).
+// Emits softmax partials (max, sum, weighted values); attn_combine_k merges the chunks.
+// Caches are [n_kv][Tcap][hd].
 // ---------------------------------------------------------------------------------------
 template <typename KVT>
 __global__ void __launch_bounds__(256) attn_partial_k(AttnP p) {
   extern __shared__ __align__(16) unsigned char smem[];
   constexpr int EPW = 4 / sizeof(KVT);  // elements per 32-bit word
-  const int tid = threadIdx.x;
+  constexpr int NLD = 4;                // 16-byte loads per thread and matrix (64 rows x 256 B at most)
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int c = blockIdx.x, kvh = blockIdx.y;
+  const int ct = p.ct;
   const int T0 = p.state[0] + p.row_off;
   const int T_end = T0 + p.m;
-  const int t0 = c * CT;
+  const int t0 = c * ct;
   if (t0 >= T_end) return;
-  const int nt = min(CT, T_end - t0);
+  const int nt = min(ct, T_end - t0);
   const int hd = p.hd, G = p.n_q / p.n_kv, QR = p.m * G;
   const int wpr = hd / EPW;   // words per cache row
   const int ksw = wpr + 1;    // padded LDS row stride in words
+  const int rb16 = wpr >> 2;  // 16-byte pieces per cache row
   uint32_t* Ks = (uint32_t*)smem;
-  uint32_t* Vs = Ks + CT * ksw;
-  float* Qs = (float*)(Vs + CT * ksw);
+  uint32_t* Vs = Ks + ct * ksw;
+  float* Qs = (float*)(Vs + ct * ksw);
   float* Ss = Qs + QB * hd;
-  const uint32_t* Kg = (const uint32_t*)((const KVT*)p.Kc + ((size_t)kvh * p.Tcap + t0) * hd);
-  const uint32_t* Vg = (const uint32_t*)((const KVT*)p.Vc + ((size_t)kvh * p.Tcap + t0) * hd);
-  for (int i = tid; i < nt * wpr; i += 256) {
-    const int row = i / wpr, w = i - row * wpr;
-    Ks[row * ksw + w] = Kg[i];
-    Vs[row * ksw + w] = Vg[i];
+  const uint4* Kg = (const uint4*)((const KVT*)p.Kc + ((size_t)kvh * p.Tcap + t0) * hd);
+  const uint4* Vg = (const uint4*)((const KVT*)p.Vc + ((size_t)kvh * p.Tcap + t0) * hd);
+  const int npieces = nt * rb16;
+  uint4 kr[NLD], vr[NLD];
+#pragma unroll
+  for (int j = 0; j < NLD; ++j) {
+    const int i = tid + 256 * j;
+    kr[j] = vr[j] = make_uint4(0, 0, 0, 0);
+    if (i < npieces) { kr[j] = Kg[i]; vr[j] = Vg[i]; }
+  }
+#pragma unroll
+  for (int j = 0; j < NLD; ++j) {
+    const int i = tid + 256 * j;
+    if (i < npieces) {
+      const int row = i / rb16, w = (i - row * rb16) * 4;
+      uint32_t* kd = Ks + row * ksw + w;
+      uint32_t* vd = Vs + row * ksw + w;
+      kd[0] = kr[j].x; kd[1] = kr[j].y; kd[2] = kr[j].z; kd[3] = kr[j].w;
+      vd[0] = vr[j].x; vd[1] = vr[j].y; vd[2] = vr[j].z; vd[3] = vr[j].w;
+    }
   }
   const float scale = 1.0f / sqrtf((float)hd);
-  const int DPT = hd >> 3;  // value dims per thread in the PV step (<= 16)
+  const int dpairs = hd >> 1;          // PV step: one thread per pair of value dims
+  const int nslots = 256 / dpairs;     // query rows processed side by side in the PV step
+  const int d2 = tid % dpairs, qslot = tid / dpairs;
   for (int qb = 0; qb < QR; qb += QB) {
     const int nq = min(QB, QR - qb);
     __syncthreads();
@@ -331,65 +408,67 @@ __global__ void __launch_bounds__(256) attn_partial_k(AttnP p) {
       Qs[qi * hd + d] = p.Q[(size_t)mi * p.ldq + (kvh * G + gi) * hd + d] * scale;
     }
     __syncthreads();
-    for (int pi = tid; pi < nq * CT; pi += 256) {
-      const int qi = pi / CT, t = pi - qi * CT;
+    // scores: one (query row, cache row) pair per thread and step
+    for (int pi = tid; pi < nq * ct; pi += 256) {
+      const int qi = pi / ct, t = pi - qi * ct;
       const int mi = (qb + qi) / G;
       float s = -INFINITY;
       if (t < nt && t0 + t <= T0 + mi) {
-        const uint32_t* kr = Ks + t * ksw;
+        const uint32_t* krow = Ks + t * ksw;
         const float* qv = Qs + qi * hd;
         float a = 0.f;
         if (sizeof(KVT) == 2) {
           for (int w = 0; w < wpr; ++w) {
-            const uint32_t kk = kr[w];
+            const uint32_t kk = krow[w];
             a += qv[2 * w] * __uint_as_float(kk << 16);
             a += qv[2 * w + 1] * __uint_as_float(kk & 0xFFFF0000u);
           }
         } else {
-          for (int w = 0; w < wpr; ++w) a += qv[w] * __uint_as_float(kr[w]);
+          for (int w = 0; w < wpr; ++w) a += qv[w] * __uint_as_float(krow[w]);
         }
         s = a;
       }
-      Ss[qi * CT + t] = s;
+      Ss[qi * ct + t] = s;
     }
     __syncthreads();
-    const int qi = tid >> 3, dg = tid & 7;
-    if (qi < nq) {
-      const float* sr = Ss + qi * CT;
-      float mx = -INFINITY;
-      for (int t = 0; t < nt; ++t) mx = fmaxf(mx, sr[t]);
-      float l = 0.f;
-      float acc[16];
-#pragma unroll
-      for (int e = 0; e < 16; ++e) acc[e] = 0.f;
-      if (mx > -INFINITY) {
+    // softmax numerators per row: one wave per query row, lanes over the cache rows
+    for (int qi = wave; qi < nq; qi += 4) {
+      float sv = lane < ct ? Ss[qi * ct + lane] : -INFINITY;
+      float mx = sv;
+      for (int o = 32; o > 0; o >>= 1) mx = fmaxf(mx, __shfl_xor(mx, o));
+      const float pr = mx > -INFINITY ? expf(sv - mx) : 0.f;   // masked entries: exp(-inf) = 0
+      float l = pr;
+      for (int o = 32; o > 0; o >>= 1) l += __shfl_xor(l, o);
+      if (lane < ct) Ss[qi * ct + lane] = pr;
+      if (lane == 0) {
+        const int qr = qb + qi, mi = qr / G, gi = qr - mi * G;
+        const size_t prow = ((size_t)mi * p.n_q + kvh * G + gi) * p.nch_max + c;
+        p.PM[prow] = mx;
+        p.PL[prow] = l;
+      }
+    }
+    __syncthreads();
+    // weighted values
+    for (int qi = qslot < nslots ? qslot : nq; qi < nq; qi += nslots) {
+      const float* pr = Ss + qi * ct;
+      float a0 = 0.f, a1 = 0.f;
+      if (sizeof(KVT) == 2) {
+        const uint32_t* vcol = Vs + d2;
         for (int t = 0; t < nt; ++t) {
-          const float pr = expf(sr[t] - mx);  // masked entries are -inf -> 0
-          l += pr;
-          const uint32_t* vr = Vs + t * ksw + (dg * DPT) / EPW;
-          if (sizeof(KVT) == 2) {
-#pragma unroll
-            for (int w = 0; w < 8; ++w) {
-              if (2 * w < DPT) {
-                const uint32_t vv = vr[w];
-                acc[2 * w] += pr * __uint_as_float(vv << 16);
-                acc[2 * w + 1] += pr * __uint_as_float(vv & 0xFFFF0000u);
-              }
-            }
-          } else {
-#pragma unroll
-            for (int w = 0; w < 16; ++w)
-              if (w < DPT) acc[w] += pr * __uint_as_float(vr[w]);
-          }
+          const uint32_t vv = vcol[t * ksw];
+          a0 += pr[t] * __uint_as_float(vv << 16);
+          a1 += pr[t] * __uint_as_float(vv & 0xFFFF0000u);
+        }
+      } else {
+        const uint32_t* vcol = Vs + 2 * d2;
+        for (int t = 0; t < nt; ++t) {
+          a0 += pr[t] * __uint_as_float(vcol[t * ksw]);
+          a1 += pr[t] * __uint_as_float(vcol[t * ksw + 1]);
         }
       }
       const int qr = qb + qi, mi = qr / G, gi = qr - mi * G;
       const size_t prow = ((size_t)mi * p.n_q + kvh * G + gi) * p.nch_max + c;
-      if (dg == 0) { p.PM[prow] = mx; p.PL[prow] = l; }
-      float* pa = p.PA + prow * hd + dg * DPT;
-#pragma unroll
-      for (int e = 0; e < 16; ++e)
-        if (e < DPT) pa[e] = acc[e];
+      *(float2*)(p.PA + prow * hd + 2 * d2) = make_float2(a0, a1);
     }
   }
 }
@@ -399,7 +478,7 @@ __global__ void __launch_bounds__(128) attn_combine_k(AttnP p) {
   const int d = threadIdx.x;
   if (d >= p.hd) return;
   const int T_end = p.state[0] + p.row_off + p.m;
-  const int nch = (T_end + CT - 1) / CT;
+  const int nch = (T_end + p.ct - 1) / p.ct;
   const float* pm = p.PM + (size_t)row * p.nch_max;
   const float* pl = p.PL + (size_t)row * p.nch_max;
   float M = -INFINITY;
@@ -558,18 +637,33 @@ __global__ void __launch_bounds__(256) stream_read_k(const uint4* base, long lon
 // ---------------------------------------------------------------------------------------
 // Launchers
 // ---------------------------------------------------------------------------------------
+template <int KPL, int M, int EPI>
+static hipError_t launch_valu_e(const GemmP& p, int waves, hipStream_t s) {
+  dim3 grid(p.NB), block(64 * waves);
+  const size_t lds = M == 1 ? (size_t)p.KT * 4 * KPL * sizeof(float) : 0;
+  if (lds > 48 * 1024) {  // beyond the default dynamic LDS limit: raise it for this kernel (once is enough)
+    static size_t raised = 0;
+    if (lds > raised) {
+      hipError_t e = hipFuncSetAttribute((const void*)gemm_valu_k<KPL, M, EPI>,
+                                         hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+      if (e != hipSuccess) return e;
+      raised = lds;
+    }
+  }
+  hipLaunchKernelGGL((gemm_valu_k<KPL, M, EPI>), grid, block, lds, s, p);
+  return hipGetLastError();
+}
+
 template <int KPL, int M>
 static hipError_t launch_valu_m(const GemmP& p, int epi, int waves, hipStream_t s) {
-  dim3 grid(p.NB), block(64 * waves);
   switch (epi) {
-    case EPI_STORE: hipLaunchKernelGGL((gemm_valu_k<KPL, M, EPI_STORE>), grid, block, 0, s, p); break;
-    case EPI_RESID: hipLaunchKernelGGL((gemm_valu_k<KPL, M, EPI_RESID>), grid, block, 0, s, p); break;
-    case EPI_QKV: hipLaunchKernelGGL((gemm_valu_k<KPL, M, EPI_QKV>), grid, block, 0, s, p); break;
-    case EPI_SWIGLU: hipLaunchKernelGGL((gemm_valu_k<KPL, M, EPI_SWIGLU>), grid, block, 0, s, p); break;
-    case EPI_ARGMAX: hipLaunchKernelGGL((gemm_valu_k<KPL, M, EPI_ARGMAX>), grid, block, 0, s, p); break;
+    case EPI_STORE: return launch_valu_e<KPL, M, EPI_STORE>(p, waves, s);
+    case EPI_RESID: return launch_valu_e<KPL, M, EPI_RESID>(p, waves, s);
+    case EPI_QKV: return launch_valu_e<KPL, M, EPI_QKV>(p, waves, s);
+    case EPI_SWIGLU: return launch_valu_e<KPL, M, EPI_SWIGLU>(p, waves, s);
+    case EPI_ARGMAX: return launch_valu_e<KPL, M, EPI_ARGMAX>(p, waves, s);
     default: return hipErrorInvalidValue;
   }
-  return hipGetLastError();
 }
 
 template <int KPL>
@@ -613,18 +707,22 @@ hipError_t launch_prep_split(const float* src, int rows, int rows_per_group, int
   return hipGetLastError();
 }
 
-static size_t attn_lds_bytes(int hd, int esize) {
+static size_t attn_lds_bytes(int hd, int esize, int ct) {
   const int wpr = hd * esize / 4;
-  return (size_t)2 * CT * (wpr + 1) * 4 + (size_t)QB * hd * 4 + (size_t)QB * CT * 4;
+  return (size_t)2 * ct * (wpr + 1) * 4 + (size_t)QB * hd * 4 + (size_t)QB * ct * 4;
 }
 
 hipError_t launch_attention(const AttnP& p, hipStream_t s) {
-  if (p.hd > 128 || p.hd % 16 != 0 || p.m < 1 || p.n_q % p.n_kv != 0) return hipErrorInvalidValue;
+  const int es = p.kvdtype == 1 ? 2 : 4;
+  // the staging registers hold ct rows of at most 4 x 256 threads x 16 bytes per matrix
+  if (p.hd > 128 || p.hd % 16 != 0 || p.m < 1 || p.n_q % p.n_kv != 0 || p.ct < 16 || p.ct > 64 || p.ct % 16 != 0 ||
+      p.ct * p.hd * es > 4 * 256 * 16)
+    return hipErrorInvalidValue;
   dim3 grid(p.nch_max, p.n_kv), block(256);
   if (p.kvdtype == 1)
-    hipLaunchKernelGGL((attn_partial_k<uint16_t>), grid, block, attn_lds_bytes(p.hd, 2), s, p);
+    hipLaunchKernelGGL((attn_partial_k<uint16_t>), grid, block, attn_lds_bytes(p.hd, 2, p.ct), s, p);
   else
-    hipLaunchKernelGGL((attn_partial_k<float>), grid, block, attn_lds_bytes(p.hd, 4), s, p);
+    hipLaunchKernelGGL((attn_partial_k<float>), grid, block, attn_lds_bytes(p.hd, 4, p.ct), s, p);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
   hipLaunchKernelGGL(attn_combine_k, dim3(p.m * p.n_q), dim3(128), 0, s, p);
