@@ -84,6 +84,8 @@ struct del_ctx {
   float2* rope = nullptr;
   float* hid = nullptr; float* q = nullptr; float* attn = nullptr; float* act = nullptr;
   uint16_t* xs_layer = nullptr; uint16_t* xs_shadow = nullptr; float* rowscale = nullptr;
+  uint16_t* xs_h = nullptr; uint16_t* xs_attn = nullptr; uint16_t* xs_h1 = nullptr; uint16_t* xs_act = nullptr;
+  float* ssq_h = nullptr; float* ssq_h1 = nullptr;
   float* PM = nullptr; float* PL = nullptr; float* PA = nullptr; int nch_max = 0, attn_ct = 64;
   float* pval = nullptr; int* pidx = nullptr;
   int* state = nullptr; int* draft_ids = nullptr; int* shadow_ids = nullptr; int* result = nullptr;
@@ -126,10 +128,11 @@ struct del_ctx {
       }
     return true;
   }
+  // waves per 16-row block: the whole k range of a block is split over the waves of its
+  // work-group; 16 waves for the matrices with few blocks, 8 when there are many
   int pick_waves(int NB, int KT) const {
-    int w = 1;
-    while (w < 16 && NB * w < target_waves) w <<= 1;
-    while (w > 1 && KT < w) w >>= 1;
+    int w = NB * 8 >= 2 * target_waves ? 8 : 16;
+    while (w > 1 && KT < 2 * w) w >>= 1;
     return w;
   }
 };
@@ -231,13 +234,26 @@ GemmP base_gemm(const del_ctx* ctx) {
   return p;
 }
 
+// Matrix-core GEMM whose input split tiles are already in p.Xs.
+del_status gemm_mf(del_ctx* ctx, GemmP p, int epi, int m) {
+  const int waves = ctx->pick_waves(p.NB, p.KT);
+  p.M = m;
+  const int pr = prof_begin(ctx, 1, epi, m, (int64_t)p.NB * p.KT * 1024);
+  HIPCHK(launch_gemm_mfma(p, epi, waves, 1, ctx->stream));
+  prof_end(ctx, pr);
+  return DEL_OK;
+}
+
 // Transformer_l on rows [row0, row0+m) of the hidden buffer; positions T + row0 + i.
-del_status run_layer(del_ctx* ctx, int l, int row0, int m) {
+// `chained`: on the matrix-core path the previous layer of this pass has already left the
+// split tiles of this layer's (gained) input in xs_h and their sums of squares in ssq_h.
+del_status run_layer(del_ctx* ctx, int l, int row0, int m, bool chained) {
   const int li = l - 1;
   const bool mf = ctx->cfg.use_mfma && ctx->wd == DEL_DTYPE_BF16 && m > 1;
   char* base = ctx->arena + (size_t)li * ctx->layer_stride;
   float* hin = ctx->hid_row(l - 1, row0);
   float* hout = ctx->hid_row(l, row0);
+  del_status st;
   // 1. RMSNorm + fused QKV + rotary + KV append
   GemmP p = base_gemm(ctx);
   p.Wt = base + ctx->off_qkv; p.NB = ctx->NBqkv; p.KT = ctx->KTd; p.N = ctx->NBqkv * 16; p.K = ctx->d;
@@ -246,37 +262,70 @@ del_status run_layer(del_ctx* ctx, int l, int row0, int m) {
   p.Kc = ctx->kc + (size_t)li * ctx->kv_layer_bytes; p.Vc = ctx->vc + (size_t)li * ctx->kv_layer_bytes;
   p.n_q = ctx->nq; p.n_kv = ctx->nkv; p.hd = ctx->hd; p.Tcap = ctx->Tcap;
   p.state = ctx->state; p.row_off = row0; p.rope = ctx->rope;
-  del_status st = gemm(ctx, p, EPI_QKV, m, mf);
+  void* Kc = p.Kc; void* Vc = p.Vc;
+  if (mf) {
+    p.Xs = ctx->xs_h;
+    if (chained) {
+      p.ssq_in = ctx->ssq_h; p.ssq_nb = ctx->NBd;
+    } else {
+      HIPCHK(launch_prep_split(hin, m, m, 0, ctx->dpad, ctx->d, ctx->KTd, p.gain, 1, p.eps, ctx->xs_h, ctx->rowscale,
+                               ctx->stream));
+      p.rowscale = ctx->rowscale;
+    }
+    st = gemm_mf(ctx, p, EPI_QKV, m);
+  } else {
+    st = gemm(ctx, p, EPI_QKV, m, false);
+  }
   if (st != DEL_OK) return st;
   // 2. attention over the cache (split over the context) + combine
   AttnP a;
   memset(&a, 0, sizeof(a));
-  a.Q = ctx->q; a.ldq = ctx->qpad; a.Kc = p.Kc; a.Vc = p.Vc; a.kvdtype = ctx->wd;
+  a.Q = ctx->q; a.ldq = ctx->qpad; a.Kc = Kc; a.Vc = Vc; a.kvdtype = ctx->wd;
   a.n_q = ctx->nq; a.n_kv = ctx->nkv; a.hd = ctx->hd; a.Tcap = ctx->Tcap; a.m = m;
   a.state = ctx->state; a.row_off = row0;
   a.PM = ctx->PM; a.PL = ctx->PL; a.PA = ctx->PA; a.nch_max = ctx->nch_max; a.ct = ctx->attn_ct;
   a.O = ctx->attn; a.ldo = ctx->qpad;
+  a.XsOut = mf ? ctx->xs_attn : nullptr;
   HIPCHK(launch_attention(a, ctx->stream));
   // 3. output projection + residual
   p = base_gemm(ctx);
   p.Wt = base + ctx->off_o; p.NB = ctx->NBd; p.KT = ctx->KTq; p.N = ctx->d; p.K = ctx->qdim;
   p.X = ctx->attn; p.ldx = ctx->qpad;
   p.R = hin; p.ldr = ctx->dpad; p.Y = hout; p.ldy = ctx->dpad;
-  st = gemm(ctx, p, EPI_RESID, m, mf);
+  if (mf) {
+    p.Xs = ctx->xs_attn;
+    p.XsOut = ctx->xs_h1; p.gain_out = ctx->gain_ffn(li); p.ssq_out = ctx->ssq_h1;
+    st = gemm_mf(ctx, p, EPI_RESID, m);
+  } else {
+    st = gemm(ctx, p, EPI_RESID, m, false);
+  }
   if (st != DEL_OK) return st;
   // 4. RMSNorm + fused gate/up + SiLU(gate) * up
   p = base_gemm(ctx);
   p.Wt = base + ctx->off_gu; p.NB = ctx->NBgu; p.KT = ctx->KTd; p.N = ctx->NBgu * 16; p.K = ctx->d;
   p.X = hout; p.ldx = ctx->dpad; p.gain = ctx->gain_ffn(li); p.rms = 1;
   p.ACT = ctx->act; p.ldact = ctx->fpad; p.d_ffn = ctx->f;
-  st = gemm(ctx, p, EPI_SWIGLU, m, mf);
+  if (mf) {
+    p.Xs = ctx->xs_h1; p.ssq_in = ctx->ssq_h1; p.ssq_nb = ctx->NBd;
+    p.XsOut = ctx->xs_act;
+    st = gemm_mf(ctx, p, EPI_SWIGLU, m);
+  } else {
+    st = gemm(ctx, p, EPI_SWIGLU, m, false);
+  }
   if (st != DEL_OK) return st;
   // 5. down projection + residual (in place: this row now holds h^l)
   p = base_gemm(ctx);
   p.Wt = base + ctx->off_dn; p.NB = ctx->NBd; p.KT = ctx->KTf; p.N = ctx->d; p.K = ctx->f;
   p.X = ctx->act; p.ldx = ctx->fpad;
   p.R = hout; p.ldr = ctx->dpad; p.Y = hout; p.ldy = ctx->dpad;
-  return gemm(ctx, p, EPI_RESID, m, mf);
+  if (mf) {
+    p.Xs = ctx->xs_act;
+    if (l < ctx->L) {   // leave the next layer's gained input behind as split tiles
+      p.XsOut = ctx->xs_h; p.gain_out = ctx->gain_attn(li + 1); p.ssq_out = ctx->ssq_h;
+    }
+    return gemm_mf(ctx, p, EPI_RESID, m);
+  }
+  return gemm(ctx, p, EPI_RESID, m, false);
 }
 
 GemmP head_gemm(const del_ctx* ctx) {
@@ -327,7 +376,8 @@ del_status shadow_head(del_ctx* ctx, int m) {
 
 void free_all(del_ctx* c) {
   void* ptrs[] = {c->arena, c->embed_t, (c->head_t != c->embed_t) ? c->head_t : nullptr, c->gains, c->kc, c->vc,
-                  c->rope, c->hid, c->q, c->attn, c->act, c->xs_layer, c->xs_shadow, c->rowscale, c->PM, c->PL,
+                  c->rope, c->hid, c->q, c->attn, c->act, c->xs_layer, c->xs_shadow, c->rowscale, c->xs_h, c->xs_attn,
+                  c->xs_h1, c->xs_act, c->ssq_h, c->ssq_h1, c->PM, c->PL,
                   c->PA, c->pval, c->pidx, c->state, c->draft_ids, c->shadow_ids, c->result, c->ids_dev,
                   c->logits_dbg, c->sink, c->stage};
   for (void* p : ptrs)
@@ -468,6 +518,15 @@ del_status del_create(const del_config* cfg, void* hip_stream, del_ctx** out) {
   CK(hipMemsetAsync(ctx->act, 0, (size_t)ctx->maxrows * ctx->fpad * 4, ctx->stream));
   CK(dmalloc(&ctx->xs_layer, (size_t)KTmax * 2048));
   CK(hipMemsetAsync(ctx->xs_layer, 0, (size_t)KTmax * 2048, ctx->stream));
+  {
+    uint16_t** bufs[4] = {&ctx->xs_h, &ctx->xs_attn, &ctx->xs_h1, &ctx->xs_act};
+    for (auto b : bufs) {
+      CK(dmalloc(b, (size_t)KTmax * 2048));
+      CK(hipMemsetAsync(*b, 0, (size_t)KTmax * 2048, ctx->stream));
+    }
+    CK(dmalloc(&ctx->ssq_h, (size_t)16 * ctx->NBd * 4));
+    CK(dmalloc(&ctx->ssq_h1, (size_t)16 * ctx->NBd * 4));
+  }
   const size_t xs_sh = (size_t)ceil_div(Rmax, 16) * ctx->KTd * 2048;
   CK(dmalloc(&ctx->xs_shadow, xs_sh));
   CK(hipMemsetAsync(ctx->xs_shadow, 0, xs_sh, ctx->stream));
@@ -590,7 +649,7 @@ del_status del_prefill(del_ctx* ctx, const int32_t* prompt, int32_t n_prompt, in
     HIPCHK(launch_embed(ctx->embed_t, ctx->wd, ctx->KTd, ctx->V, ctx->ids_dev + start, mc, ctx->hid_row(0, 0),
                         ctx->dpad, ctx->d, ctx->stream));
     for (int l = 1; l <= L; ++l) {
-      del_status st = run_layer(ctx, l, 0, mc);
+      del_status st = run_layer(ctx, l, 0, mc, l > 1);
       if (st != DEL_OK) return st;
     }
     if (start + mc > P - w) {  // overlaps the statistics window
@@ -638,7 +697,7 @@ del_status del_round(del_ctx* ctx, int32_t E, int32_t gamma, int32_t* out_tokens
     const int* tok = i == 0 ? ctx->state + 1 : ctx->draft_ids + (i - 1);
     HIPCHK(launch_embed(ctx->embed_t, ctx->wd, ctx->KTd, ctx->V, tok, 1, ctx->hid_row(0, i), ctx->dpad, ctx->d, s));
     for (int l = 1; l <= E; ++l) {
-      del_status st = run_layer(ctx, l, i, 1);
+      del_status st = run_layer(ctx, l, i, 1, false);
       if (st != DEL_OK) return st;
     }
     if (i < gamma) {  // the last pending token needs no head: only its exit state and KV
@@ -649,7 +708,7 @@ del_status del_round(del_ctx* ctx, int32_t E, int32_t gamma, int32_t* out_tokens
   HIPCHK(hipEventRecord(ctx->ev[1], s));
   // ---- verify: the gamma+1 exit states through layers E+1..L
   for (int l = E + 1; l <= L; ++l) {
-    del_status st = run_layer(ctx, l, 0, m);
+    del_status st = run_layer(ctx, l, 0, m, l > E + 1);
     if (st != DEL_OK) return st;
   }
   HIPCHK(hipEventRecord(ctx->ev[2], s));

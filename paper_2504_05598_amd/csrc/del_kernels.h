@@ -52,6 +52,14 @@ struct GemmP {
   float* ACT; int ldact; int d_ffn;  // SWIGLU
   float* pval; int* pidx;       // ARGMAX partials [rows][NB]
   int prow0;                    // first partial row of this call
+  // matrix-core path only: the epilogue can also emit its result rows as the next GEMM's split
+  // tiles (RESID: value * gain_out[n]; SWIGLU: the activation), plus, for RESID, the sum of
+  // squares of the 16 results per token row (ssq_out[token][NB]) from which the consumer forms
+  // the RMS scale (ssq_in / ssq_nb on its side).
+  uint16_t* XsOut;
+  const float* gain_out;
+  float* ssq_out;
+  const float* ssq_in; int ssq_nb;
 };
 
 struct AttnP {
@@ -63,7 +71,9 @@ struct AttnP {
   float* PM; float* PL; float* PA;  // partials [(mi*n_q+h)][nch_max] (+[hd])
   int nch_max;
   int ct;                       // cache rows per work-group (16, 32, 48 or 64)
+  int qb;                       // query rows per batch (set by the launcher)
   float* O; int ldo;            // combined output [m][n_q*hd]
+  uint16_t* XsOut;              // optional: the same rows as split tiles (input of the O projection)
 };
 
 hipError_t launch_gemm_valu(const GemmP& p, int epi, int waves, hipStream_t s);

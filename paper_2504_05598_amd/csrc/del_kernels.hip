@@ -12,7 +12,7 @@ typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8;
 typedef __attribute__((__vector_size__(4 * sizeof(float)))) float floatx4;
 
 constexpr int MAXW = 16;  // waves per work-group at most
-constexpr int QB = 32;    // query rows per attention batch
+constexpr int QBMAX = 32;  // query rows per attention batch at most
 
 __device__ __forceinline__ float bf16_bits_to_f32(uint32_t h) { return __uint_as_float(h << 16); }
 __device__ __forceinline__ uint16_t f32_to_bf16_rne(float f) {
@@ -42,6 +42,23 @@ template <bool BF16> __device__ __forceinline__ void kv_store(void* base, size_t
   else ((float*)base)[idx] = v;
 }
 
+// Eight consecutive features (a quarter of a 32-wide k tile) of one token row -> hi/lo split tiles.
+// k8 = index of the group of eight (feature / 8).
+__device__ __forceinline__ void split_store8(uint16_t* Xs, int k8, int token, const float* v) {
+  uint32_t hi[4], lo[4];
+#pragma unroll
+  for (int e = 0; e < 8; e += 2) {
+    const uint16_t h0 = f32_to_bf16_rne(v[e]), h1 = f32_to_bf16_rne(v[e + 1]);
+    const uint16_t l0 = f32_to_bf16_rne(v[e] - bf16_bits_to_f32(h0));
+    const uint16_t l1 = f32_to_bf16_rne(v[e + 1] - bf16_bits_to_f32(h1));
+    hi[e >> 1] = (uint32_t)h0 | ((uint32_t)h1 << 16);
+    lo[e >> 1] = (uint32_t)l0 | ((uint32_t)l1 << 16);
+  }
+  uint16_t* d = Xs + (size_t)(k8 >> 2) * 1024 + ((k8 & 3) * 16 + token) * 8;
+  *(uint4*)d = make_uint4(hi[0], hi[1], hi[2], hi[3]);
+  *(uint4*)(d + 512) = make_uint4(lo[0], lo[1], lo[2], lo[3]);
+}
+
 // ---------------------------------------------------------------------------------------
 // Epilogues.  fin[mi][r] holds the finished 16 outputs of row-block nb for token row mi.
 // ---------------------------------------------------------------------------------------
@@ -55,6 +72,30 @@ __device__ __forceinline__ void epilogue(const GemmP& p, int nb, float (*fin)[16
         float v = fin[mi][r];
         if (EPI == EPI_RESID) v += p.R[(size_t)(rowbase + mi) * p.ldr + n];
         p.Y[(size_t)(rowbase + mi) * p.ldy + n] = v;
+        if (EPI == EPI_RESID && p.XsOut) fin[mi][r] = v;   // keep the residual-added value for the split below
+      } else if (EPI == EPI_RESID && p.XsOut) {
+        fin[mi][r] = 0.f;
+      }
+    }
+    if (EPI == EPI_RESID && p.XsOut) {   // rowbase == 0 on this path (one block of <= 16 token rows)
+      __syncthreads();
+      for (int tid = threadIdx.x; tid < m * 2; tid += nthr) {
+        const int mi = tid >> 1, half = tid & 1;
+        float v[8];
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+          const int n = nb * 16 + half * 8 + e;
+          v[e] = fin[mi][half * 8 + e] * (p.gain_out ? p.gain_out[n] : 1.f);
+        }
+        split_store8(p.XsOut, nb * 2 + half, mi, v);
+      }
+      if (p.ssq_out) {
+        for (int tid = threadIdx.x; tid < m; tid += nthr) {
+          float q = 0.f;
+#pragma unroll
+          for (int r = 0; r < 16; ++r) q += fin[tid][r] * fin[tid][r];
+          p.ssq_out[(size_t)tid * p.NB + nb] = q;
+        }
       }
     }
   } else if (EPI == EPI_QKV) {
@@ -89,9 +130,17 @@ __device__ __forceinline__ void epilogue(const GemmP& p, int nb, float (*fin)[16
   } else if (EPI == EPI_SWIGLU) {
     for (int tid = threadIdx.x; tid < m * 8; tid += nthr) {
       const int mi = tid >> 3, r = tid & 7, j = nb * 8 + r;
+      float a = 0.f;
       if (j < p.d_ffn) {
         const float gt = fin[mi][r], up = fin[mi][r + 8];
-        p.ACT[(size_t)(rowbase + mi) * p.ldact + j] = gt / (1.0f + expf(-gt)) * up;
+        a = gt / (1.0f + expf(-gt)) * up;
+        p.ACT[(size_t)(rowbase + mi) * p.ldact + j] = a;
+      }
+      if (p.XsOut) {   // gather the 8 activations of this token row in one lane, store them split
+        float v[8];
+#pragma unroll
+        for (int e = 0; e < 8; ++e) v[e] = __shfl(a, (threadIdx.x & 56) + e);
+        if (r == 0) split_store8(p.XsOut, nb, mi, v);
       }
     }
   } else if (EPI == EPI_ARGMAX) {
@@ -122,7 +171,7 @@ __device__ __forceinline__ uint4 ld_stream(const uint4* p) {
   return make_uint4(v.x, v.y, v.z, v.w);
 }
 
-constexpr int GU = 8;  // tiles in flight per wave and pipeline stage
+constexpr int GU = 4;  // tiles in flight per wave and pipeline stage (x2: current + next)
 
 // ---------------------------------------------------------------------------------------
 // Vector-ALU GEMV (M = 1) / skinny GEMM (M = 2, 4, 8): one work-group per 16-row block; each
@@ -254,6 +303,7 @@ __global__ void __launch_bounds__(1024) gemm_mfma_k(GemmP p) {
   constexpr int U = 4;
   __shared__ float red[MAXW][16][16];
   __shared__ float fin[16][16];
+  __shared__ float scl[16];
   const int tid = threadIdx.x, nw = blockDim.x >> 6, wave = tid >> 6, lane = tid & 63;
   const int nb = blockIdx.x, cb = blockIdx.y;
   const int mvalid = min(16, p.M - cb * 16);
@@ -272,6 +322,14 @@ __global__ void __launch_bounds__(1024) gemm_mfma_k(GemmP p) {
     if (kt < kt_hi) {
       a[u] = ld_stream(wp + (size_t)kt * 64);
       if (ld) { bh[u] = xp[(size_t)kt * 128]; bl[u] = xp[(size_t)kt * 128 + 64]; }
+    }
+  }
+  if (p.ssq_in) {   // RMS scale per token row from the producer's per-block sums of squares
+    for (int mi = wave; mi < mvalid; mi += nw) {
+      float q = 0.f;
+      for (int b = lane; b < p.ssq_nb; b += 64) q += p.ssq_in[(size_t)mi * p.ssq_nb + b];
+      for (int o = 32; o > 0; o >>= 1) q += __shfl_xor(q, o);
+      if (lane == 0) scl[mi] = 1.0f / sqrtf(q / (float)p.K + p.eps);
     }
   }
   for (int kt0 = kt_lo; kt0 < kt_hi; kt0 += U) {
@@ -304,6 +362,7 @@ __global__ void __launch_bounds__(1024) gemm_mfma_k(GemmP p) {
       float s = 0.f;
       for (int w = 0; w < nw; ++w) s += red[w][mi][r];
       if (p.rowscale) s *= p.rowscale[cb * 16 + mi];
+      if (p.ssq_in) s *= scl[mi];
       fin[mi][r] = s;
     }
   }
@@ -367,6 +426,7 @@ __global__ void __launch_bounds__(256) attn_partial_k(AttnP p) {
   if (t0 >= T_end) return;
   const int nt = min(ct, T_end - t0);
   const int hd = p.hd, G = p.n_q / p.n_kv, QR = p.m * G;
+  const int QB = p.qb;        // query rows per batch (LDS is sized for it)
   const int wpr = hd / EPW;   // words per cache row
   const int ksw = wpr + 1;    // padded LDS row stride in words
   const int rb16 = wpr >> 2;  // 16-byte pieces per cache row
@@ -493,7 +553,16 @@ __global__ void __launch_bounds__(128) attn_combine_k(AttnP p) {
     }
   }
   const int mi = row / p.n_q, h = row - mi * p.n_q;
-  p.O[(size_t)mi * p.ldo + h * p.hd + d] = acc / L;
+  const float o = acc / L;
+  p.O[(size_t)mi * p.ldo + h * p.hd + d] = o;
+  if (p.XsOut) {
+    const int k = h * p.hd + d;
+    const uint16_t hi = f32_to_bf16_rne(o);
+    const uint16_t lo = f32_to_bf16_rne(o - bf16_bits_to_f32(hi));
+    uint16_t* dst = p.XsOut + (size_t)(k >> 5) * 1024 + (((k & 31) >> 3) * 16 + mi) * 8 + (k & 7);
+    dst[0] = hi;
+    dst[512] = lo;
+  }
 }
 
 // ---------------------------------------------------------------------------------------
@@ -707,9 +776,9 @@ hipError_t launch_prep_split(const float* src, int rows, int rows_per_group, int
   return hipGetLastError();
 }
 
-static size_t attn_lds_bytes(int hd, int esize, int ct) {
+static size_t attn_lds_bytes(int hd, int esize, int ct, int qb) {
   const int wpr = hd * esize / 4;
-  return (size_t)2 * ct * (wpr + 1) * 4 + (size_t)QB * hd * 4 + (size_t)QB * ct * 4;
+  return (size_t)2 * ct * (wpr + 1) * 4 + (size_t)qb * hd * 4 + (size_t)qb * ct * 4;
 }
 
 hipError_t launch_attention(const AttnP& p, hipStream_t s) {
@@ -719,10 +788,13 @@ hipError_t launch_attention(const AttnP& p, hipStream_t s) {
       p.ct * p.hd * es > 4 * 256 * 16)
     return hipErrorInvalidValue;
   dim3 grid(p.nch_max, p.n_kv), block(256);
+  AttnP q = p;
+  const int QR = p.m * (p.n_q / p.n_kv);
+  q.qb = QR >= QBMAX ? QBMAX : ((QR + 3) & ~3);   // few query rows: less LDS, more work-groups per CU
   if (p.kvdtype == 1)
-    hipLaunchKernelGGL((attn_partial_k<uint16_t>), grid, block, attn_lds_bytes(p.hd, 2, p.ct), s, p);
+    hipLaunchKernelGGL((attn_partial_k<uint16_t>), grid, block, attn_lds_bytes(p.hd, 2, p.ct, q.qb), s, q);
   else
-    hipLaunchKernelGGL((attn_partial_k<float>), grid, block, attn_lds_bytes(p.hd, 4, p.ct), s, p);
+    hipLaunchKernelGGL((attn_partial_k<float>), grid, block, attn_lds_bytes(p.hd, 4, p.ct, q.qb), s, q);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
   hipLaunchKernelGGL(attn_combine_k, dim3(p.m * p.n_q), dim3(128), 0, s, p);
