@@ -157,7 +157,7 @@ del_status del_bench_stream_read(del_ctx* ctx, int64_t bytes, int32_t iters, flo
  * launch with a pair of HIP events on the context's stream and accumulates, per kernel class,
  * the launch count and the summed duration (the events cost a few microseconds per launch, so
  * throughput is measured with profiling off).  A class is one kernel instantiation:
- * flavour (0 vector-ALU, 1 matrix-core), epilogue (0 store, 1 residual, 2 qkv+rotary,
+ * flavour (0 vector-ALU GEMV/GEMM, 1 matrix-core skinny GEMM, 2 shadow-head GEMM), epilogue (0 store, 1 residual, 2 qkv+rotary,
  * 3 swiglu, 4 argmax), rows m.  weight_bytes is what one launch of the class streams. */
 typedef struct {
   int32_t flavour, epilogue, rows, launches;

@@ -281,8 +281,8 @@ class DelContext:
         for e in arr[:min(n.value, cap)]:
             if e.launches:
                 kernel = (f"gemm_valu_k<8,{e.rows},{e.epilogue}>" if e.flavour == 0
-                          else f"gemm_mfma_k<{e.epilogue}>")
-                out.append({"kernel": kernel, "flavour": "valu" if e.flavour == 0 else "mfma",
+                          else f"gemm_mfma_k<{e.epilogue}>" if e.flavour == 1 else "head_gemm_k")
+                out.append({"kernel": kernel, "flavour": ("valu", "mfma", "mfma")[e.flavour],
                             "epilogue": names[e.epilogue], "rows": e.rows, "launches": e.launches,
                             "total_ms": e.total_ms, "avg_us": 1e3 * e.total_ms / e.launches,
                             "weight_bytes": e.weight_bytes})

@@ -351,14 +351,13 @@ del_status head_one(del_ctx* ctx, int layer, int row, int* out_id) {
 del_status shadow_head(del_ctx* ctx, int m) {
   const int R = ctx->L * m;
   const bool mf = ctx->cfg.use_mfma && ctx->wd == DEL_DTYPE_BF16;
+  int nparts = ctx->NBv;
   if (mf) {
     HIPCHK(launch_prep_split(ctx->hid_row(1, 0), R, m, (int64_t)ctx->maxrows * ctx->dpad, ctx->dpad, ctx->d,
                              ctx->KTd, ctx->gain_final(), 1, ctx->cfg.rms_eps, ctx->xs_shadow, ctx->rowscale,
                              ctx->stream));
-    GemmP p = head_gemm(ctx);
-    p.Xs = ctx->xs_shadow; p.rowscale = ctx->rowscale; p.M = R;
-    const int pr = prof_begin(ctx, 1, EPI_ARGMAX, R, (int64_t)p.NB * p.KT * 1024);
-    HIPCHK(launch_gemm_mfma(p, EPI_ARGMAX, ctx->pick_waves(p.NB * ceil_div(R, 16), p.KT), ceil_div(R, 16),
+    const int pr = prof_begin(ctx, 2, EPI_ARGMAX, R, (int64_t)ctx->NBv * ctx->KTd * 1024);
+    HIPCHK(launch_head_gemm(ctx->head_t, ctx->NBv, ctx->KTd, ctx->V, ctx->xs_shadow, R, ctx->pval, ctx->pidx, &nparts,
                             ctx->stream));
     prof_end(ctx, pr);
   } else {
@@ -370,7 +369,7 @@ del_status shadow_head(del_ctx* ctx, int m) {
       if (st != DEL_OK) return st;
     }
   }
-  HIPCHK(launch_argmax_finish(ctx->pval, ctx->pidx, R, ctx->NBv, ctx->shadow_ids, ctx->stream));
+  HIPCHK(launch_argmax_finish(ctx->pval, ctx->pidx, R, nparts, ctx->shadow_ids, ctx->stream));
   return DEL_OK;
 }
 
@@ -462,6 +461,10 @@ del_status del_create(const del_config* cfg, void* hip_stream, del_ctx** out) {
   ctx->attn_ct = 64;
   while (ctx->attn_ct * ctx->hd * ctx->esize > 4 * 256 * 16) ctx->attn_ct -= 16;
   while (ctx->attn_ct > 16 && ctx->nkv * ceil_div(ctx->Tcap, ctx->attn_ct) < 512) ctx->attn_ct -= 16;
+  if (const char* e = getenv("DEL_ATTN_CT")) {   // tuning override: 16, 32, 48 or 64 rows
+    const int v = atoi(e);
+    if (v >= 16 && v <= 64 && v % 16 == 0 && v * ctx->hd * ctx->esize <= 4 * 256 * 16) ctx->attn_ct = v;
+  }
   ctx->nch_max = ceil_div(ctx->Tcap, ctx->attn_ct);
   const int Rmax = ctx->L * ctx->maxrows;
   const int KTmax = std::max(ctx->KTd, std::max(ctx->KTq, ctx->KTf));

@@ -78,6 +78,9 @@ struct AttnP {
 
 hipError_t launch_gemm_valu(const GemmP& p, int epi, int waves, hipStream_t s);
 hipError_t launch_gemm_mfma(const GemmP& p, int epi, int waves, int col_blocks, hipStream_t s);
+// Shadow-head GEMM with fused arg-max over R rows; partials are [R][*n_slabs].
+hipError_t launch_head_gemm(const void* Wt, int NB, int KT, int N, const uint16_t* Xs, int R, float* pval,
+                            int* pidx, int* n_slabs, hipStream_t s);
 hipError_t launch_prep_split(const float* src, int rows, int rows_per_group, int64_t group_stride,
                              int ld, int K, int KT, const float* gain, int rms, float eps,
                              uint16_t* Xs, float* rowscale, hipStream_t s);

@@ -371,6 +371,119 @@ __global__ void __launch_bounds__(1024) gemm_mfma_k(GemmP p) {
 }
 
 // ---------------------------------------------------------------------------------------
+// Shadow-head GEMM with a fused arg-max (Section 4.2: every layer's hidden states through the
+// LM head in one pass): logits of R = L*(gamma+1) rows never leave the chip.  One work-group =
+// 8 waves = a slab of 8 consecutive 16-row blocks of the head, times up to 16 column blocks of
+// 16 token rows (blockIdx.y picks the group of column blocks).  Each wave streams its own row
+// block once (non-temporal); the split activation tiles of the current k tile are staged in
+// LDS (double-buffered) and shared by the 8 waves.  Emits per (row, slab) the best logit and
+// its index; argmax_finish_k merges the slabs.  The positive per-row RMS scale cannot change an
+// arg-max and is left out.
+// ---------------------------------------------------------------------------------------
+constexpr int HG_W = 8, HG_CB = 16;
+
+__global__ void __launch_bounds__(512) head_gemm_k(const uint4* __restrict__ Wt, int NB, int KT, int N,
+                                                   const uint4* __restrict__ Xs, int CB, int R, float* pval, int* pidx,
+                                                   int NS) {
+  extern __shared__ __align__(16) uint4 bs[];   // [2][HG_CB * 128]
+  constexpr int U = 4;
+  const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
+  const int slab = blockIdx.x, cb0 = blockIdx.y * HG_CB;
+  const int ncb = min(HG_CB, CB - cb0);
+  const int nb = slab * HG_W + wave;
+  const bool rowok = nb < NB;
+  const uint4* wp = Wt + (size_t)(rowok ? nb : 0) * KT * 64 + lane;
+  floatx4 acc[HG_CB];
+#pragma unroll
+  for (int c = 0; c < HG_CB; ++c) acc[c] = (floatx4){0.f, 0.f, 0.f, 0.f};
+  uint4 br[4], a[U], an[U];
+  auto loadB = [&](int kt) {
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      const int idx = tid + 512 * j, cbi = idx >> 7;
+      br[j] = cbi < ncb ? Xs[((size_t)(cb0 + cbi) * KT + kt) * 128 + (idx & 127)] : make_uint4(0, 0, 0, 0);
+    }
+  };
+  auto storeB = [&](int buf) {
+#pragma unroll
+    for (int j = 0; j < 4; ++j) bs[buf * (HG_CB * 128) + tid + 512 * j] = br[j];
+  };
+  loadB(0);
+#pragma unroll
+  for (int u = 0; u < U; ++u) a[u] = (rowok && u < KT) ? ld_stream(wp + (size_t)u * 64) : make_uint4(0, 0, 0, 0);
+  storeB(0);
+  __syncthreads();
+  for (int kt0 = 0; kt0 < KT; kt0 += U) {
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      const int kt = kt0 + U + u;
+      an[u] = (rowok && kt < KT) ? ld_stream(wp + (size_t)kt * 64) : make_uint4(0, 0, 0, 0);
+    }
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      const int kt = kt0 + u;
+      if (kt < KT) {
+        const int cur = kt & 1;
+        if (kt + 1 < KT) loadB(kt + 1);
+        const bf16x8 av = __builtin_bit_cast(bf16x8, a[u]);
+        const uint4* bp = bs + cur * (HG_CB * 128) + lane;
+#pragma unroll
+        for (int c = 0; c < HG_CB; ++c) {
+          if (c < ncb) {
+            acc[c] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(av, __builtin_bit_cast(bf16x8, bp[c * 128]), acc[c], 0, 0, 0);
+            acc[c] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(av, __builtin_bit_cast(bf16x8, bp[c * 128 + 64]), acc[c], 0, 0, 0);
+          }
+        }
+        if (kt + 1 < KT) storeB(cur ^ 1);
+        __syncthreads();
+      }
+    }
+#pragma unroll
+    for (int u = 0; u < U; ++u) a[u] = an[u];
+  }
+  // arg-max: lane holds rows 4g+j of its block for token lane%16 of every column block
+  float* wv = (float*)bs;                    // [HG_W][HG_CB][16]
+  int* wi = (int*)(wv + HG_W * HG_CB * 16);
+  const int g = lane >> 4, token = lane & 15;
+#pragma unroll
+  for (int c = 0; c < HG_CB; ++c) {
+    float best = -INFINITY;
+    int bi = 0x7FFFFFFF;
+    if (c < ncb && rowok) {
+#pragma unroll
+      for (int j = 0; j < 4; ++j) {
+        const int n = nb * 16 + 4 * g + j;
+        const float v = acc[c][j];
+        if (n < N && v > best) { best = v; bi = n; }
+      }
+    }
+#pragma unroll
+    for (int o = 16; o < 64; o <<= 1) {
+      const float ov = __shfl_xor(best, o);
+      const int oi = __shfl_xor(bi, o);
+      if (ov > best || (ov == best && oi < bi)) { best = ov; bi = oi; }
+    }
+    if (g == 0) { wv[(wave * HG_CB + c) * 16 + token] = best; wi[(wave * HG_CB + c) * 16 + token] = bi; }
+  }
+  __syncthreads();
+  if (tid < HG_CB * 16) {
+    const int c = tid >> 4, t = tid & 15;
+    const int row = (cb0 + c) * 16 + t;
+    if (c < ncb && row < R) {
+      float best = -INFINITY;
+      int bi = 0x7FFFFFFF;
+      for (int w = 0; w < HG_W; ++w) {   // ascending row blocks: strict > keeps the lowest index
+        const float v = wv[(w * HG_CB + c) * 16 + t];
+        const int ix = wi[(w * HG_CB + c) * 16 + t];
+        if (v > best || (v == best && ix < bi)) { best = v; bi = ix; }
+      }
+      pval[(size_t)row * NS + slab] = best;
+      pidx[(size_t)row * NS + slab] = bi;
+    }
+  }
+}
+
+// ---------------------------------------------------------------------------------------
 // fp32 rows -> bf16 hi/lo split tiles (+ optional gain and inverse RMS per row).
 // One work-group per row.
 // ---------------------------------------------------------------------------------------
@@ -437,6 +550,22 @@ __global__ void __launch_bounds__(256) attn_partial_k(AttnP p) {
   const uint4* Kg = (const uint4*)((const KVT*)p.Kc + ((size_t)kvh * p.Tcap + t0) * hd);
   const uint4* Vg = (const uint4*)((const KVT*)p.Vc + ((size_t)kvh * p.Tcap + t0) * hd);
   const int npieces = nt * rb16;
+  const float scale = 1.0f / sqrtf((float)hd);
+  // few query rows (decode): fetch them now, together with K and V
+  const bool qfast = QR * hd <= 4 * 256;
+  float qreg[4];
+  if (qfast) {
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      const int i = tid + 256 * j;
+      qreg[j] = 0.f;
+      if (i < QR * hd) {
+        const int qi = i / hd, d = i - qi * hd;
+        const int mi = qi / G, gi = qi - mi * G;
+        qreg[j] = p.Q[(size_t)mi * p.ldq + (kvh * G + gi) * hd + d] * scale;
+      }
+    }
+  }
   uint4 kr[NLD], vr[NLD];
 #pragma unroll
   for (int j = 0; j < NLD; ++j) {
@@ -455,17 +584,25 @@ __global__ void __launch_bounds__(256) attn_partial_k(AttnP p) {
       vd[0] = vr[j].x; vd[1] = vr[j].y; vd[2] = vr[j].z; vd[3] = vr[j].w;
     }
   }
-  const float scale = 1.0f / sqrtf((float)hd);
+  if (qfast) {
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      const int i = tid + 256 * j;
+      if (i < QR * hd) Qs[i] = qreg[j];
+    }
+  }
   const int dpairs = hd >> 1;          // PV step: one thread per pair of value dims
   const int nslots = 256 / dpairs;     // query rows processed side by side in the PV step
   const int d2 = tid % dpairs, qslot = tid / dpairs;
   for (int qb = 0; qb < QR; qb += QB) {
     const int nq = min(QB, QR - qb);
-    __syncthreads();
-    for (int i = tid; i < nq * hd; i += 256) {
-      const int qi = i / hd, d = i - qi * hd;
-      const int qr = qb + qi, mi = qr / G, gi = qr - mi * G;
-      Qs[qi * hd + d] = p.Q[(size_t)mi * p.ldq + (kvh * G + gi) * hd + d] * scale;
+    if (!qfast) {
+      __syncthreads();
+      for (int i = tid; i < nq * hd; i += 256) {
+        const int qi = i / hd, d = i - qi * hd;
+        const int qr = qb + qi, mi = qr / G, gi = qr - mi * G;
+        Qs[qi * hd + d] = p.Q[(size_t)mi * p.ldq + (kvh * G + gi) * hd + d] * scale;
+      }
     }
     __syncthreads();
     // scores: one (query row, cache row) pair per thread and step
@@ -541,16 +678,19 @@ __global__ void __launch_bounds__(128) attn_combine_k(AttnP p) {
   const int nch = (T_end + p.ct - 1) / p.ct;
   const float* pm = p.PM + (size_t)row * p.nch_max;
   const float* pl = p.PL + (size_t)row * p.nch_max;
+  const float* pa = p.PA + (size_t)row * p.nch_max * p.hd + d;
+  // every chunk below nch has written its partial (fully masked ones: max = -inf, sum = 0, values = 0),
+  // so the loops are branch-free and their loads independent
   float M = -INFINITY;
+#pragma unroll 8
   for (int c = 0; c < nch; ++c) M = fmaxf(M, pm[c]);
   float L = 0.f, acc = 0.f;
+#pragma unroll 8
   for (int c = 0; c < nch; ++c) {
     const float mc = pm[c];
-    if (mc > -INFINITY) {
-      const float w = expf(mc - M);
-      L += w * pl[c];
-      acc += w * p.PA[((size_t)row * p.nch_max + c) * p.hd + d];
-    }
+    const float w = mc > -INFINITY ? expf(mc - M) : 0.f;
+    L += w * pl[c];
+    acc += w * pa[(size_t)c * p.hd];
   }
   const int mi = row / p.n_q, h = row - mi * p.n_q;
   const float o = acc / L;
@@ -764,6 +904,23 @@ hipError_t launch_gemm_mfma(const GemmP& p, int epi, int waves, int col_blocks, 
     case EPI_ARGMAX: hipLaunchKernelGGL((gemm_mfma_k<EPI_ARGMAX>), grid, block, 0, s, p); break;
     default: return hipErrorInvalidValue;
   }
+  return hipGetLastError();
+}
+
+hipError_t launch_head_gemm(const void* Wt, int NB, int KT, int N, const uint16_t* Xs, int R, float* pval, int* pidx,
+                            int* n_slabs, hipStream_t s) {
+  if (NB <= 0 || KT <= 0 || R <= 0) return hipErrorInvalidValue;
+  const int CB = (R + 15) / 16, NS = (NB + HG_W - 1) / HG_W;
+  const size_t lds = (size_t)2 * HG_CB * 128 * sizeof(uint4);
+  static bool raised = false;
+  if (!raised) {
+    hipError_t e = hipFuncSetAttribute((const void*)head_gemm_k, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+    if (e != hipSuccess) return e;
+    raised = true;
+  }
+  hipLaunchKernelGGL(head_gemm_k, dim3(NS, (CB + HG_CB - 1) / HG_CB), dim3(512), lds, s, (const uint4*)Wt, NB, KT, N,
+                     (const uint4*)Xs, CB, R, pval, pidx, NS);
+  *n_slabs = NS;
   return hipGetLastError();
 }
 
