@@ -144,6 +144,7 @@ def main():
     torch.cuda.synchronize()
     vanilla_tps = nv / (time.perf_counter() - t0)
     stream_gbs = ctx.stream_read_gbps(min(4 << 30, cfg.layer_weight_bytes() * cfg.n_layers), 10)
+    copy_gbs = ctx.stream_copy_gbps(1 << 30, 5)     # also the known-size kernel for counter calibration
 
     result = {
         "metric": "accepted tokens/sec at batch 1 (Llama-2-7B shape)",
@@ -177,7 +178,7 @@ def main():
             "mean_gamma": round(sum(r[1] for r in recs) / len(recs), 2),
             "vanilla_tokens_per_s": round(vanilla_tps, 2),
             "speedup_over_vanilla": round(value / vanilla_tps, 3),
-            "stream_read_GBs": round(stream_gbs, 1),
+            "stream_read_GBs": round(stream_gbs, 1), "stream_copy_GBs": round(copy_gbs, 1),
             "paper_speedup_over_autoregressive": "2.16-2.62x on A100-40G / 2xH100-PCIe (context only)",
         },
         "kernels": {n: {"launches": k["launches"], "avg_us": round(1e3 * k["total_ms"] / k["launches"], 2),

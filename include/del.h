@@ -152,6 +152,9 @@ del_status del_debug_set_pending(del_ctx* ctx, int32_t token);
  * the GEMV kernels' access pattern (sets the achievable-bandwidth ceiling), and
  * the time of the last such call in ms. */
 del_status del_bench_stream_read(del_ctx* ctx, int64_t bytes, int32_t iters, float* ms_per_iter);
+/* A plain device-to-device copy kernel of `bytes` (reads and writes that many bytes of a
+ * temporary buffer): the known-size kernel the profiler's HBM byte counters are scaled by. */
+del_status del_bench_stream_copy(del_ctx* ctx, int64_t bytes, int32_t iters, float* ms_per_iter);
 
 /* Per-kernel timing for the roofline report.  While enabled, del_round brackets every GEMM
  * launch with a pair of HIP events on the context's stream and accumulates, per kernel class,

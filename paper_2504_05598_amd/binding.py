@@ -15,7 +15,7 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 
 EXPORTS = ["del_create", "del_destroy", "del_load_weights", "del_prefill", "del_round",
            "del_layer_stats", "del_set_layer_stats", "del_last_timings", "del_debug_hidden",
-           "del_debug_logits", "del_debug_state", "del_debug_set_pending", "del_profile_enable", "del_profile_read", "del_bench_stream_read", "del_strerror",
+           "del_debug_logits", "del_debug_state", "del_debug_set_pending", "del_profile_enable", "del_profile_read", "del_bench_stream_read", "del_bench_stream_copy", "del_strerror",
            "del_last_error_text"]
 
 DEL_DTYPE_FP32, DEL_DTYPE_BF16 = 0, 1
@@ -94,6 +94,7 @@ def load_library():
     lib.del_profile_enable.argtypes = [C.c_void_p, C.c_int32]
     lib.del_profile_read.argtypes = [C.c_void_p, P(del_prof_entry), C.c_int32, P(C.c_int32)]
     lib.del_bench_stream_read.argtypes = [C.c_void_p, C.c_int64, C.c_int32, P(C.c_float)]
+    lib.del_bench_stream_copy.argtypes = [C.c_void_p, C.c_int64, C.c_int32, P(C.c_float)]
     lib.del_strerror.argtypes = [C.c_int]
     lib.del_strerror.restype = C.c_char_p
     lib.del_last_error_text.argtypes = [C.c_void_p]
@@ -287,6 +288,12 @@ class DelContext:
                             "total_ms": e.total_ms, "avg_us": 1e3 * e.total_ms / e.launches,
                             "weight_bytes": e.weight_bytes})
         return out
+
+    def stream_copy_gbps(self, nbytes: int, iters: int = 10) -> float:
+        """GB/s of a plain copy kernel counting bytes read plus bytes written."""
+        ms = C.c_float()
+        _check(load_library().del_bench_stream_copy(self.ctx, nbytes, iters, C.byref(ms)), self.ctx)
+        return 2 * nbytes / (ms.value * 1e-3) / 1e9
 
     def stream_read_gbps(self, nbytes: int, iters: int = 20) -> float:
         ms = C.c_float()

@@ -700,7 +700,7 @@ del_status del_round(del_ctx* ctx, int32_t E, int32_t gamma, int32_t* out_tokens
     const int* tok = i == 0 ? ctx->state + 1 : ctx->draft_ids + (i - 1);
     HIPCHK(launch_embed(ctx->embed_t, ctx->wd, ctx->KTd, ctx->V, tok, 1, ctx->hid_row(0, i), ctx->dpad, ctx->d, s));
     for (int l = 1; l <= E; ++l) {
-      del_status st = run_layer(ctx, l, i, 1, false);
+      del_status st = run_layer(ctx, l, i, 1, l > 1);
       if (st != DEL_OK) return st;
     }
     if (i < gamma) {  // the last pending token needs no head: only its exit state and KV
@@ -853,6 +853,24 @@ del_status del_bench_stream_read(del_ctx* ctx, int64_t bytes, int32_t iters, flo
   HIPCHK(hipStreamSynchronize(ctx->stream));
   float ms = 0.f;
   HIPCHK(hipEventElapsedTime(&ms, ctx->ev[0], ctx->ev[1]));
+  *ms_per_iter = ms / iters;
+  return DEL_OK;
+}
+
+del_status del_bench_stream_copy(del_ctx* ctx, int64_t bytes, int32_t iters, float* ms_per_iter) {
+  if (!ctx || !ms_per_iter || iters < 1 || bytes < 1024) return DEL_E_ARG;
+  char* buf = nullptr;
+  HIPCHK(hipMalloc((void**)&buf, (size_t)bytes * 2));
+  hipError_t e = hipMemsetAsync(buf, 1, (size_t)bytes * 2, ctx->stream);
+  if (e == hipSuccess) e = launch_stream_copy(buf, buf + bytes, bytes, ctx->stream);
+  if (e == hipSuccess) e = hipEventRecord(ctx->ev[0], ctx->stream);
+  for (int i = 0; i < iters && e == hipSuccess; ++i) e = launch_stream_copy(buf, buf + bytes, bytes, ctx->stream);
+  if (e == hipSuccess) e = hipEventRecord(ctx->ev[1], ctx->stream);
+  if (e == hipSuccess) e = hipStreamSynchronize(ctx->stream);
+  float ms = 0.f;
+  if (e == hipSuccess) e = hipEventElapsedTime(&ms, ctx->ev[0], ctx->ev[1]);
+  (void)hipFree(buf);
+  if (e != hipSuccess) return ctx->fail(e, "del_bench_stream_copy");
   *ms_per_iter = ms / iters;
   return DEL_OK;
 }

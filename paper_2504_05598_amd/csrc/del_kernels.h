@@ -96,6 +96,7 @@ hipError_t launch_set_state(int* state, int add_T, int set_T, const int* pending
 hipError_t launch_tile_scatter(const void* src, int wdtype, int64_t row0, int64_t nrows, int64_t cols,
                                int map, int vbase, int hd, void* dst, int KT, hipStream_t s);
 hipError_t launch_pad_gain(const float* src, int K, float* dst, int Kpad, hipStream_t s);
+hipError_t launch_stream_copy(const void* src, void* dst, int64_t bytes, hipStream_t s);
 hipError_t launch_stream_read(const void* base, int64_t bytes, float* sink, hipStream_t s);
 
 

@@ -59,7 +59,7 @@ def _first_divergence_is_near_tie(ctx, cfg, prompt, a, b):
     return n
 
 
-@pytest.mark.parametrize("name,n", [("llama1b", 96), ("llama7b", 64)])
+@pytest.mark.parametrize("name,n", [("llama1b", 96), ("llama7b", 64), ("llama13b", 40), ("llama70b", 20)])
 @pytest.mark.timeout(600)
 def test_speculative_equals_autoregressive_on_gpu(name, n):
     from gpu_harness import gpu_context, gpu_generate, log
