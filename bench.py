@@ -41,6 +41,21 @@ def round_bytes(cfg, E, gamma, T):
     return (gamma * E + L) * b_layer + (gamma + 1) * b_head + kv_read + kv_write + hidden
 
 
+def measured_traffic(cfg_name, kernel):
+    """HBM bytes per launch of `kernel` from the committed rocprofv3 PMC summary (FETCH_SIZE and
+    WRITE_SIZE, each scaled by a plain copy kernel of known size), or None if there is none."""
+    path = os.path.join(os.path.dirname(os.path.abspath(__file__)), "profiles",
+                        f"bench_{cfg_name}_hbm_traffic.txt")
+    try:
+        for line in open(path):
+            parts = line.split()
+            if len(parts) == 3 and parts[0] == "traffic_bytes_per_launch" and parts[1] == kernel:
+                return int(float(parts[2]))
+    except OSError:
+        pass
+    return None
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -165,7 +180,7 @@ def main():
                    "tokens_in_timed_region": tokens, "prefill_s": round(prefill_s, 3)},
         "roofline": {
             "bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
-            "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": None,
+            "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": measured_traffic(cfg.name, dom_name),
             "kernel": dom_name, "bytes_per_launch": int(dom_bytes), "avg_launch_us": round(dom_us, 2),
             "launches": dom["launches"],
         },
