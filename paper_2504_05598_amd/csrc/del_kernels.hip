@@ -340,20 +340,23 @@ __global__ void __launch_bounds__(1024) gemm_mfma_k(GemmP p) {
   const int nb = blockIdx.x, cb = blockIdx.y;
   const int mvalid = min(16, p.M - cb * 16);
   const int token = lane & 15, g = lane >> 4;
-  const uint4* wp = (const uint4*)p.Wt + (size_t)nb * p.KT * 64 + lane;
-  const uint4* xp = (const uint4*)p.Xs + (size_t)cb * p.KT * 128 + lane;
-  const bool ld = token < mvalid;
+  // Lanes of token rows beyond the valid ones read the tile of token row 0 of their k group
+  // (same cache lines as the active lanes, no extra traffic, no divergent loads); their output
+  // columns are never used.
+  const int blane = token < mvalid ? lane : (lane & 48);
   const int per = (p.KT + nw - 1) / nw;
-  const int kt_lo = wave * per, kt_hi = min(p.KT, kt_lo + per);
+  const int kt_lo = min(p.KT, wave * per), kt_hi = min(p.KT, kt_lo + per);
+  const int ngroups = (kt_hi - kt_lo) / U;
+  const uint4* wp = (const uint4*)p.Wt + ((size_t)nb * p.KT + kt_lo) * 64 + lane;
+  const uint4* xp = (const uint4*)p.Xs + ((size_t)cb * p.KT + kt_lo) * 128 + blane;
   floatx4 acc = {0.f, 0.f, 0.f, 0.f}, acc2 = {0.f, 0.f, 0.f, 0.f};   // hi and lo products, independent chains
   uint4 a[U], bh[U], bl[U], an[U], bhn[U], bln[U];
+  if (ngroups > 0) {
 #pragma unroll
-  for (int u = 0; u < U; ++u) {
-    const int kt = kt_lo + u;
-    a[u] = bh[u] = bl[u] = make_uint4(0, 0, 0, 0);
-    if (kt < kt_hi) {
-      a[u] = ld_stream(wp + (size_t)kt * 64);
-      if (ld) { bh[u] = xp[(size_t)kt * 128]; bl[u] = xp[(size_t)kt * 128 + 64]; }
+    for (int u = 0; u < U; ++u) {
+      a[u] = ld_stream(wp + u * 64);
+      bh[u] = xp[u * 128];
+      bl[u] = xp[u * 128 + 64];
     }
   }
   if (p.ssq_in) {   // RMS scale per token row from the producer's per-block sums of squares
@@ -364,15 +367,15 @@ __global__ void __launch_bounds__(1024) gemm_mfma_k(GemmP p) {
       if (lane == 0) scl[mi] = 1.0f / sqrtf(q / (float)p.K + p.eps);
     }
   }
-  for (int kt0 = kt_lo; kt0 < kt_hi; kt0 += U) {
+  // steady state: branch-free
+  for (int gi = 0; gi + 1 < ngroups; ++gi) {
+    const uint4* wn = wp + (size_t)(gi + 1) * U * 64;
+    const uint4* xn = xp + (size_t)(gi + 1) * U * 128;
 #pragma unroll
     for (int u = 0; u < U; ++u) {
-      const int kt = kt0 + U + u;
-      an[u] = bhn[u] = bln[u] = make_uint4(0, 0, 0, 0);
-      if (kt < kt_hi) {
-        an[u] = ld_stream(wp + (size_t)kt * 64);
-        if (ld) { bhn[u] = xp[(size_t)kt * 128]; bln[u] = xp[(size_t)kt * 128 + 64]; }
-      }
+      an[u] = ld_stream(wn + u * 64);
+      bhn[u] = xn[u * 128];
+      bln[u] = xn[u * 128 + 64];
     }
 #pragma unroll
     for (int u = 0; u < U; ++u) {
@@ -382,6 +385,21 @@ __global__ void __launch_bounds__(1024) gemm_mfma_k(GemmP p) {
     }
 #pragma unroll
     for (int u = 0; u < U; ++u) { a[u] = an[u]; bh[u] = bhn[u]; bl[u] = bln[u]; }
+  }
+  if (ngroups > 0) {
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      const bf16x8 av = __builtin_bit_cast(bf16x8, a[u]);
+      acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(av, __builtin_bit_cast(bf16x8, bh[u]), acc, 0, 0, 0);
+      acc2 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(av, __builtin_bit_cast(bf16x8, bl[u]), acc2, 0, 0, 0);
+    }
+  }
+  for (int kt = kt_lo + ngroups * U; kt < kt_hi; ++kt) {
+    const uint4 aw = ld_stream(wp + (size_t)(kt - kt_lo) * 64);
+    const uint4 h = xp[(size_t)(kt - kt_lo) * 128], l = xp[(size_t)(kt - kt_lo) * 128 + 64];
+    const bf16x8 av = __builtin_bit_cast(bf16x8, aw);
+    acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(av, __builtin_bit_cast(bf16x8, h), acc, 0, 0, 0);
+    acc2 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(av, __builtin_bit_cast(bf16x8, l), acc2, 0, 0, 0);
   }
 #pragma unroll
   for (int j = 0; j < 4; ++j) acc[j] += acc2[j];
@@ -425,12 +443,15 @@ __global__ void __launch_bounds__(512) head_gemm_k(const uint4* __restrict__ Wt,
   const int ncb = min(HG_CB, CB - cb0);
   const int nb = slab * HG_W + wave;
   const bool rowok = nb < NB;
-  const uint4* wp = Wt + (size_t)(rowok ? nb : 0) * KT * 64 + lane;
+  // loads are unconditional (clamped addresses) so that the steady-state loop has no branches
+  // around memory operations; a wave beyond the last row block re-reads that block and its
+  // candidates are masked below
+  const uint4* wp = Wt + (size_t)(rowok ? nb : NB - 1) * KT * 64 + lane;
   floatx4 acc[HG_CB];
 #pragma unroll
   for (int c = 0; c < HG_CB; ++c) acc[c] = (floatx4){0.f, 0.f, 0.f, 0.f};
   uint4 br[4], a[U], an[U];
-  auto loadB = [&](int kt) {
+  auto loadB = [&](int kt) {   // column blocks beyond ncb are not fetched (the condition is wave-uniform)
 #pragma unroll
     for (int j = 0; j < 4; ++j) {
       const int idx = tid + 512 * j, cbi = idx >> 7;
@@ -441,38 +462,46 @@ __global__ void __launch_bounds__(512) head_gemm_k(const uint4* __restrict__ Wt,
 #pragma unroll
     for (int j = 0; j < 4; ++j) bs[buf * (HG_CB * 128) + tid + 512 * j] = br[j];
   };
-  loadB(0);
+  // one k tile: prefetch the next activation tiles, multiply, hand them over through LDS
+  auto tile = [&](const uint4& aw, int kt) {
+    const int cur = kt & 1;
+    loadB(min(kt + 1, KT - 1));
+    const bf16x8 av = __builtin_bit_cast(bf16x8, aw);
+    const uint4* bp = bs + cur * (HG_CB * 128) + lane;
 #pragma unroll
-  for (int u = 0; u < U; ++u) a[u] = (rowok && u < KT) ? ld_stream(wp + (size_t)u * 64) : make_uint4(0, 0, 0, 0);
-  storeB(0);
-  __syncthreads();
-  for (int kt0 = 0; kt0 < KT; kt0 += U) {
-#pragma unroll
-    for (int u = 0; u < U; ++u) {
-      const int kt = kt0 + U + u;
-      an[u] = (rowok && kt < KT) ? ld_stream(wp + (size_t)kt * 64) : make_uint4(0, 0, 0, 0);
-    }
-#pragma unroll
-    for (int u = 0; u < U; ++u) {
-      const int kt = kt0 + u;
-      if (kt < KT) {
-        const int cur = kt & 1;
-        if (kt + 1 < KT) loadB(kt + 1);
-        const bf16x8 av = __builtin_bit_cast(bf16x8, a[u]);
-        const uint4* bp = bs + cur * (HG_CB * 128) + lane;
-#pragma unroll
-        for (int c = 0; c < HG_CB; ++c) {
-          if (c < ncb) {
-            acc[c] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(av, __builtin_bit_cast(bf16x8, bp[c * 128]), acc[c], 0, 0, 0);
-            acc[c] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(av, __builtin_bit_cast(bf16x8, bp[c * 128 + 64]), acc[c], 0, 0, 0);
-          }
-        }
-        if (kt + 1 < KT) storeB(cur ^ 1);
-        __syncthreads();
+    for (int c = 0; c < HG_CB; ++c) {
+      if (c < ncb) {
+        acc[c] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(av, __builtin_bit_cast(bf16x8, bp[c * 128]), acc[c], 0, 0, 0);
+        acc[c] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(av, __builtin_bit_cast(bf16x8, bp[c * 128 + 64]), acc[c], 0, 0, 0);
       }
     }
+    storeB(cur ^ 1);
+    __syncthreads();
+  };
+  const int ngroups = KT / U;
+  loadB(0);
+  if (ngroups > 0) {
+#pragma unroll
+    for (int u = 0; u < U; ++u) a[u] = ld_stream(wp + u * 64);
+  }
+  storeB(0);
+  __syncthreads();
+  for (int gi = 0; gi + 1 < ngroups; ++gi) {
+    const uint4* wn = wp + (size_t)(gi + 1) * U * 64;
+#pragma unroll
+    for (int u = 0; u < U; ++u) an[u] = ld_stream(wn + u * 64);
+#pragma unroll
+    for (int u = 0; u < U; ++u) tile(a[u], gi * U + u);
 #pragma unroll
     for (int u = 0; u < U; ++u) a[u] = an[u];
+  }
+  if (ngroups > 0) {
+#pragma unroll
+    for (int u = 0; u < U; ++u) tile(a[u], (ngroups - 1) * U + u);
+  }
+  for (int kt = ngroups * U; kt < KT; ++kt) {
+    const uint4 aw = ld_stream(wp + (size_t)kt * 64);
+    tile(aw, kt);
   }
   // arg-max: lane holds rows 4g+j of its block for token lane%16 of every column block
   float* wv = (float*)bs;                    // [HG_W][HG_CB][16]
