@@ -156,10 +156,10 @@ del_status del_bench_stream_read(del_ctx* ctx, int64_t bytes, int32_t iters, flo
  * temporary buffer): the known-size kernel the profiler's HBM byte counters are scaled by. */
 del_status del_bench_stream_copy(del_ctx* ctx, int64_t bytes, int32_t iters, float* ms_per_iter);
 
-/* Per-kernel timing for the roofline report.  While enabled, del_round brackets every GEMM
- * launch with a pair of HIP events on the context's stream and accumulates, per kernel class,
- * the launch count and the summed duration (the events cost a few microseconds per launch, so
- * throughput is measured with profiling off).  A class is one kernel instantiation:
+/* Per-kernel timing for the roofline report.  While enabled, every GEMM launch of del_round
+ * carries a pair of HIP events that receive the kernel's own start and stop timestamps
+ * (hipExtLaunchKernel); per kernel class the launch count and the summed duration are
+ * accumulated (throughput is still measured with profiling off).  A class is one kernel instantiation:
  * flavour (0 vector-ALU GEMV/GEMM, 1 matrix-core skinny GEMM, 2 shadow-head GEMM), epilogue (0 store, 1 residual, 2 qkv+rotary,
  * 3 swiglu, 4 argmax), rows m.  weight_bytes is what one launch of the class streams. */
 typedef struct {

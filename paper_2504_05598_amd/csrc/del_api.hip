@@ -168,13 +168,12 @@ int prof_begin(del_ctx* ctx, int flavour, int epi, int rows, int64_t bytes) {
     ctx->prof_cls.push_back(cls);
   }
   ctx->prof_cls[pair] = cls;
-  if (hipEventRecord(ctx->prof_ev[2 * pair], ctx->stream) != hipSuccess) return -1;
   return pair;
 }
 
+// the launch itself stamps the pair with the kernel's own start and stop times
 void prof_end(del_ctx* ctx, int pair) {
-  if (pair < 0) return;
-  if (hipEventRecord(ctx->prof_ev[2 * pair + 1], ctx->stream) == hipSuccess) ctx->prof_used = pair + 1;
+  if (pair >= 0) ctx->prof_used = pair + 1;
 }
 
 // after a stream synchronisation: fold the recorded pairs into the class totals
@@ -201,6 +200,7 @@ del_status gemm(del_ctx* ctx, GemmP p, int epi, int m, bool mfma) {
     p.rowscale = p.rms ? ctx->rowscale : nullptr;
     p.M = m;
     const int pr = prof_begin(ctx, 1, epi, m, wbytes);
+    if (pr >= 0) { p.ev_start = ctx->prof_ev[2 * pr]; p.ev_stop = ctx->prof_ev[2 * pr + 1]; }
     HIPCHK(launch_gemm_mfma(p, epi, waves, 1, ctx->stream));
     prof_end(ctx, pr);
     return DEL_OK;
@@ -219,6 +219,7 @@ del_status gemm(del_ctx* ctx, GemmP p, int epi, int m, bool mfma) {
     q.row_off = p.row_off + off;
     q.prow0 = p.prow0 + off;
     const int pr = prof_begin(ctx, 0, epi, g, wbytes);
+    if (pr >= 0) { q.ev_start = ctx->prof_ev[2 * pr]; q.ev_stop = ctx->prof_ev[2 * pr + 1]; }
     HIPCHK(launch_gemm_valu(q, epi, waves, ctx->stream));
     prof_end(ctx, pr);
     off += g;
@@ -239,6 +240,7 @@ del_status gemm_mf(del_ctx* ctx, GemmP p, int epi, int m) {
   const int waves = ctx->pick_waves(p.NB, p.KT);
   p.M = m;
   const int pr = prof_begin(ctx, 1, epi, m, (int64_t)p.NB * p.KT * 1024);
+  if (pr >= 0) { p.ev_start = ctx->prof_ev[2 * pr]; p.ev_stop = ctx->prof_ev[2 * pr + 1]; }
   HIPCHK(launch_gemm_mfma(p, epi, waves, 1, ctx->stream));
   prof_end(ctx, pr);
   return DEL_OK;
@@ -358,7 +360,8 @@ del_status shadow_head(del_ctx* ctx, int m) {
                              ctx->stream));
     const int pr = prof_begin(ctx, 2, EPI_ARGMAX, R, (int64_t)ctx->NBv * ctx->KTd * 1024);
     HIPCHK(launch_head_gemm(ctx->head_t, ctx->NBv, ctx->KTd, ctx->V, ctx->xs_shadow, R, ctx->pval, ctx->pidx, &nparts,
-                            ctx->stream));
+                            ctx->stream, pr >= 0 ? ctx->prof_ev[2 * pr] : nullptr,
+                            pr >= 0 ? ctx->prof_ev[2 * pr + 1] : nullptr));
     prof_end(ctx, pr);
   } else {
     for (int l = 1; l <= ctx->L; ++l) {

@@ -60,6 +60,9 @@ struct GemmP {
   const float* gain_out;
   float* ssq_out;
   const float* ssq_in; int ssq_nb;
+  // host side only: when both are set the launch records the kernel's own start and stop
+  // timestamps into these events (per-kernel profiling)
+  hipEvent_t ev_start, ev_stop;
 };
 
 struct AttnP {
@@ -80,7 +83,8 @@ hipError_t launch_gemm_valu(const GemmP& p, int epi, int waves, hipStream_t s);
 hipError_t launch_gemm_mfma(const GemmP& p, int epi, int waves, int col_blocks, hipStream_t s);
 // Shadow-head GEMM with fused arg-max over R rows; partials are [R][*n_slabs].
 hipError_t launch_head_gemm(const void* Wt, int NB, int KT, int N, const uint16_t* Xs, int R, float* pval,
-                            int* pidx, int* n_slabs, hipStream_t s);
+                            int* pidx, int* n_slabs, hipStream_t s, hipEvent_t ev_start = nullptr,
+                            hipEvent_t ev_stop = nullptr);
 hipError_t launch_prep_split(const float* src, int rows, int rows_per_group, int64_t group_stride,
                              int ld, int K, int KT, const float* gain, int rms, float eps,
                              uint16_t* Xs, float* rowscale, hipStream_t s);

@@ -5,6 +5,7 @@
 // del_kernels.h); activations stay fp32 on the vector path and are split into bf16 hi + lo
 // halves (16 mantissa bits together) on the matrix-core path, accumulating in fp32.
 #include "del_kernels.h"
+#include <hip/hip_ext.h>
 
 namespace del {
 
@@ -886,21 +887,26 @@ __global__ void pad_gain_k(const float* src, int K, float* dst, int Kpad) {
   if (k < Kpad) dst[k] = k < K ? src[k] : 0.f;
 }
 
-// Pure streaming read with the GEMV access pattern (1 KiB per wave per load, 4 in flight).
-__global__ void __launch_bounds__(256) stream_read_k(const uint4* base, long long n_tiles, float* sink) {
+// Pure streaming read with the GEMV access pattern (non-temporal 1 KiB loads per wave, each wave
+// a contiguous span, 8 loads in flight): the achievable-bandwidth ceiling of the weight stream.
+__global__ void __launch_bounds__(512) stream_read_k(const uint4* base, long long n_tiles, float* sink) {
   const int lane = threadIdx.x & 63;
-  const long long wave = ((long long)blockIdx.x * 256 + threadIdx.x) >> 6;
-  const long long n_waves = ((long long)gridDim.x * 256) >> 6;
+  const long long wave = ((long long)blockIdx.x * 512 + threadIdx.x) >> 6;
+  const long long n_waves = ((long long)gridDim.x * 512) >> 6;
+  const long long per = (n_tiles + n_waves - 1) / n_waves;
+  const long long t0 = wave * per, t1 = t0 + per < n_tiles ? t0 + per : n_tiles;
   uint32_t acc = 0;
-  for (long long t = wave; t < n_tiles; t += n_waves * 4) {
-    uint4 v[4];
+  long long t = t0;
+  for (; t + 8 <= t1; t += 8) {
+    uint4 v[8];
 #pragma unroll
-    for (int u = 0; u < 4; ++u) {
-      const long long tt = t + u * n_waves;
-      v[u] = tt < n_tiles ? base[tt * 64 + lane] : make_uint4(0, 0, 0, 0);
-    }
+    for (int u = 0; u < 8; ++u) v[u] = ld_stream(base + (t + u) * 64 + lane);
 #pragma unroll
-    for (int u = 0; u < 4; ++u) acc ^= v[u].x ^ v[u].y ^ v[u].z ^ v[u].w;
+    for (int u = 0; u < 8; ++u) acc ^= v[u].x ^ v[u].y ^ v[u].z ^ v[u].w;
+  }
+  for (; t < t1; ++t) {
+    const uint4 v = ld_stream(base + t * 64 + lane);
+    acc ^= v.x ^ v.y ^ v.z ^ v.w;
   }
   if (acc == 0x9E3779B9u) sink[0] = 1.f;  // practically never; keeps the loads alive
 }
@@ -927,7 +933,10 @@ static hipError_t launch_valu_e(const GemmP& p, int waves, hipStream_t s) {
       raised = lds;
     }
   }
-  hipLaunchKernelGGL((gemm_valu_k<KPL, M, EPI>), grid, block, lds, s, p);
+  if (p.ev_start && p.ev_stop)
+    hipExtLaunchKernelGGL((gemm_valu_k<KPL, M, EPI>), grid, block, (uint32_t)lds, s, p.ev_start, p.ev_stop, 0, p);
+  else
+    hipLaunchKernelGGL((gemm_valu_k<KPL, M, EPI>), grid, block, lds, s, p);
   return hipGetLastError();
 }
 
@@ -964,19 +973,35 @@ hipError_t launch_gemm_mfma(const GemmP& p, int epi, int waves, int col_blocks, 
       p.M > col_blocks * 16 || p.M <= (col_blocks - 1) * 16)
     return hipErrorInvalidValue;
   dim3 grid(p.NB, col_blocks), block(64 * waves);
+  const bool timed = p.ev_start && p.ev_stop;
   switch (epi) {
-    case EPI_STORE: hipLaunchKernelGGL((gemm_mfma_k<EPI_STORE>), grid, block, 0, s, p); break;
-    case EPI_RESID: hipLaunchKernelGGL((gemm_mfma_k<EPI_RESID>), grid, block, 0, s, p); break;
-    case EPI_QKV: hipLaunchKernelGGL((gemm_mfma_k<EPI_QKV>), grid, block, 0, s, p); break;
-    case EPI_SWIGLU: hipLaunchKernelGGL((gemm_mfma_k<EPI_SWIGLU>), grid, block, 0, s, p); break;
-    case EPI_ARGMAX: hipLaunchKernelGGL((gemm_mfma_k<EPI_ARGMAX>), grid, block, 0, s, p); break;
+    case EPI_STORE:
+      if (timed) hipExtLaunchKernelGGL((gemm_mfma_k<EPI_STORE>), grid, block, 0, s, p.ev_start, p.ev_stop, 0, p);
+      else hipLaunchKernelGGL((gemm_mfma_k<EPI_STORE>), grid, block, 0, s, p);
+      break;
+    case EPI_RESID:
+      if (timed) hipExtLaunchKernelGGL((gemm_mfma_k<EPI_RESID>), grid, block, 0, s, p.ev_start, p.ev_stop, 0, p);
+      else hipLaunchKernelGGL((gemm_mfma_k<EPI_RESID>), grid, block, 0, s, p);
+      break;
+    case EPI_QKV:
+      if (timed) hipExtLaunchKernelGGL((gemm_mfma_k<EPI_QKV>), grid, block, 0, s, p.ev_start, p.ev_stop, 0, p);
+      else hipLaunchKernelGGL((gemm_mfma_k<EPI_QKV>), grid, block, 0, s, p);
+      break;
+    case EPI_SWIGLU:
+      if (timed) hipExtLaunchKernelGGL((gemm_mfma_k<EPI_SWIGLU>), grid, block, 0, s, p.ev_start, p.ev_stop, 0, p);
+      else hipLaunchKernelGGL((gemm_mfma_k<EPI_SWIGLU>), grid, block, 0, s, p);
+      break;
+    case EPI_ARGMAX:
+      if (timed) hipExtLaunchKernelGGL((gemm_mfma_k<EPI_ARGMAX>), grid, block, 0, s, p.ev_start, p.ev_stop, 0, p);
+      else hipLaunchKernelGGL((gemm_mfma_k<EPI_ARGMAX>), grid, block, 0, s, p);
+      break;
     default: return hipErrorInvalidValue;
   }
   return hipGetLastError();
 }
 
 hipError_t launch_head_gemm(const void* Wt, int NB, int KT, int N, const uint16_t* Xs, int R, float* pval, int* pidx,
-                            int* n_slabs, hipStream_t s) {
+                            int* n_slabs, hipStream_t s, hipEvent_t ev_start, hipEvent_t ev_stop) {
   if (NB <= 0 || KT <= 0 || R <= 0) return hipErrorInvalidValue;
   const int CB = (R + 15) / 16, NS = (NB + HG_W - 1) / HG_W;
   const size_t lds = (size_t)2 * HG_CB * 128 * sizeof(uint4);
@@ -986,8 +1011,12 @@ hipError_t launch_head_gemm(const void* Wt, int NB, int KT, int N, const uint16_
     if (e != hipSuccess) return e;
     raised = true;
   }
-  hipLaunchKernelGGL(head_gemm_k, dim3(NS, (CB + HG_CB - 1) / HG_CB), dim3(512), lds, s, (const uint4*)Wt, NB, KT, N,
-                     (const uint4*)Xs, CB, R, pval, pidx, NS);
+  if (ev_start && ev_stop)
+    hipExtLaunchKernelGGL(head_gemm_k, dim3(NS, (CB + HG_CB - 1) / HG_CB), dim3(512), (uint32_t)lds, s, ev_start, ev_stop,
+                          0, (const uint4*)Wt, NB, KT, N, (const uint4*)Xs, CB, R, pval, pidx, NS);
+  else
+    hipLaunchKernelGGL(head_gemm_k, dim3(NS, (CB + HG_CB - 1) / HG_CB), dim3(512), lds, s, (const uint4*)Wt, NB, KT, N,
+                       (const uint4*)Xs, CB, R, pval, pidx, NS);
   *n_slabs = NS;
   return hipGetLastError();
 }
@@ -1083,7 +1112,7 @@ hipError_t launch_stream_copy(const void* src, void* dst, int64_t bytes, hipStre
 hipError_t launch_stream_read(const void* base, int64_t bytes, float* sink, hipStream_t s) {
   const long long n_tiles = bytes / 1024;
   if (n_tiles <= 0) return hipErrorInvalidValue;
-  hipLaunchKernelGGL(stream_read_k, dim3(256 * 8), dim3(256), 0, s, (const uint4*)base, n_tiles, sink);
+  hipLaunchKernelGGL(stream_read_k, dim3(256 * 8), dim3(512), 0, s, (const uint4*)base, n_tiles, sink);
   return hipGetLastError();
 }
 
