@@ -86,7 +86,7 @@ struct del_ctx {
   uint16_t* xs_layer = nullptr; uint16_t* xs_shadow = nullptr; float* rowscale = nullptr;
   uint16_t* xs_h = nullptr; uint16_t* xs_attn = nullptr; uint16_t* xs_h1 = nullptr; uint16_t* xs_act = nullptr;
   float* ssq_h = nullptr; float* ssq_h1 = nullptr;
-  float* PM = nullptr; float* PL = nullptr; float* PA = nullptr; int nch_max = 0, attn_ct = 64;
+  float* PM = nullptr; float* PL = nullptr; float* PA = nullptr; int nch_max = 0, attn_ct = 64, attn_S = 0;   // attn_S > 0: register decode kernel with S splits
   float* pval = nullptr; int* pidx = nullptr;
   int* state = nullptr; int* draft_ids = nullptr; int* shadow_ids = nullptr; int* result = nullptr;
   int* ids_dev = nullptr; int* result_host = nullptr;
@@ -288,12 +288,18 @@ del_status run_layer(del_ctx* ctx, int l, int row0, int m, bool chained) {
   a.PM = ctx->PM; a.PL = ctx->PL; a.PA = ctx->PA; a.nch_max = ctx->nch_max; a.ct = ctx->attn_ct;
   a.O = ctx->attn; a.ldo = ctx->qpad;
   a.XsOut = mf ? ctx->xs_attn : nullptr;
-  HIPCHK(launch_attention(a, ctx->stream));
+  const bool dec = m == 1 && ctx->attn_S > 0;
+  if (dec) HIPCHK(launch_attention_decode(a, ctx->attn_S, ctx->stream));
+  else HIPCHK(launch_attention(a, ctx->stream));
   // 3. output projection + residual
   p = base_gemm(ctx);
   p.Wt = base + ctx->off_o; p.NB = ctx->NBd; p.KT = ctx->KTq; p.N = ctx->d; p.K = ctx->qdim;
   p.X = ctx->attn; p.ldx = ctx->qpad;
   p.R = hin; p.ldr = ctx->dpad; p.Y = hout; p.ldy = ctx->dpad;
+  if (dec) {
+    p.att_PM = ctx->PM; p.att_PL = ctx->PL; p.att_PA = ctx->PA;
+    p.att_S = ctx->attn_S; p.att_stride = ctx->nch_max; p.att_hd = ctx->hd;
+  }
   if (mf) {
     p.Xs = ctx->xs_attn;
     p.XsOut = ctx->xs_h1; p.gain_out = ctx->gain_ffn(li); p.ssq_out = ctx->ssq_h1;
@@ -469,6 +475,14 @@ del_status del_create(const del_config* cfg, void* hip_stream, del_ctx** out) {
     if (v >= 16 && v <= 64 && v % 16 == 0 && v * ctx->hd * ctx->esize <= 4 * 256 * 16) ctx->attn_ct = v;
   }
   ctx->nch_max = ceil_div(ctx->Tcap, ctx->attn_ct);
+  if (attention_decode_supported(ctx->wd, ctx->hd, ctx->nq / ctx->nkv)) {
+    // about 128 work-groups, at most 8 partials per head for the consumer to merge
+    ctx->attn_S = std::max(1, std::min(std::min(8, ctx->nch_max), ceil_div(128, ctx->nkv)));
+    if (const char* e = getenv("DEL_ATTN_SPLITS")) {
+      const int v = atoi(e);
+      if (v >= 0 && v <= std::min(16, ctx->nch_max)) ctx->attn_S = v;   // 0: staged kernels everywhere
+    }
+  }
   const int Rmax = ctx->L * ctx->maxrows;
   const int KTmax = std::max(ctx->KTd, std::max(ctx->KTq, ctx->KTf));
 

@@ -60,6 +60,10 @@ struct GemmP {
   const float* gain_out;
   float* ssq_out;
   const float* ssq_in; int ssq_nb;
+  // vector path, one row: the input row is the attention output given as att_S per-split
+  // softmax partials per head (max, sum, weighted values [hd]), merged while staging
+  const float* att_PM; const float* att_PL; const float* att_PA;
+  int att_S, att_stride, att_hd;
   // host side only: when both are set the launch records the kernel's own start and stop
   // timestamps into these events (per-kernel profiling)
   hipEvent_t ev_start, ev_stop;
@@ -89,6 +93,8 @@ hipError_t launch_prep_split(const float* src, int rows, int rows_per_group, int
                              int ld, int K, int KT, const float* gain, int rms, float eps,
                              uint16_t* Xs, float* rowscale, hipStream_t s);
 hipError_t launch_attention(const AttnP& p, hipStream_t s);
+hipError_t launch_attention_decode(const AttnP& p, int S, hipStream_t s);
+bool attention_decode_supported(int kvdtype, int hd, int G);
 hipError_t launch_embed(const void* Et, int wdtype, int KT, int vocab, const int* ids, int m,
                         float* out, int ld, int d_model, hipStream_t s);
 hipError_t launch_argmax_finish(const float* pval, const int* pidx, int rows, int NB,

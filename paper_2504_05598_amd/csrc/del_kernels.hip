@@ -256,7 +256,30 @@ __global__ void __launch_bounds__(1024) gemm_valu_k(GemmP p) {
         xv[j] = make_float4(0.f, 0.f, 0.f, 0.f);
         gv[j] = make_float4(1.f, 1.f, 1.f, 1.f);
         if (k < Kp) {
-          xv[j] = *(const float4*)(p.X + k);
+          if (p.att_S > 0) {
+            // the input row is the attention output: merge the S per-split softmax partials here
+            xv[j] = make_float4(0.f, 0.f, 0.f, 0.f);
+            if (k < p.K) {
+              const int h = k / p.att_hd, d = k - h * p.att_hd;
+              const float* pm = p.att_PM + (size_t)h * p.att_stride;
+              const float* pl = p.att_PL + (size_t)h * p.att_stride;
+              float mx = -INFINITY;
+              for (int sidx = 0; sidx < p.att_S; ++sidx) mx = fmaxf(mx, pm[sidx]);
+              float L = 0.f;
+              float4 a = make_float4(0.f, 0.f, 0.f, 0.f);
+              for (int sidx = 0; sidx < p.att_S; ++sidx) {
+                const float ms = pm[sidx];
+                const float c = ms > -INFINITY ? expf(ms - mx) : 0.f;
+                L += c * pl[sidx];
+                const float4 t = *(const float4*)(p.att_PA + ((size_t)h * p.att_stride + sidx) * p.att_hd + d);
+                a.x += c * t.x; a.y += c * t.y; a.z += c * t.z; a.w += c * t.w;
+              }
+              const float inv = 1.0f / L;
+              xv[j] = make_float4(a.x * inv, a.y * inv, a.z * inv, a.w * inv);
+            }
+          } else {
+            xv[j] = *(const float4*)(p.X + k);
+          }
           if (has_gain) gv[j] = *(const float4*)(p.gain + k);
         }
       }
@@ -733,6 +756,144 @@ __global__ void __launch_bounds__(256) attn_partial_k(AttnP p) {
   }
 }
 
+// ---------------------------------------------------------------------------------------
+// Decode attention (one new token row): one work-group per (split of the context, kv head),
+// 8 waves.  A wave-wide 16-byte load covers 64/LPR whole cache rows (LPR lanes per row); each
+// lane keeps its slice of q in registers, scores are reduced over the LPR lanes of a row, and
+// every lane group runs its own online softmax over the rows it sees, so K and V go from HBM
+// to registers once with eight 1 KiB loads in flight per wave.  Lane groups and waves are
+// merged at the end; the S per-split partials are merged by the consumer (the O projection's
+// input staging), so no combine kernel runs on this path.
+// ---------------------------------------------------------------------------------------
+struct SoftAcc { float m, l; };
+
+template <typename KVT, int HD, int G>
+__global__ void __launch_bounds__(512) attn_decode_k(AttnP p) {
+  constexpr int EPL = 16 / sizeof(KVT);   // elements per lane and load
+  constexpr int LPR = HD / EPL;           // lanes per cache row
+  constexpr int RPL = 64 / LPR;           // cache rows per wave-wide load
+  constexpr int UL = 4;                   // loads in flight per wave, matrix and pipeline stage
+  constexpr int NWV = 8;
+  __shared__ float sm[NWV][G], sl[NWV][G];
+  __shared__ float sa[NWV][G][HD];
+  const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
+  const int split = blockIdx.x, kvh = blockIdx.y, S = gridDim.x;
+  const int T_end = p.state[0] + p.row_off + 1;
+  const int rps = ((T_end + S - 1) / S + RPL - 1) / RPL * RPL;   // rows per split, whole loads
+  const int t_lo = split * rps, t_hi = min(T_end, t_lo + rps);
+  const int rs = lane / LPR, dl = lane % LPR;
+  const float scale = 1.0f / sqrtf((float)HD);
+  float q[G][EPL];
+#pragma unroll
+  for (int g = 0; g < G; ++g) {
+    const float* qp = p.Q + (size_t)(kvh * G + g) * HD + dl * EPL;
+#pragma unroll
+    for (int e = 0; e < EPL; e += 4) {
+      const float4 t = *(const float4*)(qp + e);
+      q[g][e] = t.x * scale; q[g][e + 1] = t.y * scale; q[g][e + 2] = t.z * scale; q[g][e + 3] = t.w * scale;
+    }
+  }
+  float m[G], l[G], acc[G][EPL];
+#pragma unroll
+  for (int g = 0; g < G; ++g) {
+    m[g] = -INFINITY; l[g] = 0.f;
+#pragma unroll
+    for (int e = 0; e < EPL; ++e) acc[g][e] = 0.f;
+  }
+  // row groups of this wave: j = wave, wave + NWV, ...; group j covers rows t_lo + j*RPL ...
+  const int ngrp = t_hi > t_lo ? (t_hi - t_lo + RPL - 1) / RPL : 0;
+  const uint4* Kg = (const uint4*)((const KVT*)p.Kc + (size_t)kvh * p.Tcap * HD);
+  const uint4* Vg = (const uint4*)((const KVT*)p.Vc + (size_t)kvh * p.Tcap * HD);
+  // rows past t_hi (a ragged last group) are read from row t_hi - 1 and masked
+  auto row_of = [&](int j) { return min(t_lo + j * RPL + rs, t_hi - 1); };
+  uint4 kc[UL], vc[UL], kn[UL], vn[UL];
+  auto consume = [&](const uint4& kk, const uint4& vv, int j) {
+    const bool valid = j < ngrp && t_lo + j * RPL + rs < t_hi;
+    float kf[EPL], vf[EPL];
+    if (sizeof(KVT) == 2) { WDec<8>::dec(kk, kf); WDec<8>::dec(vv, vf); }
+    else { WDec<4>::dec(kk, kf); WDec<4>::dec(vv, vf); }
+#pragma unroll
+    for (int g = 0; g < G; ++g) {
+      float sdot = 0.f;
+#pragma unroll
+      for (int e = 0; e < EPL; ++e) sdot += q[g][e] * kf[e];
+#pragma unroll
+      for (int o = 1; o < LPR; o <<= 1) sdot += __shfl_xor(sdot, o);
+      if (valid) {
+        const float mn = fmaxf(m[g], sdot);
+        const float c = expf(m[g] - mn);      // m = -inf at the first row: exp(-inf) = 0
+        const float pr = expf(sdot - mn);
+        l[g] = l[g] * c + pr;
+#pragma unroll
+        for (int e = 0; e < EPL; ++e) acc[g][e] = acc[g][e] * c + pr * vf[e];
+        m[g] = mn;
+      }
+    }
+  };
+  if (ngrp > 0) {
+    const int nit = (ngrp - wave + NWV * UL - 1) / (NWV * UL);   // iterations of this wave (may be <= 0)
+    if (nit > 0) {
+#pragma unroll
+      for (int u = 0; u < UL; ++u) {
+        const int j = min(wave + u * NWV, ngrp - 1);
+        const size_t off = (size_t)row_of(j) * LPR + dl;
+        kc[u] = Kg[off]; vc[u] = Vg[off];
+      }
+      for (int it = 0; it < nit; ++it) {
+        const int j0 = wave + it * NWV * UL;
+#pragma unroll
+        for (int u = 0; u < UL; ++u) {   // next iteration's rows (clamped: re-reads the last group at the end)
+          const int j = min(j0 + (UL + u) * NWV, ngrp - 1);
+          const size_t off = (size_t)row_of(j) * LPR + dl;
+          kn[u] = Kg[off]; vn[u] = Vg[off];
+        }
+#pragma unroll
+        for (int u = 0; u < UL; ++u) consume(kc[u], vc[u], j0 + u * NWV);
+#pragma unroll
+        for (int u = 0; u < UL; ++u) { kc[u] = kn[u]; vc[u] = vn[u]; }
+      }
+    }
+  }
+  // merge the lane groups of a wave (same value dims, different rows) ...
+#pragma unroll
+  for (int g = 0; g < G; ++g) {
+#pragma unroll
+    for (int o = LPR; o < 64; o <<= 1) {
+      const float m2 = __shfl_xor(m[g], o), l2 = __shfl_xor(l[g], o);
+      const float M = fmaxf(m[g], m2);
+      const float c1 = m[g] > -INFINITY ? expf(m[g] - M) : 0.f;
+      const float c2 = m2 > -INFINITY ? expf(m2 - M) : 0.f;
+      l[g] = l[g] * c1 + l2 * c2;
+#pragma unroll
+      for (int e = 0; e < EPL; ++e) acc[g][e] = acc[g][e] * c1 + __shfl_xor(acc[g][e], o) * c2;
+      m[g] = M;
+    }
+    if (rs == 0) {
+      if (dl == 0) { sm[wave][g] = m[g]; sl[wave][g] = l[g]; }
+#pragma unroll
+      for (int e = 0; e < EPL; ++e) sa[wave][g][dl * EPL + e] = acc[g][e];
+    }
+  }
+  __syncthreads();
+  // ... then the waves, in a fixed order; one partial per (query row, split)
+  for (int i = tid; i < G * HD; i += 512) {
+    const int g = i / HD, d = i - g * HD;
+    float M = -INFINITY;
+#pragma unroll
+    for (int w = 0; w < NWV; ++w) M = fmaxf(M, sm[w][g]);
+    float L = 0.f, A = 0.f;
+#pragma unroll
+    for (int w = 0; w < NWV; ++w) {
+      const float c = sm[w][g] > -INFINITY ? expf(sm[w][g] - M) : 0.f;
+      L += c * sl[w][g];
+      A += c * sa[w][g][d];
+    }
+    const size_t prow = (size_t)(kvh * G + g) * p.nch_max + split;
+    if (d == 0) { p.PM[prow] = M; p.PL[prow] = L; }
+    p.PA[prow * HD + d] = A;
+  }
+}
+
 __global__ void __launch_bounds__(128) attn_combine_k(AttnP p) {
   const int row = blockIdx.x;  // mi * n_q + h
   const int d = threadIdx.x;
@@ -1033,6 +1194,25 @@ hipError_t launch_prep_split(const float* src, int rows, int rows_per_group, int
 static size_t attn_lds_bytes(int hd, int esize, int ct, int qb) {
   const int wpr = hd * esize / 4;
   return (size_t)2 * ct * (wpr + 1) * 4 + (size_t)qb * hd * 4 + (size_t)qb * ct * 4;
+}
+
+// Decode path (m == 1) for the shapes the register kernel is built for; S = number of splits.
+// Returns hipErrorNotSupported for other shapes (the caller falls back to the staged kernels).
+hipError_t launch_attention_decode(const AttnP& p, int S, hipStream_t s) {
+  if (p.m != 1 || S < 1 || S > p.nch_max) return hipErrorInvalidValue;
+  const int G = p.n_q / p.n_kv;
+  dim3 grid(S, p.n_kv), block(512);
+  if (p.kvdtype == 1 && p.hd == 128 && G == 1) hipLaunchKernelGGL((attn_decode_k<uint16_t, 128, 1>), grid, block, 0, s, p);
+  else if (p.kvdtype == 1 && p.hd == 64 && G == 4) hipLaunchKernelGGL((attn_decode_k<uint16_t, 64, 4>), grid, block, 0, s, p);
+  else if (p.kvdtype == 1 && p.hd == 128 && G == 8) hipLaunchKernelGGL((attn_decode_k<uint16_t, 128, 8>), grid, block, 0, s, p);
+  else if (p.kvdtype == 0 && p.hd == 64 && G == 1) hipLaunchKernelGGL((attn_decode_k<float, 64, 1>), grid, block, 0, s, p);
+  else return hipErrorNotSupported;
+  return hipGetLastError();
+}
+
+bool attention_decode_supported(int kvdtype, int hd, int G) {
+  return (kvdtype == 1 && hd == 128 && (G == 1 || G == 8)) || (kvdtype == 1 && hd == 64 && G == 4) ||
+         (kvdtype == 0 && hd == 64 && G == 1);
 }
 
 hipError_t launch_attention(const AttnP& p, hipStream_t s) {
