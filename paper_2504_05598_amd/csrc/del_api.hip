@@ -86,7 +86,7 @@ struct del_ctx {
   uint16_t* xs_layer = nullptr; uint16_t* xs_shadow = nullptr; float* rowscale = nullptr;
   uint16_t* xs_h = nullptr; uint16_t* xs_attn = nullptr; uint16_t* xs_h1 = nullptr; uint16_t* xs_act = nullptr;
   float* ssq_h = nullptr; float* ssq_h1 = nullptr;
-  float* PM = nullptr; float* PL = nullptr; float* PA = nullptr; int nch_max = 0, attn_ct = 64, attn_S = 0;   // attn_S > 0: register decode kernel with S splits
+  float* PM = nullptr; float* PL = nullptr; float* PA = nullptr; int nch_max = 0, attn_ct = 64, attn_S = 0, attn_dec_rows = 15;   // attn_S > 0: register decode kernel with S splits
   float* pval = nullptr; int* pidx = nullptr;
   int* state = nullptr; int* draft_ids = nullptr; int* shadow_ids = nullptr; int* result = nullptr;
   int* ids_dev = nullptr; int* result_host = nullptr;
@@ -288,9 +288,19 @@ del_status run_layer(del_ctx* ctx, int l, int row0, int m, bool chained) {
   a.PM = ctx->PM; a.PL = ctx->PL; a.PA = ctx->PA; a.nch_max = ctx->nch_max; a.ct = ctx->attn_ct;
   a.O = ctx->attn; a.ldo = ctx->qpad;
   a.XsOut = mf ? ctx->xs_attn : nullptr;
-  const bool dec = m == 1 && ctx->attn_S > 0;
-  if (dec) HIPCHK(launch_attention_decode(a, ctx->attn_S, ctx->stream));
-  else HIPCHK(launch_attention(a, ctx->stream));
+  // few token rows: the register kernel, one work-group per (split, kv head, row); a single row's
+  // partials are merged by the O projection itself, several rows' by the merge kernel
+  const bool dec_any = ctx->attn_S > 0 && m <= ctx->attn_dec_rows;
+  const bool dec = dec_any && m == 1;
+  if (dec_any) {
+    HIPCHK(launch_attention_decode(a, ctx->attn_S, ctx->stream));
+    if (m > 1) {
+      a.nsplit = ctx->attn_S;
+      HIPCHK(launch_attention_merge(a, ctx->stream));
+    }
+  } else {
+    HIPCHK(launch_attention(a, ctx->stream));
+  }
   // 3. output projection + residual
   p = base_gemm(ctx);
   p.Wt = base + ctx->off_o; p.NB = ctx->NBd; p.KT = ctx->KTq; p.N = ctx->d; p.K = ctx->qdim;
@@ -481,6 +491,10 @@ del_status del_create(const del_config* cfg, void* hip_stream, del_ctx** out) {
     if (const char* e = getenv("DEL_ATTN_SPLITS")) {
       const int v = atoi(e);
       if (v >= 0 && v <= std::min(16, ctx->nch_max)) ctx->attn_S = v;   // 0: staged kernels everywhere
+    }
+    if (const char* e = getenv("DEL_ATTN_DEC_ROWS")) {
+      const int v = atoi(e);
+      if (v >= 1 && v <= 64) ctx->attn_dec_rows = v;
     }
   }
   const int Rmax = ctx->L * ctx->maxrows;

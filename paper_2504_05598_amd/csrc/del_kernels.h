@@ -79,6 +79,7 @@ struct AttnP {
   int nch_max;
   int ct;                       // cache rows per work-group (16, 32, 48 or 64)
   int qb;                       // query rows per batch (set by the launcher)
+  int nsplit;                   // > 0: the partials come from the decode kernel, this many per row
   float* O; int ldo;            // combined output [m][n_q*hd]
   uint16_t* XsOut;              // optional: the same rows as split tiles (input of the O projection)
 };
@@ -94,6 +95,7 @@ hipError_t launch_prep_split(const float* src, int rows, int rows_per_group, int
                              uint16_t* Xs, float* rowscale, hipStream_t s);
 hipError_t launch_attention(const AttnP& p, hipStream_t s);
 hipError_t launch_attention_decode(const AttnP& p, int S, hipStream_t s);
+hipError_t launch_attention_merge(const AttnP& p, hipStream_t s);
 bool attention_decode_supported(int kvdtype, int hd, int G);
 hipError_t launch_embed(const void* Et, int wdtype, int KT, int vocab, const int* ids, int m,
                         float* out, int ld, int d_model, hipStream_t s);

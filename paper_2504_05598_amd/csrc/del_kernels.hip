@@ -778,7 +778,8 @@ __global__ void __launch_bounds__(512) attn_decode_k(AttnP p) {
   __shared__ float sa[NWV][G][HD];
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
   const int split = blockIdx.x, kvh = blockIdx.y, S = gridDim.x;
-  const int T_end = p.state[0] + p.row_off + 1;
+  const int mi = blockIdx.z;                              // token row of this pass; attends rows <= its own
+  const int T_end = p.state[0] + p.row_off + mi + 1;
   const int rps = ((T_end + S - 1) / S + RPL - 1) / RPL * RPL;   // rows per split, whole loads
   const int t_lo = split * rps, t_hi = min(T_end, t_lo + rps);
   const int rs = lane / LPR, dl = lane % LPR;
@@ -786,7 +787,7 @@ __global__ void __launch_bounds__(512) attn_decode_k(AttnP p) {
   float q[G][EPL];
 #pragma unroll
   for (int g = 0; g < G; ++g) {
-    const float* qp = p.Q + (size_t)(kvh * G + g) * HD + dl * EPL;
+    const float* qp = p.Q + (size_t)mi * p.ldq + (size_t)(kvh * G + g) * HD + dl * EPL;
 #pragma unroll
     for (int e = 0; e < EPL; e += 4) {
       const float4 t = *(const float4*)(qp + e);
@@ -888,7 +889,7 @@ __global__ void __launch_bounds__(512) attn_decode_k(AttnP p) {
       L += c * sl[w][g];
       A += c * sa[w][g][d];
     }
-    const size_t prow = (size_t)(kvh * G + g) * p.nch_max + split;
+    const size_t prow = ((size_t)mi * p.n_q + kvh * G + g) * p.nch_max + split;
     if (d == 0) { p.PM[prow] = M; p.PL[prow] = L; }
     p.PA[prow * HD + d] = A;
   }
@@ -899,7 +900,7 @@ __global__ void __launch_bounds__(128) attn_combine_k(AttnP p) {
   const int d = threadIdx.x;
   if (d >= p.hd) return;
   const int T_end = p.state[0] + p.row_off + p.m;
-  const int nch = (T_end + p.ct - 1) / p.ct;
+  const int nch = p.nsplit > 0 ? p.nsplit : (T_end + p.ct - 1) / p.ct;   // partials per row
   const float* pm = p.PM + (size_t)row * p.nch_max;
   const float* pl = p.PL + (size_t)row * p.nch_max;
   const float* pa = p.PA + (size_t)row * p.nch_max * p.hd + d;
@@ -1199,9 +1200,9 @@ static size_t attn_lds_bytes(int hd, int esize, int ct, int qb) {
 // Decode path (m == 1) for the shapes the register kernel is built for; S = number of splits.
 // Returns hipErrorNotSupported for other shapes (the caller falls back to the staged kernels).
 hipError_t launch_attention_decode(const AttnP& p, int S, hipStream_t s) {
-  if (p.m != 1 || S < 1 || S > p.nch_max) return hipErrorInvalidValue;
+  if (p.m < 1 || S < 1 || S > p.nch_max) return hipErrorInvalidValue;
   const int G = p.n_q / p.n_kv;
-  dim3 grid(S, p.n_kv), block(512);
+  dim3 grid(S, p.n_kv, p.m), block(512);   // one work-group per (split, kv head, token row)
   if (p.kvdtype == 1 && p.hd == 128 && G == 1) hipLaunchKernelGGL((attn_decode_k<uint16_t, 128, 1>), grid, block, 0, s, p);
   else if (p.kvdtype == 1 && p.hd == 64 && G == 4) hipLaunchKernelGGL((attn_decode_k<uint16_t, 64, 4>), grid, block, 0, s, p);
   else if (p.kvdtype == 1 && p.hd == 128 && G == 8) hipLaunchKernelGGL((attn_decode_k<uint16_t, 128, 8>), grid, block, 0, s, p);
@@ -1213,6 +1214,13 @@ hipError_t launch_attention_decode(const AttnP& p, int S, hipStream_t s) {
 bool attention_decode_supported(int kvdtype, int hd, int G) {
   return (kvdtype == 1 && hd == 128 && (G == 1 || G == 8)) || (kvdtype == 1 && hd == 64 && G == 4) ||
          (kvdtype == 0 && hd == 64 && G == 1);
+}
+
+// Merge p.nsplit partials per row (written by the decode kernel) into O (and XsOut).
+hipError_t launch_attention_merge(const AttnP& p, hipStream_t s) {
+  if (p.nsplit < 1 || p.nsplit > p.nch_max || p.hd > 128) return hipErrorInvalidValue;
+  hipLaunchKernelGGL(attn_combine_k, dim3(p.m * p.n_q), dim3(128), 0, s, p);
+  return hipGetLastError();
 }
 
 hipError_t launch_attention(const AttnP& p, hipStream_t s) {
