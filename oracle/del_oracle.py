@@ -45,6 +45,13 @@ the pins in tests/ cover the mathematics around them):
       l ascending, d ascending).
   R9  TPL's numerator is evaluated as the sum over i of alpha^i (the form given
       below Eq. 1), which is also defined at alpha = 1.
+  R18 dynamic draft-exiting (Section 4.4, Eq. 3; Algorithm 1 loop): the confidence
+      of a token is its soft-max probability at temperature 1; drafting runs up
+      to d_max steps and stops before appending a token whose confidence is
+      below tau_E; the hidden state of the stopping step is the round's last
+      row.  In Eq. 3 the mismatched count is n - c (reading R1) and a ratio
+      whose denominator is zero (no matched, or no mismatched, token seen yet)
+      counts as 0.
 """
 from __future__ import annotations
 
@@ -104,6 +111,23 @@ def first_mismatch(draft_layer_tokens: Sequence[int], target_tokens: Sequence[in
     return gamma
 
 
+def confidence_sums(shadow: Sequence[Sequence[int]], conf: Sequence[Sequence[float]],
+                    target: Sequence[int], u: int) -> Tuple[List[float], List[float]]:
+    """tcs^l, fcs^l: confidence of layer l's shadow tokens at positions 0..u, summed over the
+    matched and over the mismatched ones (Section 4.4); index 0 unused."""
+    tcs, fcs = [0.0], [0.0]
+    for l in range(1, len(shadow)):
+        t = f = 0.0
+        for i in range(u + 1):
+            if int(shadow[l][i]) == int(target[i]):
+                t += float(conf[l][i])
+            else:
+                f += float(conf[l][i])
+        tcs.append(t)
+        fcs.append(f)
+    return tcs, fcs
+
+
 def matched_counts(shadow: Sequence[Sequence[int]], target: Sequence[int], u: int) -> List[int]:
     """c^l = sum_{i=0}^{u} 1(shadow[l][i] == target[i]); index 0 unused (Section 4.2)."""
     out = [0]
@@ -122,12 +146,36 @@ class DelStats:
         self.c_hist: List[List[int]] = []   # one [L+1] list per round
         self.n_hist: List[int] = []
         self.u_hist: List[int] = []
+        self.tcs_hist: List[List[float]] = []   # confidence summed over matched shadow tokens
+        self.fcs_hist: List[List[float]] = []   # ... over mismatched ones
 
-    def append(self, c: Sequence[int], n: int, u: int) -> None:
+    def append(self, c: Sequence[int], n: int, u: int,
+               tcs: Optional[Sequence[float]] = None, fcs: Optional[Sequence[float]] = None) -> None:
         assert len(c) == self.L + 1
         self.c_hist.append([int(x) for x in c])
         self.n_hist.append(int(n))
         self.u_hist.append(int(u))
+        self.tcs_hist.append([float(x) for x in (tcs if tcs is not None else [0.0] * (self.L + 1))])
+        self.fcs_hist.append([float(x) for x in (fcs if fcs is not None else [0.0] * (self.L + 1))])
+
+    def S_tcs(self, l: int) -> float:
+        return decayed_sum([t[l] for t in self.tcs_hist], self.omega)
+
+    def S_fcs(self, l: int) -> float:
+        return decayed_sum([t[l] for t in self.fcs_hist], self.omega)
+
+    def tau(self) -> List[float]:
+        """Dynamic threshold, Eq. 3: midpoint of the decayed mean confidence of matched and of
+        mismatched shadow tokens; a ratio with a zero denominator counts as 0."""
+        out = [0.0]
+        sn = self.S_n()
+        for l in range(1, self.L + 1):
+            sc = self.S_c(l)
+            sm = sn - sc                       # S(n - c): S is linear
+            a = self.S_tcs(l) / sc if sc > 0.0 else 0.0
+            b = self.S_fcs(l) / sm if sm > 0.0 else 0.0
+            out.append(0.5 * (a + b))
+        return out
 
     def S_c(self, l: int) -> float:
         return decayed_sum([c[l] for c in self.c_hist], self.omega)
@@ -192,6 +240,14 @@ class RoundRecord:
     next_E: int
     next_gamma: int
     hidden: Optional[torch.Tensor] = None   # [L+1, gamma+1, d] if kept
+    conf: Optional[List[List[float]]] = None        # confidence of every shadow token [L+1][gamma+1]
+    draft_conf: Optional[List[float]] = None        # confidence of each draft step taken (incl. a stopping one)
+    stopped_early: bool = False                     # the draft loop broke on low confidence
+    tcs: Optional[List[float]] = None
+    fcs: Optional[List[float]] = None
+    tau: Optional[List[float]] = None               # thresholds after the update
+    S_tcs: Optional[List[float]] = None
+    S_fcs: Optional[List[float]] = None
 
 
 @dataclass
@@ -206,6 +262,8 @@ class PrefillRecord:
     next_E: int
     next_gamma: int
     hidden: Optional[torch.Tensor] = None   # [L+1, window, d]
+    conf: Optional[List[List[float]]] = None
+    tau: Optional[List[float]] = None
 
 
 class Oracle:
@@ -300,9 +358,16 @@ class Oracle:
 
     def head(self, h: torch.Tensor) -> Tuple[List[int], List[float]]:
         """Greedy token and top-2 logit gap per row."""
+        ids, gaps, _ = self.head_conf(h)
+        return ids, gaps
+
+    def head_conf(self, h: torch.Tensor) -> Tuple[List[int], List[float], List[float]]:
+        """Greedy token, top-2 logit gap and confidence (soft-max probability of the greedy
+        token, Section 4.4) per row."""
         lg = self.logits(h)
         lg32 = lg.to(torch.float32)
-        ids, gaps = [], []
+        lse = torch.logsumexp(lg, dim=-1)
+        ids, gaps, conf = [], [], []
         for r in range(lg32.shape[0]):
             row = lg32[r]
             top = row.max()
@@ -310,7 +375,8 @@ class Oracle:
             two = torch.topk(lg[r], 2).values
             ids.append(idx)
             gaps.append(float(two[0] - two[1]))
-        return ids, gaps
+            conf.append(float(torch.exp(lg[r, idx] - lse[r])))
+        return ids, gaps, conf
 
     # ---- prefill ----
     def prefill(self, prompt: Sequence[int], keep_hidden: bool = False) -> PrefillRecord:
@@ -327,29 +393,39 @@ class Oracle:
         self.T = P
         shadow = [[0] * w]
         gaps = [[0.0] * w]
+        conf = [[0.0] * w]
         for l in range(1, self.L + 1):
-            ids, g = self.head(hid[l])
+            ids, g, cf = self.head_conf(hid[l])
             shadow.append(ids)
             gaps.append(g)
+            conf.append(cf)
         target = shadow[self.L]
         c = matched_counts(shadow, target, w - 1)
-        self.stats.append(c, w, w - 1)
+        tcs, fcs = confidence_sums(shadow, conf, target, w - 1)
+        self.stats.append(c, w, w - 1, tcs, fcs)
         first = target[w - 1]
         self.pending = first
         E, gamma = self.stats.select()
         return PrefillRecord(first, gaps[self.L][w - 1], w, shadow, gaps, c,
-                             self.stats.alpha(), E, gamma, hid if keep_hidden else None)
+                             self.stats.alpha(), E, gamma, hid if keep_hidden else None,
+                             conf, self.stats.tau())
 
     # ---- one self-speculative round ----
-    def round(self, E: int, gamma: int, keep_hidden: bool = False) -> RoundRecord:
+    def round(self, E: int, gamma: int, keep_hidden: bool = False,
+              tau: Optional[float] = None) -> RoundRecord:
+        """One self-speculative round.  tau = None: draft exactly `gamma` tokens.  Otherwise
+        dynamic draft-exiting (Section 4.4; Algorithm 1 loop): draft up to `gamma` (= d_max)
+        tokens and stop, before appending, at the first token whose confidence is below tau."""
         L, d = self.L, self.cfg.d_model
         assert 1 <= E <= L and 0 <= gamma
         assert self.pending is not None, "prefill first"
         T = self.T
         assert T + gamma + 1 <= self.max_context
         hid = torch.zeros((L + 1, gamma + 1, d), dtype=self.dtype)
-        # draft: gamma auto-regressive steps through the first E layers
+        # draft: auto-regressive steps through the first E layers
         drafts: List[int] = []
+        draft_conf: List[float] = []
+        stopped = False
         tok = self.pending
         for i in range(gamma):
             h = self.embed(tok)[None, :]
@@ -357,15 +433,23 @@ class Oracle:
             for l in range(1, E + 1):
                 h = self.layer(l, h, T + i)
                 hid[l, i] = h[0]
-            ids, _ = self.head(hid[E, i][None, :])
+            ids, _, cf = self.head_conf(hid[E, i][None, :])
+            draft_conf.append(cf[0])
+            if tau is not None and cf[0] < tau:
+                stopped = True                  # not appended; row i is the round's last row
+                break
             drafts.append(ids[0])
             tok = ids[0]
-        # the last pending token passes the first E layers (no head needed)
-        h = self.embed(tok)[None, :]
-        hid[0, gamma] = h[0]
-        for l in range(1, E + 1):
-            h = self.layer(l, h, T + gamma)
-            hid[l, gamma] = h[0]
+        if stopped:
+            gamma = len(drafts)
+            hid = hid[:, :gamma + 1].clone()
+        else:
+            # the last pending token passes the first E layers (no head needed)
+            h = self.embed(tok)[None, :]
+            hid[0, gamma] = h[0]
+            for l in range(1, E + 1):
+                h = self.layer(l, h, T + gamma)
+                hid[l, gamma] = h[0]
         # verify: the gamma+1 exit states pass the remaining layers together
         rows = hid[E].clone()
         for l in range(E + 1, L + 1):
@@ -374,23 +458,29 @@ class Oracle:
         # shadow tokens of every layer (layer L's are the target's tokens)
         shadow = [[0] * (gamma + 1)]
         gaps = [[0.0] * (gamma + 1)]
+        conf = [[0.0] * (gamma + 1)]
         for l in range(1, L + 1):
-            ids, g = self.head(hid[l])
+            ids, g, cf = self.head_conf(hid[l])
             shadow.append(ids)
             gaps.append(g)
+            conf.append(cf)
         target = shadow[L]
         u = first_mismatch(drafts, target, gamma)
         n = u + 1
         out = target[:u + 1]
         c = matched_counts(shadow, target, u)
-        self.stats.append(c, n, u)
+        tcs, fcs = confidence_sums(shadow, conf, target, u)
+        self.stats.append(c, n, u, tcs, fcs)
         alpha = self.stats.alpha()
         nE, ng = self.stats.select()
         self.T = T + u + 1
         self.pending = out[-1]
         return RoundRecord(E, gamma, T, drafts, target, u, n, out, shadow, gaps, c, alpha,
                            [0.0] + [self.stats.S_c(l) for l in range(1, L + 1)],
-                           self.stats.S_n(), nE, ng, hid if keep_hidden else None)
+                           self.stats.S_n(), nE, ng, hid if keep_hidden else None,
+                           conf, draft_conf, stopped, tcs, fcs, self.stats.tau(),
+                           [0.0] + [self.stats.S_tcs(l) for l in range(1, L + 1)],
+                           [0.0] + [self.stats.S_fcs(l) for l in range(1, L + 1)])
 
     # ---- reference definitions used by the pins ----
     def vanilla_step(self) -> int:
@@ -456,6 +546,23 @@ def generate_del(oracle: Oracle, prompt: Sequence[int], n_tokens: int, keep_hidd
         recs.append(r)
         toks.extend(r.out_tokens)
         E, gamma = r.next_E, r.next_gamma
+    return toks, pre, recs
+
+
+def generate_del_full(oracle: Oracle, prompt: Sequence[int], n_tokens: int, keep_hidden: bool = False,
+                      ) -> Tuple[List[int], PrefillRecord, List[RoundRecord]]:
+    """Algorithm 1 in full: DEL selects the exit layer every round and the draft loop runs up to
+    d_max steps, stopping at the first token whose confidence is below tau_E (Section 4.4)."""
+    pre = oracle.prefill(prompt, keep_hidden)
+    toks = [pre.first_token]
+    E, tau = pre.next_E, pre.tau[pre.next_E]
+    recs = []
+    while len(toks) < n_tokens:
+        cap = min(oracle.cfg.d_max, n_tokens - len(toks) - 1)
+        r = oracle.round(E, cap, keep_hidden, tau=tau)
+        recs.append(r)
+        toks.extend(r.out_tokens)
+        E, tau = r.next_E, r.tau[r.next_E]
     return toks, pre, recs
 
 
