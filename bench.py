@@ -158,6 +158,24 @@ def main():
         ctx.round(1, 0)
     torch.cuda.synchronize()
     vanilla_tps = nv / (time.perf_counter() - t0)
+    # ---- the same K rounds with dynamic draft-exiting (Section 4.4): E and tau_E from the statistics
+    ctx.prefill(prompt)
+
+    def run_dynamic(n_rounds):
+        tokens, drafted = 0, 0
+        st = ctx.stats()
+        for _ in range(n_rounds):
+            E = st["next_E"]
+            out, g, _ = ctx.round_dynamic(E, st["tau"][E], cfg.d_max)
+            tokens += len(out); drafted += g
+            st = ctx.stats()
+        return tokens, drafted
+    run_dynamic(W)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    dyn_tokens, dyn_drafted = run_dynamic(K)
+    torch.cuda.synchronize()
+    dyn_tps = dyn_tokens / (time.perf_counter() - t0)
     stream_gbs = ctx.stream_read_gbps(min(4 << 30, cfg.layer_weight_bytes() * cfg.n_layers), 10)
     copy_gbs = ctx.stream_copy_gbps(1 << 30, 5)     # also the known-size kernel for counter calibration
 
@@ -193,6 +211,8 @@ def main():
             "mean_gamma": round(sum(r[1] for r in recs) / len(recs), 2),
             "vanilla_tokens_per_s": round(vanilla_tps, 2),
             "speedup_over_vanilla": round(value / vanilla_tps, 3),
+            "with_draft_exiting_tokens_per_s": round(dyn_tps, 2),
+            "with_draft_exiting_mean_gamma": round(dyn_drafted / K, 2),
             "stream_read_GBs": round(stream_gbs, 1), "stream_copy_GBs": round(copy_gbs, 1),
             "paper_speedup_over_autoregressive": "2.16-2.62x on A100-40G / 2xH100-PCIe (context only)",
         },

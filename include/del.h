@@ -115,6 +115,16 @@ del_status del_prefill(del_ctx* ctx, const int32_t* prompt, int32_t n_prompt,
  * Errors: DEL_E_STATE before prefill, DEL_E_ARG, DEL_E_CAPACITY (state unchanged). */
 del_status del_round(del_ctx* ctx, int32_t E, int32_t gamma, int32_t* out_tokens, int32_t* n_out);
 
+/* The same round with dynamic draft-exiting (Section 4.4, Eq. 3; Algorithm 1, draft loop):
+ * drafting runs for up to d_cap <= d_max steps and stops, before appending it, at the first token
+ * whose confidence (soft-max probability of the drafted token) is below `tau` >= 0 - normally the
+ * tau of layer E from del_layer_stats.  The hidden state of the stopping step is the round's last
+ * row, so no extra pass over the first E layers is needed.  out_tokens has room for d_cap+1 ids.
+ * *gamma_used = tokens drafted, *stopped_early = 1 if the loop stopped on low confidence (either
+ * may be NULL).  The host reads one confidence per draft step (a 4-byte copy and a stream sync). */
+del_status del_round_dynamic(del_ctx* ctx, int32_t E, double tau, int32_t d_cap, int32_t* out_tokens,
+                             int32_t* n_out, int32_t* gamma_used, int32_t* stopped_early);
+
 /* Per-layer statistics (Section 4.2; Eq. 2).  Arrays are caller-allocated and
  * indexed by layer number 0..L (entry 0 unused).  Any array pointer may be NULL. */
 typedef struct {
@@ -128,10 +138,19 @@ typedef struct {
   int32_t* last_shadow;      /* [(L+1)*(d_max+1)] shadow ids, row-major by layer;
                                 row l, entries 0..last_gamma (prefill: not filled) */
   int32_t* last_draft;       /* [d_max] drafted ids of the last round              */
+  /* dynamic draft-exiting (Section 4.4): decayed confidence sums over matched / mismatched
+   * shadow tokens and the threshold tau_l of Eq. 3 (a ratio with a zero denominator counts
+   * as 0; mismatches = valid positions - matches)                                        */
+  double* S_tcs;             /* [L+1]                                              */
+  double* S_fcs;             /* [L+1]                                              */
+  double* tau;               /* [L+1]                                              */
+  float* last_conf;          /* [(L+1)*(d_max+1)] confidence of each shadow token, like last_shadow */
+  float* last_draft_conf;    /* [d_max+1] confidence of each draft step taken (incl. a stopping one) */
+  int32_t last_stopped;      /* 1 if the last round's draft loop stopped on low confidence */
 } del_stats;
 del_status del_layer_stats(const del_ctx* ctx, del_stats* out);
-/* Import S_n and S_c (resume, or re-synchronise a test harness); recomputes alpha
- * and the next (E, gamma).  Only S_n and S_c are read. */
+/* Import S_n and S_c, and S_tcs / S_fcs when both are non-NULL (resume, or re-synchronise a
+ * test harness); recomputes alpha, tau and the next (E, gamma).  Nothing else is read. */
 del_status del_set_layer_stats(del_ctx* ctx, const del_stats* in);
 
 /* Wall time of the segments of the last round, from HIP events on the stream. */

@@ -13,7 +13,7 @@ from typing import List, Optional, Sequence, Tuple
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
 
-EXPORTS = ["del_create", "del_destroy", "del_load_weights", "del_prefill", "del_round",
+EXPORTS = ["del_create", "del_destroy", "del_load_weights", "del_prefill", "del_round", "del_round_dynamic",
            "del_layer_stats", "del_set_layer_stats", "del_last_timings", "del_debug_hidden",
            "del_debug_logits", "del_debug_state", "del_debug_set_pending", "del_profile_enable", "del_profile_read", "del_bench_stream_read", "del_bench_stream_copy", "del_strerror",
            "del_last_error_text"]
@@ -56,7 +56,10 @@ class del_stats(C.Structure):
                 ("last_u", C.c_int32), ("last_n", C.c_int32), ("S_n", C.c_double),
                 ("S_c", C.POINTER(C.c_double)), ("alpha", C.POINTER(C.c_double)),
                 ("last_c", C.POINTER(C.c_int32)), ("last_shadow", C.POINTER(C.c_int32)),
-                ("last_draft", C.POINTER(C.c_int32))]
+                ("last_draft", C.POINTER(C.c_int32)),
+                ("S_tcs", C.POINTER(C.c_double)), ("S_fcs", C.POINTER(C.c_double)),
+                ("tau", C.POINTER(C.c_double)), ("last_conf", C.POINTER(C.c_float)),
+                ("last_draft_conf", C.POINTER(C.c_float)), ("last_stopped", C.c_int32)]
 
 
 _lib = None
@@ -84,6 +87,8 @@ def load_library():
     lib.del_prefill.argtypes = [C.c_void_p, P(C.c_int32), C.c_int32, P(C.c_int32), P(C.c_int32),
                                 P(C.c_int32)]
     lib.del_round.argtypes = [C.c_void_p, C.c_int32, C.c_int32, P(C.c_int32), P(C.c_int32)]
+    lib.del_round_dynamic.argtypes = [C.c_void_p, C.c_int32, C.c_double, C.c_int32, P(C.c_int32), P(C.c_int32),
+                                      P(C.c_int32), P(C.c_int32)]
     lib.del_layer_stats.argtypes = [C.c_void_p, P(del_stats)]
     lib.del_set_layer_stats.argtypes = [C.c_void_p, P(del_stats)]
     lib.del_last_timings.argtypes = [C.c_void_p, P(C.c_float), P(C.c_float), P(C.c_float)]
@@ -151,6 +156,14 @@ def del_round(ctx, E: int, gamma: int) -> List[int]:
     return list(out[:n.value])
 
 
+def del_round_dynamic(ctx, E: int, tau: float, d_cap: int) -> Tuple[List[int], int, bool]:
+    """Returns (accepted tokens, tokens drafted, stopped early)."""
+    out = (C.c_int32 * (d_cap + 1))()
+    n, g, stop = C.c_int32(), C.c_int32(), C.c_int32()
+    _check(load_library().del_round_dynamic(ctx, E, tau, d_cap, out, C.byref(n), C.byref(g), C.byref(stop)), ctx)
+    return list(out[:n.value]), g.value, bool(stop.value)
+
+
 def del_layer_stats(ctx, n_layers: int, d_max: int) -> dict:
     L = n_layers
     S_c = (C.c_double * (L + 1))()
@@ -158,7 +171,17 @@ def del_layer_stats(ctx, n_layers: int, d_max: int) -> dict:
     last_c = (C.c_int32 * (L + 1))()
     shadow = (C.c_int32 * ((L + 1) * (d_max + 1)))()
     draft = (C.c_int32 * max(1, d_max))()
+    S_tcs = (C.c_double * (L + 1))()
+    S_fcs = (C.c_double * (L + 1))()
+    tau = (C.c_double * (L + 1))()
+    conf = (C.c_float * ((L + 1) * (d_max + 1)))()
+    dconf = (C.c_float * (d_max + 1))()
     st = del_stats()
+    st.S_tcs = C.cast(S_tcs, C.POINTER(C.c_double))
+    st.S_fcs = C.cast(S_fcs, C.POINTER(C.c_double))
+    st.tau = C.cast(tau, C.POINTER(C.c_double))
+    st.last_conf = C.cast(conf, C.POINTER(C.c_float))
+    st.last_draft_conf = C.cast(dconf, C.POINTER(C.c_float))
     st.S_c = C.cast(S_c, C.POINTER(C.c_double))
     st.alpha = C.cast(alpha, C.POINTER(C.c_double))
     st.last_c = C.cast(last_c, C.POINTER(C.c_int32))
@@ -172,14 +195,24 @@ def del_layer_stats(ctx, n_layers: int, d_max: int) -> dict:
         "S_n": st.S_n, "S_c": list(S_c), "alpha": list(alpha), "last_c": list(last_c),
         "last_shadow": [list(shadow[l * (d_max + 1): l * (d_max + 1) + g + 1]) for l in range(L + 1)],
         "last_draft": list(draft[:g]),
+        "S_tcs": list(S_tcs), "S_fcs": list(S_fcs), "tau": list(tau),
+        "last_conf": [list(conf[l * (d_max + 1): l * (d_max + 1) + g + 1]) for l in range(L + 1)],
+        "last_draft_conf": list(dconf[:g + (1 if st.last_stopped else 0)]),
+        "last_stopped": bool(st.last_stopped),
     }
 
 
-def del_set_layer_stats(ctx, S_c: Sequence[float], S_n: float) -> None:
+def del_set_layer_stats(ctx, S_c: Sequence[float], S_n: float,
+                        S_tcs: Optional[Sequence[float]] = None, S_fcs: Optional[Sequence[float]] = None) -> None:
     arr = (C.c_double * len(S_c))(*S_c)
     st = del_stats()
     st.S_c = C.cast(arr, C.POINTER(C.c_double))
     st.S_n = S_n
+    if S_tcs is not None and S_fcs is not None:
+        a = (C.c_double * len(S_tcs))(*S_tcs)
+        b = (C.c_double * len(S_fcs))(*S_fcs)
+        st.S_tcs = C.cast(a, C.POINTER(C.c_double))
+        st.S_fcs = C.cast(b, C.POINTER(C.c_double))
     _check(load_library().del_set_layer_stats(ctx, C.byref(st)), ctx)
 
 
@@ -238,11 +271,14 @@ class DelContext:
     def round(self, E: int, gamma: int) -> List[int]:
         return del_round(self.ctx, E, gamma)
 
+    def round_dynamic(self, E: int, tau: float, d_cap: Optional[int] = None) -> Tuple[List[int], int, bool]:
+        return del_round_dynamic(self.ctx, E, tau, self.cfg.d_max if d_cap is None else d_cap)
+
     def stats(self) -> dict:
         return del_layer_stats(self.ctx, self.cfg.n_layers, self.cfg.d_max)
 
-    def set_stats(self, S_c: Sequence[float], S_n: float) -> None:
-        del_set_layer_stats(self.ctx, S_c, S_n)
+    def set_stats(self, S_c: Sequence[float], S_n: float, S_tcs=None, S_fcs=None) -> None:
+        del_set_layer_stats(self.ctx, S_c, S_n, S_tcs, S_fcs)
 
     def timings(self) -> Tuple[float, float, float]:
         return del_last_timings(self.ctx)

@@ -27,18 +27,36 @@ struct Policy {
   std::vector<double> Sc;  // [L+1]
   double Sn = 0.0;
   std::vector<double> alpha;
+  std::vector<double> St, Sf, tau;  // decayed confidence sums (matched / mismatched), thresholds
   int next_E = 1, next_gamma = 0;
 
   void reset(int L_, int d_max_, double omega_) {
     L = L_; d_max = d_max_; omega = omega_;
     Sc.assign(L + 1, 0.0);
     alpha.assign(L + 1, 0.0);
+    St.assign(L + 1, 0.0); Sf.assign(L + 1, 0.0); tau.assign(L + 1, 0.0);
     Sn = 0.0; next_E = 1; next_gamma = 0;
   }
-  void update(const int* c, int n) {  // c indexed by layer number 1..L
-    for (int l = 1; l <= L; ++l) Sc[l] = omega * Sc[l] + (double)c[l];
+  // c, tcs, fcs indexed by layer number 1..L
+  void update(const int* c, int n, const double* tcs, const double* fcs) {
+    for (int l = 1; l <= L; ++l) {
+      Sc[l] = omega * Sc[l] + (double)c[l];
+      St[l] = omega * St[l] + tcs[l];
+      Sf[l] = omega * Sf[l] + fcs[l];
+    }
     Sn = omega * Sn + (double)n;
     select();
+  }
+  // Dynamic threshold (Section 4.4, Eq. 3): midpoint of the decayed mean confidence of the
+  // matched and of the mismatched shadow tokens; mismatches = valid positions - matches; a ratio
+  // with a zero denominator counts as 0.
+  void thresholds() {
+    for (int l = 1; l <= L; ++l) {
+      const double sm = Sn - Sc[l];
+      const double a = Sc[l] > 0.0 ? St[l] / Sc[l] : 0.0;
+      const double b = sm > 0.0 ? Sf[l] / sm : 0.0;
+      tau[l] = 0.5 * (a + b);
+    }
   }
   // alpha_l = S(c^l)/S(n) (Eq. 2 with n_r = u_r + 1 valid positions);
   // (E, gamma) = argmax_{l in [1,L), d in [0,d_max]} TPL(l, d) (Eq. 1, Section 4.3).
@@ -58,6 +76,7 @@ struct Policy {
       }
     }
     next_E = bl; next_gamma = bd;
+    thresholds();
   }
 };
 
@@ -87,7 +106,10 @@ struct del_ctx {
   uint16_t* xs_h = nullptr; uint16_t* xs_attn = nullptr; uint16_t* xs_h1 = nullptr; uint16_t* xs_act = nullptr;
   float* ssq_h = nullptr; float* ssq_h1 = nullptr;
   float* PM = nullptr; float* PL = nullptr; float* PA = nullptr; int nch_max = 0, attn_ct = 64, attn_S = 0, attn_dec_rows = 15;   // attn_S > 0: register decode kernel with S splits
-  float* pval = nullptr; int* pidx = nullptr;
+  float* pval = nullptr; int* pidx = nullptr; float* psum = nullptr;
+  float* conf_dev = nullptr;   // [Rmax] shadow confidences, then [d_max+1] draft confidences
+  float* conf_host = nullptr;  // pinned mirror
+  int* step_host = nullptr;    // pinned: (token id, confidence bits) of the last draft step
   int* state = nullptr; int* draft_ids = nullptr; int* shadow_ids = nullptr; int* result = nullptr;
   int* ids_dev = nullptr; int* result_host = nullptr;
   float* logits_dbg = nullptr; float* sink = nullptr;
@@ -101,6 +123,8 @@ struct del_ctx {
   Policy pol;
   int last_E = 0, last_gamma = 0, last_u = 0, last_n = 0;
   std::vector<int> last_c, last_shadow, last_draft;
+  std::vector<float> last_conf, last_draft_conf;   // like last_shadow / last_draft
+  int last_stopped = 0;
   float t_draft = 0, t_verify = 0, t_shadow = 0;
   int target_waves = 4096;
   // per-kernel profiling (off by default)
@@ -350,22 +374,23 @@ GemmP head_gemm(const del_ctx* ctx) {
   GemmP p = base_gemm(ctx);
   p.Wt = ctx->head_t; p.NB = ctx->NBv; p.KT = ctx->KTd; p.N = ctx->V; p.K = ctx->d;
   p.ldx = ctx->dpad; p.gain = ctx->gain_final(); p.rms = 1;
-  p.pval = ctx->pval; p.pidx = ctx->pidx;
+  p.pval = ctx->pval; p.pidx = ctx->pidx; p.psum = ctx->psum;
   return p;
 }
 
 // Final norm + LM head + arg-max on one row of the hidden buffer (the draft's head).
-del_status head_one(del_ctx* ctx, int layer, int row, int* out_id) {
+// Also the token's confidence (its soft-max probability, Section 4.4) into out_conf.
+del_status head_one(del_ctx* ctx, int layer, int row, int* out_id, float* out_conf) {
   GemmP p = head_gemm(ctx);
   p.X = ctx->hid_row(layer, row);
   del_status st = gemm(ctx, p, EPI_ARGMAX, 1, false);
   if (st != DEL_OK) return st;
-  HIPCHK(launch_argmax_finish(ctx->pval, ctx->pidx, 1, ctx->NBv, out_id, ctx->stream));
+  HIPCHK(launch_argmax_finish(ctx->pval, ctx->pidx, ctx->psum, 1, ctx->NBv, out_id, out_conf, ctx->stream));
   return DEL_OK;
 }
 
 // Shadow tokens (Section 4.2): final norm + LM head + arg-max of rows 0..m-1 of every layer
-// 1..L, into shadow_ids[(l-1)*m + i].
+// 1..L, into shadow_ids[(l-1)*m + i], and their confidences into conf_dev[(l-1)*m + i].
 del_status shadow_head(del_ctx* ctx, int m) {
   const int R = ctx->L * m;
   const bool mf = ctx->cfg.use_mfma && ctx->wd == DEL_DTYPE_BF16;
@@ -375,8 +400,8 @@ del_status shadow_head(del_ctx* ctx, int m) {
                              ctx->KTd, ctx->gain_final(), 1, ctx->cfg.rms_eps, ctx->xs_shadow, ctx->rowscale,
                              ctx->stream));
     const int pr = prof_begin(ctx, 2, EPI_ARGMAX, R, (int64_t)ctx->NBv * ctx->KTd * 1024);
-    HIPCHK(launch_head_gemm(ctx->head_t, ctx->NBv, ctx->KTd, ctx->V, ctx->xs_shadow, R, ctx->pval, ctx->pidx, &nparts,
-                            ctx->stream, pr >= 0 ? ctx->prof_ev[2 * pr] : nullptr,
+    HIPCHK(launch_head_gemm(ctx->head_t, ctx->NBv, ctx->KTd, ctx->V, ctx->xs_shadow, R, ctx->rowscale, ctx->pval,
+                            ctx->pidx, ctx->psum, &nparts, ctx->stream, pr >= 0 ? ctx->prof_ev[2 * pr] : nullptr,
                             pr >= 0 ? ctx->prof_ev[2 * pr + 1] : nullptr));
     prof_end(ctx, pr);
   } else {
@@ -388,7 +413,7 @@ del_status shadow_head(del_ctx* ctx, int m) {
       if (st != DEL_OK) return st;
     }
   }
-  HIPCHK(launch_argmax_finish(ctx->pval, ctx->pidx, R, nparts, ctx->shadow_ids, ctx->stream));
+  HIPCHK(launch_argmax_finish(ctx->pval, ctx->pidx, ctx->psum, R, nparts, ctx->shadow_ids, ctx->conf_dev, ctx->stream));
   return DEL_OK;
 }
 
@@ -396,11 +421,13 @@ void free_all(del_ctx* c) {
   void* ptrs[] = {c->arena, c->embed_t, (c->head_t != c->embed_t) ? c->head_t : nullptr, c->gains, c->kc, c->vc,
                   c->rope, c->hid, c->q, c->attn, c->act, c->xs_layer, c->xs_shadow, c->rowscale, c->xs_h, c->xs_attn,
                   c->xs_h1, c->xs_act, c->ssq_h, c->ssq_h1, c->PM, c->PL,
-                  c->PA, c->pval, c->pidx, c->state, c->draft_ids, c->shadow_ids, c->result, c->ids_dev,
+                  c->PA, c->pval, c->pidx, c->psum, c->conf_dev, c->state, c->draft_ids, c->shadow_ids, c->result, c->ids_dev,
                   c->logits_dbg, c->sink, c->stage};
   for (void* p : ptrs)
     if (p) (void)hipFree(p);
   if (c->result_host) (void)hipHostFree(c->result_host);
+  if (c->conf_host) (void)hipHostFree(c->conf_host);
+  if (c->step_host) (void)hipHostFree(c->step_host);
   for (auto& e : c->ev)
     if (e) (void)hipEventDestroy(e);
   for (auto& e : c->prof_ev)
@@ -460,6 +487,8 @@ del_status del_create(const del_config* cfg, void* hip_stream, del_ctx** out) {
   ctx->last_c.assign(ctx->L + 1, 0);
   ctx->last_shadow.assign((size_t)(ctx->L + 1) * (cfg->d_max + 1), 0);
   ctx->last_draft.assign(std::max(1, cfg->d_max), 0);
+  ctx->last_conf.assign((size_t)(ctx->L + 1) * (cfg->d_max + 1), 0.f);
+  ctx->last_draft_conf.assign((size_t)cfg->d_max + 1, 0.f);
   if (const char* tw = getenv("DEL_TARGET_WAVES")) {
     const int v = atoi(tw);
     if (v >= 64 && v <= 65536) ctx->target_waves = v;
@@ -571,6 +600,10 @@ del_status del_create(const del_config* cfg, void* hip_stream, del_ctx** out) {
   CK(dmalloc(&ctx->PA, prow * ctx->hd * 4));
   CK(dmalloc(&ctx->pval, (size_t)Rmax * ctx->NBv * 4));
   CK(dmalloc(&ctx->pidx, (size_t)Rmax * ctx->NBv * 4));
+  CK(dmalloc(&ctx->psum, (size_t)Rmax * ctx->NBv * 4));
+  CK(dmalloc(&ctx->conf_dev, (size_t)(Rmax + cfg->d_max + 1) * 4));
+  CK(hipHostMalloc((void**)&ctx->conf_host, (size_t)(Rmax + cfg->d_max + 1) * 4, hipHostMallocDefault));
+  CK(hipHostMalloc((void**)&ctx->step_host, 16, hipHostMallocDefault));
   CK(dmalloc(&ctx->state, 16));
   CK(hipMemsetAsync(ctx->state, 0, 16, ctx->stream));
   CK(dmalloc(&ctx->draft_ids, (size_t)(cfg->d_max + 1) * 4));
@@ -675,6 +708,7 @@ del_status del_prefill(del_ctx* ctx, const int32_t* prompt, int32_t n_prompt, in
   HIPCHK(launch_set_state(ctx->state, 0, 0, nullptr, -1, ctx->stream));
   const int w = std::min(ctx->cfg.prefill_window, P);
   std::vector<int> shadow((size_t)L * w, 0);  // [l-1][window position]
+  std::vector<float> sconf((size_t)L * w, 0.f);
   // chunks of up to 16 rows; a ragged chunk, if any, comes first so the last ones are full
   const int CH = 16;
   int start = 0;
@@ -691,11 +725,15 @@ del_status del_prefill(del_ctx* ctx, const int32_t* prompt, int32_t n_prompt, in
       if (st != DEL_OK) return st;
       HIPCHK(hipMemcpyAsync(ctx->result_host, ctx->shadow_ids, (size_t)L * mc * 4, hipMemcpyDeviceToHost,
                             ctx->stream));
+      HIPCHK(hipMemcpyAsync(ctx->conf_host, ctx->conf_dev, (size_t)L * mc * 4, hipMemcpyDeviceToHost, ctx->stream));
       HIPCHK(hipStreamSynchronize(ctx->stream));
       for (int i = 0; i < mc; ++i) {
         const int pos = start + i;
         if (pos < P - w) continue;
-        for (int l = 1; l <= L; ++l) shadow[(size_t)(l - 1) * w + (pos - (P - w))] = ctx->result_host[(l - 1) * mc + i];
+        for (int l = 1; l <= L; ++l) {
+          shadow[(size_t)(l - 1) * w + (pos - (P - w))] = ctx->result_host[(l - 1) * mc + i];
+          sconf[(size_t)(l - 1) * w + (pos - (P - w))] = ctx->conf_host[(l - 1) * mc + i];
+        }
       }
     }
     HIPCHK(launch_set_state(ctx->state, mc, -1, nullptr, -1, ctx->stream));
@@ -706,7 +744,13 @@ del_status del_prefill(del_ctx* ctx, const int32_t* prompt, int32_t n_prompt, in
   std::vector<int> c(L + 1, 0);
   for (int l = 1; l <= L; ++l)
     for (int i = 0; i < w; ++i) c[l] += shadow[(size_t)(l - 1) * w + i] == shadow[(size_t)(L - 1) * w + i];
-  ctx->pol.update(c.data(), w);
+  std::vector<double> tcs(L + 1, 0.0), fcs(L + 1, 0.0);
+  for (int l = 1; l <= L; ++l)
+    for (int i = 0; i < w; ++i) {
+      const bool hit = shadow[(size_t)(l - 1) * w + i] == shadow[(size_t)(L - 1) * w + i];
+      (hit ? tcs : fcs)[l] += (double)sconf[(size_t)(l - 1) * w + i];
+    }
+  ctx->pol.update(c.data(), w, tcs.data(), fcs.data());
   const int first = shadow[(size_t)(L - 1) * w + (w - 1)];
   HIPCHK(launch_set_state(ctx->state, 0, -1, nullptr, first, ctx->stream));
   HIPCHK(hipStreamSynchronize(ctx->stream));
@@ -717,16 +761,23 @@ del_status del_prefill(del_ctx* ctx, const int32_t* prompt, int32_t n_prompt, in
   return DEL_OK;
 }
 
-del_status del_round(del_ctx* ctx, int32_t E, int32_t gamma, int32_t* out_tokens, int32_t* n_out) {
+// One round.  tau < 0: draft exactly `gamma` tokens.  tau >= 0: dynamic draft-exiting (Section 4.4;
+// Algorithm 1 loop): draft up to `gamma` tokens, stop before appending the first one whose
+// confidence is below tau; the stopping step's exit state is the round's last row.
+static del_status round_impl(del_ctx* ctx, int E, int gamma, double tau, int32_t* out_tokens, int32_t* n_out,
+                             int32_t* gamma_used, int32_t* stopped_early) {
   if (!ctx || !out_tokens || !n_out) return DEL_E_ARG;
   if (ctx->phase != 1) return DEL_E_STATE;
   const int L = ctx->L;
   if (E < 1 || E > L || gamma < 0 || gamma > ctx->cfg.d_max) return DEL_E_ARG;
   if (ctx->T + gamma + 1 > ctx->Tcap) return DEL_E_CAPACITY;
-  const int m = gamma + 1;
+  const bool dynamic = tau >= 0.0;
+  const int Rmax = L * ctx->maxrows;
+  float* dconf = ctx->conf_dev + Rmax;   // draft confidences
   hipStream_t s = ctx->stream;
   HIPCHK(hipEventRecord(ctx->ev[0], s));
-  // ---- draft: gamma auto-regressive steps through layers 1..E + head
+  // ---- draft: auto-regressive steps through layers 1..E + head
+  bool stopped = false;
   for (int i = 0; i <= gamma; ++i) {
     const int* tok = i == 0 ? ctx->state + 1 : ctx->draft_ids + (i - 1);
     HIPCHK(launch_embed(ctx->embed_t, ctx->wd, ctx->KTd, ctx->V, tok, 1, ctx->hid_row(0, i), ctx->dpad, ctx->d, s));
@@ -735,10 +786,22 @@ del_status del_round(del_ctx* ctx, int32_t E, int32_t gamma, int32_t* out_tokens
       if (st != DEL_OK) return st;
     }
     if (i < gamma) {  // the last pending token needs no head: only its exit state and KV
-      del_status st = head_one(ctx, E, i, ctx->draft_ids + i);
+      del_status st = head_one(ctx, E, i, ctx->draft_ids + i, dconf + i);
       if (st != DEL_OK) return st;
+      if (dynamic) {  // the host decides whether to go on: one small copy and a sync per step
+        HIPCHK(hipMemcpyAsync(ctx->step_host, dconf + i, 4, hipMemcpyDeviceToHost, s));
+        HIPCHK(hipStreamSynchronize(s));
+        float cf;
+        memcpy(&cf, ctx->step_host, 4);
+        if ((double)cf < tau) {   // not appended; row i is the last row of the round
+          gamma = i;
+          stopped = true;
+          break;
+        }
+      }
     }
   }
+  const int m = gamma + 1;
   HIPCHK(hipEventRecord(ctx->ev[1], s));
   // ---- verify: the gamma+1 exit states through layers E+1..L
   for (int l = E + 1; l <= L; ++l) {
@@ -755,6 +818,8 @@ del_status del_round(del_ctx* ctx, int32_t E, int32_t gamma, int32_t* out_tokens
   HIPCHK(hipEventRecord(ctx->ev[3], s));
   const size_t nres = (size_t)3 + gamma + (size_t)L * m;
   HIPCHK(hipMemcpyAsync(ctx->result_host, ctx->result, nres * 4, hipMemcpyDeviceToHost, s));
+  HIPCHK(hipMemcpyAsync(ctx->conf_host, ctx->conf_dev, (size_t)L * m * 4, hipMemcpyDeviceToHost, s));
+  HIPCHK(hipMemcpyAsync(ctx->conf_host + Rmax, dconf, (size_t)(gamma + 1) * 4, hipMemcpyDeviceToHost, s));
   HIPCHK(hipStreamSynchronize(s));
   prof_collect(ctx);
   (void)hipEventElapsedTime(&ctx->t_draft, ctx->ev[0], ctx->ev[1]);
@@ -765,22 +830,50 @@ del_status del_round(del_ctx* ctx, int32_t E, int32_t gamma, int32_t* out_tokens
   const int* drafts = res + 3;
   const int* sh = res + 3 + gamma;  // [L][m]
   const int* target = sh + (size_t)(L - 1) * m;
-  // ---- statistics (Section 4.2): c^l over the valid positions 0..u, n = u + 1
+  float* cf = ctx->conf_host;       // [L][m]
+  const float* dcf = ctx->conf_host + Rmax;
+  // the drafted tokens are layer E's shadow tokens: their confidences are the draft's too
+  for (int i = 0; i < gamma; ++i) cf[(size_t)(E - 1) * m + i] = dcf[i];
+  // ---- statistics (Sections 4.2, 4.4): over the valid positions 0..u, n = u + 1
   std::vector<int> c(L + 1, 0);
+  std::vector<double> tcs(L + 1, 0.0), fcs(L + 1, 0.0);
   for (int l = 1; l <= L; ++l)
-    for (int i = 0; i <= u; ++i) c[l] += sh[(size_t)(l - 1) * m + i] == target[i];
-  ctx->pol.update(c.data(), u + 1);
+    for (int i = 0; i <= u; ++i) {
+      const bool hit = sh[(size_t)(l - 1) * m + i] == target[i];
+      c[l] += hit;
+      (hit ? tcs : fcs)[l] += (double)cf[(size_t)(l - 1) * m + i];
+    }
+  ctx->pol.update(c.data(), u + 1, tcs.data(), fcs.data());
   for (int i = 0; i <= u; ++i) out_tokens[i] = target[i];
   *n_out = u + 1;
+  if (gamma_used) *gamma_used = gamma;
+  if (stopped_early) *stopped_early = stopped ? 1 : 0;
   ctx->T = res[1]; ctx->pending = res[2];
   ctx->rounds += 1; ctx->last_rows = m;
   ctx->last_c = c; ctx->last_E = E; ctx->last_gamma = gamma; ctx->last_u = u; ctx->last_n = u + 1;
+  ctx->last_stopped = stopped ? 1 : 0;
   const int stride = ctx->cfg.d_max + 1;
   std::fill(ctx->last_shadow.begin(), ctx->last_shadow.end(), 0);
+  std::fill(ctx->last_conf.begin(), ctx->last_conf.end(), 0.f);
   for (int l = 1; l <= L; ++l)
-    for (int i = 0; i < m; ++i) ctx->last_shadow[(size_t)l * stride + i] = sh[(size_t)(l - 1) * m + i];
+    for (int i = 0; i < m; ++i) {
+      ctx->last_shadow[(size_t)l * stride + i] = sh[(size_t)(l - 1) * m + i];
+      ctx->last_conf[(size_t)l * stride + i] = cf[(size_t)(l - 1) * m + i];
+    }
   for (int i = 0; i < gamma; ++i) ctx->last_draft[i] = drafts[i];
+  std::fill(ctx->last_draft_conf.begin(), ctx->last_draft_conf.end(), 0.f);
+  for (int i = 0; i < gamma + (stopped ? 1 : 0); ++i) ctx->last_draft_conf[i] = dcf[i];
   return DEL_OK;
+}
+
+del_status del_round(del_ctx* ctx, int32_t E, int32_t gamma, int32_t* out_tokens, int32_t* n_out) {
+  return round_impl(ctx, E, gamma, -1.0, out_tokens, n_out, nullptr, nullptr);
+}
+
+del_status del_round_dynamic(del_ctx* ctx, int32_t E, double tau, int32_t d_cap, int32_t* out_tokens, int32_t* n_out,
+                             int32_t* gamma_used, int32_t* stopped_early) {
+  if (!(tau >= 0.0)) return DEL_E_ARG;
+  return round_impl(ctx, E, d_cap, tau, out_tokens, n_out, gamma_used, stopped_early);
 }
 
 del_status del_layer_stats(const del_ctx* ctx, del_stats* out) {
@@ -794,7 +887,13 @@ del_status del_layer_stats(const del_ctx* ctx, del_stats* out) {
     if (out->S_c) out->S_c[l] = ctx->pol.Sc[l];
     if (out->alpha) out->alpha[l] = ctx->pol.alpha[l];
     if (out->last_c) out->last_c[l] = ctx->last_c[l];
+    if (out->tau) out->tau[l] = ctx->pol.tau[l];
+    if (out->S_tcs) out->S_tcs[l] = ctx->pol.St[l];
+    if (out->S_fcs) out->S_fcs[l] = ctx->pol.Sf[l];
   }
+  out->last_stopped = ctx->last_stopped;
+  if (out->last_conf) memcpy(out->last_conf, ctx->last_conf.data(), ctx->last_conf.size() * 4);
+  if (out->last_draft_conf) memcpy(out->last_draft_conf, ctx->last_draft_conf.data(), ctx->last_draft_conf.size() * 4);
   if (out->last_shadow) memcpy(out->last_shadow, ctx->last_shadow.data(), ctx->last_shadow.size() * 4);
   if (out->last_draft)
     for (int i = 0; i < ctx->cfg.d_max; ++i) out->last_draft[i] = ctx->last_draft[i];
@@ -807,6 +906,12 @@ del_status del_set_layer_stats(del_ctx* ctx, const del_stats* in) {
   for (int l = 1; l <= ctx->L; ++l)
     if (!(in->S_c[l] >= 0.0)) return DEL_E_ARG;
   for (int l = 1; l <= ctx->L; ++l) ctx->pol.Sc[l] = in->S_c[l];
+  if (in->S_tcs && in->S_fcs)
+    for (int l = 1; l <= ctx->L; ++l) {
+      if (!(in->S_tcs[l] >= 0.0) || !(in->S_fcs[l] >= 0.0)) return DEL_E_ARG;
+      ctx->pol.St[l] = in->S_tcs[l];
+      ctx->pol.Sf[l] = in->S_fcs[l];
+    }
   ctx->pol.Sn = in->S_n;
   ctx->pol.select();
   return DEL_OK;

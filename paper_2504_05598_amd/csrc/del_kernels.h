@@ -51,6 +51,7 @@ struct GemmP {
   const float2* rope;           // [Tcap][hd/2] (cos, sin)
   float* ACT; int ldact; int d_ffn;  // SWIGLU
   float* pval; int* pidx;       // ARGMAX partials [rows][NB]
+  float* psum;                  // optional: sum of exp(logit - block max) per partial (confidence)
   int prow0;                    // first partial row of this call
   // matrix-core path only: the epilogue can also emit its result rows as the next GEMM's split
   // tiles (RESID: value * gain_out[n]; SWIGLU: the activation), plus, for RESID, the sum of
@@ -87,9 +88,9 @@ struct AttnP {
 hipError_t launch_gemm_valu(const GemmP& p, int epi, int waves, hipStream_t s);
 hipError_t launch_gemm_mfma(const GemmP& p, int epi, int waves, int col_blocks, hipStream_t s);
 // Shadow-head GEMM with fused arg-max over R rows; partials are [R][*n_slabs].
-hipError_t launch_head_gemm(const void* Wt, int NB, int KT, int N, const uint16_t* Xs, int R, float* pval,
-                            int* pidx, int* n_slabs, hipStream_t s, hipEvent_t ev_start = nullptr,
-                            hipEvent_t ev_stop = nullptr);
+hipError_t launch_head_gemm(const void* Wt, int NB, int KT, int N, const uint16_t* Xs, int R, const float* rowscale,
+                            float* pval, int* pidx, float* psum, int* n_slabs, hipStream_t s,
+                            hipEvent_t ev_start = nullptr, hipEvent_t ev_stop = nullptr);
 hipError_t launch_prep_split(const float* src, int rows, int rows_per_group, int64_t group_stride,
                              int ld, int K, int KT, const float* gain, int rms, float eps,
                              uint16_t* Xs, float* rowscale, hipStream_t s);
@@ -99,8 +100,9 @@ hipError_t launch_attention_merge(const AttnP& p, hipStream_t s);
 bool attention_decode_supported(int kvdtype, int hd, int G);
 hipError_t launch_embed(const void* Et, int wdtype, int KT, int vocab, const int* ids, int m,
                         float* out, int ld, int d_model, hipStream_t s);
-hipError_t launch_argmax_finish(const float* pval, const int* pidx, int rows, int NB,
-                                int* out_ids, hipStream_t s);
+// psum / out_conf may be null; out_conf[row] = soft-max probability of the arg-max token.
+hipError_t launch_argmax_finish(const float* pval, const int* pidx, const float* psum, int rows, int NB,
+                                int* out_ids, float* out_conf, hipStream_t s);
 hipError_t launch_accept(int* state, const int* draft_ids, int* shadow_ids, int L, int m, int E,
                          int gamma, int* result, hipStream_t s);
 hipError_t launch_set_state(int* state, int add_T, int set_T, const int* pending_src,

@@ -157,6 +157,12 @@ __device__ __forceinline__ void epilogue(const GemmP& p, int nb, float (*fin)[16
       const size_t o = (size_t)(p.prow0 + rowbase + mi) * p.NB + nb;
       p.pval[o] = best;
       p.pidx[o] = bi;
+      if (p.psum) {   // soft-max denominator of this block relative to its own maximum
+        float se = 0.f;
+        for (int r = 0; r < 16; ++r)
+          if (nb * 16 + r < p.N) se += expf(fin[mi][r] - best);
+        p.psum[o] = se;
+      }
     }
   }
 }
@@ -458,8 +464,9 @@ __global__ void __launch_bounds__(1024) gemm_mfma_k(GemmP p) {
 constexpr int HG_W = 8, HG_CB = 16;
 
 __global__ void __launch_bounds__(512) head_gemm_k(const uint4* __restrict__ Wt, int NB, int KT, int N,
-                                                   const uint4* __restrict__ Xs, int CB, int R, float* pval, int* pidx,
-                                                   int NS) {
+                                                   const uint4* __restrict__ Xs, int CB, int R,
+                                                   const float* __restrict__ rowscale, float* pval, int* pidx,
+                                                   float* psum, int NS) {
   extern __shared__ __align__(16) uint4 bs[];   // [2][HG_CB * 128]
   constexpr int U = 4;
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
@@ -527,20 +534,27 @@ __global__ void __launch_bounds__(512) head_gemm_k(const uint4* __restrict__ Wt,
     const uint4 aw = ld_stream(wp + (size_t)kt * 64);
     tile(aw, kt);
   }
-  // arg-max: lane holds rows 4g+j of its block for token lane%16 of every column block
+  // arg-max: lane holds rows 4g+j of its block for token lane%16 of every column block.  The
+  // per-row RMS scale is positive, so it cannot change the arg-max; it is applied because the
+  // stored maximum and the soft-max sums (confidence) are in logit units.
   float* wv = (float*)bs;                    // [HG_W][HG_CB][16]
   int* wi = (int*)(wv + HG_W * HG_CB * 16);
+  float* ws = (float*)(wi + HG_W * HG_CB * 16);
   const int g = lane >> 4, token = lane & 15;
 #pragma unroll
   for (int c = 0; c < HG_CB; ++c) {
     float best = -INFINITY;
     int bi = 0x7FFFFFFF;
+    float v[4];
+    const int row = (cb0 + c) * 16 + token;
+    const float sc = (c < ncb && row < R && rowscale) ? rowscale[row] : 1.0f;
+#pragma unroll
+    for (int j = 0; j < 4; ++j) v[j] = acc[c][j] * sc;
     if (c < ncb && rowok) {
 #pragma unroll
       for (int j = 0; j < 4; ++j) {
         const int n = nb * 16 + 4 * g + j;
-        const float v = acc[c][j];
-        if (n < N && v > best) { best = v; bi = n; }
+        if (n < N && v[j] > best) { best = v[j]; bi = n; }
       }
     }
 #pragma unroll
@@ -549,7 +563,21 @@ __global__ void __launch_bounds__(512) head_gemm_k(const uint4* __restrict__ Wt,
       const int oi = __shfl_xor(bi, o);
       if (ov > best || (ov == best && oi < bi)) { best = ov; bi = oi; }
     }
-    if (g == 0) { wv[(wave * HG_CB + c) * 16 + token] = best; wi[(wave * HG_CB + c) * 16 + token] = bi; }
+    float se = 0.f;
+    if (psum && c < ncb && rowok) {
+#pragma unroll
+      for (int j = 0; j < 4; ++j)
+        if (nb * 16 + 4 * g + j < N) se += expf(v[j] - best);
+    }
+    if (psum) {
+      se += __shfl_xor(se, 16);
+      se += __shfl_xor(se, 32);
+    }
+    if (g == 0) {
+      wv[(wave * HG_CB + c) * 16 + token] = best;
+      wi[(wave * HG_CB + c) * 16 + token] = bi;
+      ws[(wave * HG_CB + c) * 16 + token] = se;
+    }
   }
   __syncthreads();
   if (tid < HG_CB * 16) {
@@ -565,6 +593,14 @@ __global__ void __launch_bounds__(512) head_gemm_k(const uint4* __restrict__ Wt,
       }
       pval[(size_t)row * NS + slab] = best;
       pidx[(size_t)row * NS + slab] = bi;
+      if (psum) {
+        float se = 0.f;
+        for (int w = 0; w < HG_W; ++w) {
+          const float v = wv[(w * HG_CB + c) * 16 + t];
+          if (v > -INFINITY) se += ws[(w * HG_CB + c) * 16 + t] * expf(v - best);
+        }
+        psum[(size_t)row * NS + slab] = se;
+      }
     }
   }
 }
@@ -952,7 +988,10 @@ __global__ void __launch_bounds__(256) embed_k(const void* Et, int KT, int vocab
 }
 
 // Merge the per-row-block (max, index) partials of one logits row; lowest index wins ties.
-__global__ void __launch_bounds__(256) argmax_finish_k(const float* pval, const int* pidx, int NB, int* out_ids) {
+// With psum (per-block sums of exp(logit - block max)) also the confidence of the arg-max token:
+// its soft-max probability 1 / sum_b psum[b] * exp(max_b - max) (Section 4.4).
+__global__ void __launch_bounds__(256) argmax_finish_k(const float* pval, const int* pidx, const float* psum, int NB,
+                                                       int* out_ids, float* out_conf) {
   __shared__ float sv[256];
   __shared__ int si[256];
   const int row = blockIdx.x, tid = threadIdx.x;
@@ -973,7 +1012,23 @@ __global__ void __launch_bounds__(256) argmax_finish_k(const float* pval, const 
     }
     __syncthreads();
   }
+  const float M = sv[0];
   if (tid == 0) out_ids[row] = si[0];
+  if (psum && out_conf) {
+    __syncthreads();
+    float se = 0.f;
+    for (int b = tid; b < NB; b += 256) {
+      const float v = pval[(size_t)row * NB + b];
+      if (v > -INFINITY) se += psum[(size_t)row * NB + b] * expf(v - M);
+    }
+    sv[tid] = se;
+    __syncthreads();
+    for (int s = 128; s > 0; s >>= 1) {
+      if (tid < s) sv[tid] += sv[tid + s];
+      __syncthreads();
+    }
+    if (tid == 0) out_conf[row] = 1.0f / sv[0];
+  }
 }
 
 // Greedy acceptance on the device (Section 2, greedy special case): u = first i < gamma
@@ -1162,8 +1217,9 @@ hipError_t launch_gemm_mfma(const GemmP& p, int epi, int waves, int col_blocks, 
   return hipGetLastError();
 }
 
-hipError_t launch_head_gemm(const void* Wt, int NB, int KT, int N, const uint16_t* Xs, int R, float* pval, int* pidx,
-                            int* n_slabs, hipStream_t s, hipEvent_t ev_start, hipEvent_t ev_stop) {
+hipError_t launch_head_gemm(const void* Wt, int NB, int KT, int N, const uint16_t* Xs, int R, const float* rowscale,
+                            float* pval, int* pidx, float* psum, int* n_slabs, hipStream_t s, hipEvent_t ev_start,
+                            hipEvent_t ev_stop) {
   if (NB <= 0 || KT <= 0 || R <= 0) return hipErrorInvalidValue;
   const int CB = (R + 15) / 16, NS = (NB + HG_W - 1) / HG_W;
   const size_t lds = (size_t)2 * HG_CB * 128 * sizeof(uint4);
@@ -1175,10 +1231,10 @@ hipError_t launch_head_gemm(const void* Wt, int NB, int KT, int N, const uint16_
   }
   if (ev_start && ev_stop)
     hipExtLaunchKernelGGL(head_gemm_k, dim3(NS, (CB + HG_CB - 1) / HG_CB), dim3(512), (uint32_t)lds, s, ev_start, ev_stop,
-                          0, (const uint4*)Wt, NB, KT, N, (const uint4*)Xs, CB, R, pval, pidx, NS);
+                          0, (const uint4*)Wt, NB, KT, N, (const uint4*)Xs, CB, R, rowscale, pval, pidx, psum, NS);
   else
     hipLaunchKernelGGL(head_gemm_k, dim3(NS, (CB + HG_CB - 1) / HG_CB), dim3(512), lds, s, (const uint4*)Wt, NB, KT, N,
-                       (const uint4*)Xs, CB, R, pval, pidx, NS);
+                       (const uint4*)Xs, CB, R, rowscale, pval, pidx, psum, NS);
   *n_slabs = NS;
   return hipGetLastError();
 }
@@ -1252,8 +1308,9 @@ hipError_t launch_embed(const void* Et, int wdtype, int KT, int vocab, const int
   return hipGetLastError();
 }
 
-hipError_t launch_argmax_finish(const float* pval, const int* pidx, int rows, int NB, int* out_ids, hipStream_t s) {
-  hipLaunchKernelGGL(argmax_finish_k, dim3(rows), dim3(256), 0, s, pval, pidx, NB, out_ids);
+hipError_t launch_argmax_finish(const float* pval, const int* pidx, const float* psum, int rows, int NB, int* out_ids,
+                                float* out_conf, hipStream_t s) {
+  hipLaunchKernelGGL(argmax_finish_k, dim3(rows), dim3(256), 0, s, pval, pidx, psum, NB, out_ids, out_conf);
   return hipGetLastError();
 }
 

@@ -22,6 +22,7 @@ from synthdata import gen_tensor, iter_tensor_specs
 
 GAP_TOL = 1e-2     # oracle top-2 logit gap below which either of the top two ids is accepted
 HID_TOL = 2e-2     # bf16 weights, fp32 accumulation (stated by the benchmark contract)
+CONF_RTOL = 5e-3   # confidence = 1 / sum exp(logit - max): a few 1e-4 of logit error over the vocabulary
 
 
 def log(*a):
@@ -63,15 +64,24 @@ def _resync(ctx: DelContext, oracle: Oracle, prompt, emitted, rep: ParityReport)
     if first != emitted[-1]:
         ctx.set_pending(emitted[-1])
     L = oracle.L
-    ctx.set_stats([0.0] + [oracle.stats.S_c(l) for l in range(1, L + 1)], oracle.stats.S_n())
+    ctx.set_stats([0.0] + [oracle.stats.S_c(l) for l in range(1, L + 1)], oracle.stats.S_n(),
+                  [0.0] + [oracle.stats.S_tcs(l) for l in range(1, L + 1)],
+                  [0.0] + [oracle.stats.S_fcs(l) for l in range(1, L + 1)])
     T, pend = ctx.state()
     assert T == oracle.T and pend == oracle.pending
     rep.resyncs += 1
 
 
+def _close(a, b, rtol):
+    return abs(a - b) <= rtol * max(abs(a), abs(b)) + 1e-9
+
+
 def lockstep(cfg, oracle: Oracle, ctx: DelContext, prompt, n_tokens, schedule=None,
-             check_hidden=True, max_rounds=None) -> ParityReport:
-    """schedule: None = DEL-selected (E, gamma) from the oracle; or a fixed (E, gamma)."""
+             check_hidden=True, max_rounds=None, dynamic=False) -> ParityReport:
+    """schedule: None = DEL-selected (E, gamma) from the oracle; or a fixed (E, gamma).
+    dynamic: full DEL (Section 4.4): E from the oracle's selection, the draft loop stops on the
+    oracle's tau_E; a stop decision may differ only where the oracle's confidence is within
+    CONF_RTOL of the threshold."""
     rep = ParityReport()
     L, d_max = cfg.n_layers, cfg.d_max
     pre = oracle.prefill(prompt, keep_hidden=check_hidden)
@@ -98,14 +108,35 @@ def lockstep(cfg, oracle: Oracle, ctx: DelContext, prompt, n_tokens, schedule=No
         assert (gE, gg) == (pre.next_E, pre.next_gamma)
         for l in range(1, L + 1):
             assert st["alpha"][l] == pre.alpha[l] or abs(st["alpha"][l] - pre.alpha[l]) < 1e-12
+            assert _close(st["tau"][l], pre.tau[l], CONF_RTOL), ("prefill tau", l, st["tau"][l], pre.tau[l])
     else:
         _resync(ctx, oracle, prompt, emitted, rep)
     E, gamma = (pre.next_E, pre.next_gamma) if schedule is None else schedule
+    tau = pre.tau[E]
     while len(emitted) < n_tokens and (max_rounds is None or rep.rounds < max_rounds):
-        g = min(gamma, n_tokens - len(emitted) - 1)
-        r = oracle.round(E, g, keep_hidden=check_hidden)
-        out = ctx.round(E, g)
-        st = ctx.stats()
+        stop_flip = False
+        if dynamic:
+            g = min(cfg.d_max, n_tokens - len(emitted) - 1)
+            r = oracle.round(E, g, keep_hidden=check_hidden, tau=tau)
+            out, g_gpu, stopped = ctx.round_dynamic(E, tau, g)
+            st = ctx.stats()
+            if (g_gpu, stopped) != (r.gamma, r.stopped_early):
+                # the two sides stopped at different steps: tolerated only on a near-threshold confidence
+                k = min(g_gpu, r.gamma)
+                assert k < len(r.draft_conf) and _close(r.draft_conf[k], tau, CONF_RTOL), (
+                    f"round {rep.rounds + 1}: gpu drafted {g_gpu} (stopped {stopped}), oracle {r.gamma} "
+                    f"(stopped {r.stopped_early}), oracle confidences {r.draft_conf}, tau {tau}")
+                stop_flip = True
+                rep.flips += 1
+            g = min(g_gpu, r.gamma)
+            for i, cf in enumerate(st["last_draft_conf"][:g]):
+                if st["last_draft"][:i] == r.draft_ids[:i]:       # same inputs up to this step
+                    assert _close(cf, r.draft_conf[i], CONF_RTOL), ("draft confidence", i, cf, r.draft_conf[i])
+        else:
+            g = min(gamma, n_tokens - len(emitted) - 1)
+            r = oracle.round(E, g, keep_hidden=check_hidden)
+            out = ctx.round(E, g)
+            st = ctx.stats()
         rep.rounds += 1
         # rows whose inputs are the same on both sides: up to the first differing draft
         same_rows = g + 1
@@ -117,6 +148,9 @@ def lockstep(cfg, oracle: Oracle, ctx: DelContext, prompt, n_tokens, schedule=No
         for l in range(1, L + 1):
             for i in range(same_rows):
                 rep.compared_ids += 1
+                if st["last_shadow"][l][i] == r.shadow[l][i]:
+                    assert _close(st["last_conf"][l][i], r.conf[l][i], CONF_RTOL), (
+                        "confidence", rep.rounds, l, i, st["last_conf"][l][i], r.conf[l][i])
                 if st["last_shadow"][l][i] != r.shadow[l][i]:
                     assert r.gaps[l][i] < GAP_TOL, (
                         f"round {rep.rounds} E={E} g={g} layer {l} row {i}: gpu {st['last_shadow'][l][i]} "
@@ -131,7 +165,7 @@ def lockstep(cfg, oracle: Oracle, ctx: DelContext, prompt, n_tokens, schedule=No
                 rep.max_hidden_err = max(rep.max_hidden_err, err)
                 assert err <= HID_TOL, ("hidden", rep.rounds, l, err)
         emitted.extend(r.out_tokens)
-        if not flipped and same_rows == g + 1:
+        if not flipped and not stop_flip and same_rows == g + 1:
             # identical ids everywhere: counts, tokens, statistics and selection must be equal
             assert out == r.out_tokens, (out, r.out_tokens)
             assert st["last_u"] == r.u and st["last_n"] == r.n
@@ -142,27 +176,35 @@ def lockstep(cfg, oracle: Oracle, ctx: DelContext, prompt, n_tokens, schedule=No
                 assert abs(st["alpha"][l] - r.alpha[l]) <= 1e-9
             assert abs(st["S_n"] - r.S_n) <= 1e-9 * r.S_n
             assert (st["next_E"], st["next_gamma"]) == (r.next_E, r.next_gamma)
+            for l in range(1, L + 1):
+                assert _close(st["S_tcs"][l], r.S_tcs[l], CONF_RTOL) and _close(st["S_fcs"][l], r.S_fcs[l], CONF_RTOL)
+                assert _close(st["tau"][l], r.tau[l], CONF_RTOL), ("tau", l, st["tau"][l], r.tau[l])
             T, pend = ctx.state()
             assert T == oracle.T and pend == oracle.pending
         else:
             _resync(ctx, oracle, prompt, emitted, rep)
         if schedule is None:
             E, gamma = r.next_E, r.next_gamma
+        tau = r.tau[E]
     rep.tokens = emitted
     return rep
 
 
-def gpu_generate(ctx: DelContext, prompt, n_tokens, schedule=None):
+def gpu_generate(ctx: DelContext, prompt, n_tokens, schedule=None, dynamic=False):
     """Free-running generation through the C ABI with the library's own (E, gamma) choice
-    (or a fixed schedule).  Returns tokens and the per-round log."""
+    (or a fixed schedule; or, dynamic, the library's E and tau_E with draft-exiting).
+    Returns tokens and the per-round log."""
     first, E, gamma = ctx.prefill(prompt)
     if schedule is not None:
         E, gamma = schedule
     toks = [first]
     rounds = []
     while len(toks) < n_tokens:
-        g = min(gamma, n_tokens - len(toks) - 1)
-        out = ctx.round(E, g)
+        g = min(ctx.cfg.d_max if dynamic else gamma, n_tokens - len(toks) - 1)
+        if dynamic:
+            out, g, _ = ctx.round_dynamic(E, ctx.stats()["tau"][E], g)
+        else:
+            out = ctx.round(E, g)
         assert 1 <= len(out) <= g + 1
         rounds.append((E, g, len(out)))
         toks.extend(out)

@@ -69,9 +69,12 @@ def test_speculative_equals_autoregressive_on_gpu(name, n):
     vanilla, _ = gpu_generate(ctx, prompt, n, schedule=(1, 0))
     spec, rounds = gpu_generate(ctx, prompt, n)
     fixed, _ = gpu_generate(ctx, prompt, n, schedule=(max(1, cfg.n_layers // 4), min(4, cfg.d_max)))
+    full, rounds_full = gpu_generate(ctx, prompt, n, dynamic=True)
     k1 = _first_divergence_is_near_tie(ctx, cfg, prompt, vanilla, spec)
     k2 = _first_divergence_is_near_tie(ctx, cfg, prompt, vanilla, fixed)
-    log(f"[{name}] DEL-driven == vanilla for {k1}/{n} tokens, fixed schedule for {k2}/{n}; "
-        f"{len(rounds)} rounds, mean tokens/round {n / len(rounds):.2f}")
+    k3 = _first_divergence_is_near_tie(ctx, cfg, prompt, vanilla, full)
+    log(f"[{name}] DEL-driven == vanilla for {k1}/{n} tokens, fixed schedule for {k2}/{n}, full DEL "
+        f"(draft-exiting) for {k3}/{n}; {len(rounds)} rounds, mean tokens/round {n / len(rounds):.2f} "
+        f"({len(rounds_full)} rounds with draft-exiting)")
     assert all(1 <= e < cfg.n_layers and 0 <= g <= cfg.d_max for e, g, _ in rounds)
     ctx.close()

@@ -36,6 +36,38 @@ def test_del_driven_lockstep(name):
     ctx.close()
 
 
+@pytest.mark.parametrize("name", ["tiny", "mini_fp32", "mini_gqa", "mini_mha"])
+def test_full_del_with_draft_exiting_lockstep(name):
+    """Algorithm 1 in full: the exit layer from the TPL arg-max, the draft loop stopped by tau_E."""
+    from gpu_harness import lockstep
+    cfg, ctx, oracle = _setup(name)
+    prompt = gen_prompt(cfg).tolist()
+    rep = lockstep(cfg, oracle, ctx, prompt, cfg.gen_len, dynamic=True)
+    assert len(rep.tokens) >= cfg.gen_len
+    _check_report(rep, name + " dynamic")
+    ctx.close()
+
+
+def test_draft_exit_threshold_extremes():
+    """tau = 0 never stops (a fixed-length round); tau > 1 stops at once (a vanilla step)."""
+    from gpu_harness import gpu_context
+    cfg = get_config("mini_gqa")
+    ctx, _ = gpu_context(cfg)
+    prompt = gen_prompt(cfg).tolist()
+    ctx.prefill(prompt)
+    fixed = [ctx.round(2, cfg.d_max) for _ in range(4)]
+    ctx.prefill(prompt)
+    never = [ctx.round_dynamic(2, 0.0, cfg.d_max) for _ in range(4)]
+    assert [o for o, g, s in never] == fixed and all(g == cfg.d_max and not s for o, g, s in never)
+    ctx.prefill(prompt)
+    always = [ctx.round_dynamic(2, 1.5, cfg.d_max) for _ in range(6)]
+    assert all(g == 0 and s and len(o) == 1 for o, g, s in always)
+    ctx.prefill(prompt)
+    vanilla = [ctx.round(1, 0) for _ in range(6)]
+    assert [o for o, g, s in always] == vanilla
+    ctx.close()
+
+
 def test_tiny_all_exit_layers_and_lengths():
     """C1: E in {1,2,3} x gamma in {1..4}, 64 tokens each."""
     from gpu_harness import lockstep
