@@ -7,8 +7,10 @@
 #include <cstdio>
 #include <cstdlib>
 #include <cstring>
+#include <map>
 #include <new>
 #include <string>
+#include <tuple>
 #include <vector>
 
 #include "../../include/del.h"
@@ -127,6 +129,13 @@ struct del_ctx {
   int last_stopped = 0;
   float t_draft = 0, t_verify = 0, t_shadow = 0;
   int target_waves = 4096;
+  // Optional (DEL_GRAPHS=1): the segments of a round are captured once per (kind, E, gamma) into HIP
+  // graphs and replayed; positions and token ids live in device memory, so a graph depends on
+  // nothing else.  Off by default: on this GPU the kernels of a round already run back to back
+  // from plain launches, and replaying graphs measured no faster.
+  bool use_graphs = false;
+  bool own_stream = false;
+  std::map<std::tuple<int, int, int>, hipGraphExec_t> graphs;
   // per-kernel profiling (off by default)
   bool prof_on = false;
   std::vector<hipEvent_t> prof_ev;     // pairs
@@ -432,7 +441,40 @@ void free_all(del_ctx* c) {
     if (e) (void)hipEventDestroy(e);
   for (auto& e : c->prof_ev)
     if (e) (void)hipEventDestroy(e);
+  for (auto& g : c->graphs)
+    if (g.second) (void)hipGraphExecDestroy(g.second);
+  c->graphs.clear();
+  if (c->own_stream && c->stream) (void)hipStreamDestroy(c->stream);
 }
+
+// Run a segment of a round: eagerly (default), or as a HIP graph captured from the very same
+// enqueue code the first time this (kind, a, b) is seen and replayed afterwards.
+template <class F>
+del_status run_segment(del_ctx* ctx, int kind, int a, int b, F&& enqueue) {
+  if (!ctx->use_graphs || ctx->prof_on) return enqueue();
+  const auto key = std::make_tuple(kind, a, b);
+  auto it = ctx->graphs.find(key);
+  if (it == ctx->graphs.end()) {
+    if (ctx->graphs.size() >= 512) return enqueue();   // bounded cache: run the rest eagerly
+    hipGraph_t g = nullptr;
+    HIPCHK(hipStreamBeginCapture(ctx->stream, hipStreamCaptureModeRelaxed));
+    const del_status st = enqueue();
+    const hipError_t e = hipStreamEndCapture(ctx->stream, &g);
+    if (st != DEL_OK || e != hipSuccess) {
+      if (g) (void)hipGraphDestroy(g);
+      return st != DEL_OK ? st : ctx->fail(e, "hipStreamEndCapture");
+    }
+    hipGraphExec_t ge = nullptr;
+    const hipError_t e2 = hipGraphInstantiate(&ge, g, nullptr, nullptr, 0);
+    (void)hipGraphDestroy(g);
+    if (e2 != hipSuccess) return ctx->fail(e2, "hipGraphInstantiate");
+    it = ctx->graphs.emplace(key, ge).first;
+  }
+  HIPCHK(hipGraphLaunch(it->second, ctx->stream));
+  return DEL_OK;
+}
+
+enum { SEG_DRAFT = 0, SEG_VERIFY = 1, SEG_SHADOW = 2, SEG_STEP = 3, SEG_LAST = 4 };
 
 }  // namespace
 
@@ -467,6 +509,12 @@ del_status del_create(const del_config* cfg, void* hip_stream, del_ctx** out) {
   if (!ctx) return DEL_E_NOMEM;
   ctx->cfg = *cfg;
   ctx->stream = (hipStream_t)hip_stream;
+  if (const char* e = getenv("DEL_GRAPHS")) ctx->use_graphs = atoi(e) != 0;
+  if (!ctx->stream && ctx->use_graphs) {
+    // stream capture needs a stream of its own (default priority); the NULL stream cannot be captured
+    if (hipStreamCreateWithFlags(&ctx->stream, hipStreamNonBlocking) == hipSuccess) ctx->own_stream = true;
+    else { ctx->stream = nullptr; ctx->use_graphs = false; }
+  }
   ctx->L = cfg->n_layers; ctx->d = cfg->d_model; ctx->nq = cfg->n_q_heads; ctx->nkv = cfg->n_kv_heads;
   ctx->hd = cfg->head_dim; ctx->f = cfg->d_ffn; ctx->V = cfg->vocab; ctx->wd = cfg->weight_dtype;
   ctx->esize = ctx->wd == DEL_DTYPE_BF16 ? 2 : 4;
@@ -629,6 +677,9 @@ void del_destroy(del_ctx* ctx) {
 
 del_status del_load_weights(del_ctx* ctx, const del_tensor* tensors, int32_t n) {
   if (!ctx || (!tensors && n > 0) || n < 0) return DEL_E_ARG;
+  // device-resident sources were produced on the caller's streams: wait for them
+  for (int i = 0; i < n; ++i)
+    if (tensors[i].location == DEL_MEM_DEVICE) { HIPCHK(hipDeviceSynchronize()); break; }
   for (int i = 0; i < n; ++i) {
     const del_tensor& t = tensors[i];
     if (!t.data || t.kind < 0 || t.kind > DEL_T_WD) return DEL_E_ARG;
@@ -776,50 +827,84 @@ static del_status round_impl(del_ctx* ctx, int E, int gamma, double tau, int32_t
   float* dconf = ctx->conf_dev + Rmax;   // draft confidences
   hipStream_t s = ctx->stream;
   HIPCHK(hipEventRecord(ctx->ev[0], s));
-  // ---- draft: auto-regressive steps through layers 1..E + head
-  bool stopped = false;
-  for (int i = 0; i <= gamma; ++i) {
+  // one draft step: embed the pending token, layers 1..E on row i, optionally the head
+  auto draft_step = [&](int i, bool with_head, bool copy_conf) -> del_status {
     const int* tok = i == 0 ? ctx->state + 1 : ctx->draft_ids + (i - 1);
     HIPCHK(launch_embed(ctx->embed_t, ctx->wd, ctx->KTd, ctx->V, tok, 1, ctx->hid_row(0, i), ctx->dpad, ctx->d, s));
     for (int l = 1; l <= E; ++l) {
       del_status st = run_layer(ctx, l, i, 1, l > 1);
       if (st != DEL_OK) return st;
     }
-    if (i < gamma) {  // the last pending token needs no head: only its exit state and KV
+    if (with_head) {
       del_status st = head_one(ctx, E, i, ctx->draft_ids + i, dconf + i);
       if (st != DEL_OK) return st;
-      if (dynamic) {  // the host decides whether to go on: one small copy and a sync per step
-        HIPCHK(hipMemcpyAsync(ctx->step_host, dconf + i, 4, hipMemcpyDeviceToHost, s));
-        HIPCHK(hipStreamSynchronize(s));
-        float cf;
-        memcpy(&cf, ctx->step_host, 4);
-        if ((double)cf < tau) {   // not appended; row i is the last row of the round
-          gamma = i;
-          stopped = true;
-          break;
-        }
+      if (copy_conf) HIPCHK(hipMemcpyAsync(ctx->step_host, dconf + i, 4, hipMemcpyDeviceToHost, s));
+    }
+    return DEL_OK;
+  };
+  // ---- draft: auto-regressive steps through layers 1..E + head
+  bool stopped = false;
+  if (!dynamic) {
+    // the last pending token (step gamma) needs no head: only its exit state and KV
+    del_status st = run_segment(ctx, SEG_DRAFT, E, gamma, [&]() -> del_status {
+      for (int i = 0; i <= gamma; ++i) {
+        del_status st2 = draft_step(i, i < gamma, false);
+        if (st2 != DEL_OK) return st2;
+      }
+      return DEL_OK;
+    });
+    if (st != DEL_OK) return st;
+  } else {
+    const int cap = gamma;
+    for (int i = 0; i <= cap; ++i) {
+      if (i == cap) {   // all `cap` tokens appended: the last one still needs its exit state
+        del_status st = run_segment(ctx, SEG_LAST, E, i, [&]() { return draft_step(i, false, false); });
+        if (st != DEL_OK) return st;
+        break;
+      }
+      // the host decides whether to go on: one small copy and a sync per step
+      del_status st = run_segment(ctx, SEG_STEP, E, i, [&]() { return draft_step(i, true, true); });
+      if (st != DEL_OK) return st;
+      HIPCHK(hipStreamSynchronize(s));
+      float cf;
+      memcpy(&cf, ctx->step_host, 4);
+      if ((double)cf < tau) {   // not appended; row i is the last row of the round
+        gamma = i;
+        stopped = true;
+        break;
       }
     }
   }
   const int m = gamma + 1;
   HIPCHK(hipEventRecord(ctx->ev[1], s));
   // ---- verify: the gamma+1 exit states through layers E+1..L
-  for (int l = E + 1; l <= L; ++l) {
-    del_status st = run_layer(ctx, l, 0, m, l > E + 1);
+  {
+    del_status st = run_segment(ctx, SEG_VERIFY, E, m, [&]() -> del_status {
+      for (int l = E + 1; l <= L; ++l) {
+        del_status st2 = run_layer(ctx, l, 0, m, l > E + 1);
+        if (st2 != DEL_OK) return st2;
+      }
+      return DEL_OK;
+    });
     if (st != DEL_OK) return st;
   }
   HIPCHK(hipEventRecord(ctx->ev[2], s));
-  // ---- shadow tokens of every layer (row L = the target's tokens), acceptance on device
+  // ---- shadow tokens of every layer (row L = the target's tokens), acceptance on device,
+  //      results to pinned host memory
   {
-    del_status st = shadow_head(ctx, m);
+    del_status st = run_segment(ctx, SEG_SHADOW, E, gamma, [&]() -> del_status {
+      del_status st2 = shadow_head(ctx, m);
+      if (st2 != DEL_OK) return st2;
+      HIPCHK(launch_accept(ctx->state, ctx->draft_ids, ctx->shadow_ids, L, m, E, gamma, ctx->result, s));
+      const size_t nres = (size_t)3 + gamma + (size_t)L * m;
+      HIPCHK(hipMemcpyAsync(ctx->result_host, ctx->result, nres * 4, hipMemcpyDeviceToHost, s));
+      HIPCHK(hipMemcpyAsync(ctx->conf_host, ctx->conf_dev, (size_t)L * m * 4, hipMemcpyDeviceToHost, s));
+      HIPCHK(hipMemcpyAsync(ctx->conf_host + Rmax, dconf, (size_t)(gamma + 1) * 4, hipMemcpyDeviceToHost, s));
+      return DEL_OK;
+    });
     if (st != DEL_OK) return st;
   }
-  HIPCHK(launch_accept(ctx->state, ctx->draft_ids, ctx->shadow_ids, L, m, E, gamma, ctx->result, s));
   HIPCHK(hipEventRecord(ctx->ev[3], s));
-  const size_t nres = (size_t)3 + gamma + (size_t)L * m;
-  HIPCHK(hipMemcpyAsync(ctx->result_host, ctx->result, nres * 4, hipMemcpyDeviceToHost, s));
-  HIPCHK(hipMemcpyAsync(ctx->conf_host, ctx->conf_dev, (size_t)L * m * 4, hipMemcpyDeviceToHost, s));
-  HIPCHK(hipMemcpyAsync(ctx->conf_host + Rmax, dconf, (size_t)(gamma + 1) * 4, hipMemcpyDeviceToHost, s));
   HIPCHK(hipStreamSynchronize(s));
   prof_collect(ctx);
   (void)hipEventElapsedTime(&ctx->t_draft, ctx->ev[0], ctx->ev[1]);

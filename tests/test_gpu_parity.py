@@ -187,3 +187,40 @@ def test_rounds_are_deterministic():
     h2 = ctx.hidden(cfg.n_layers, 0)
     assert t1 == t2 and r1 == r2 and np.array_equal(h1, h2)
     ctx.close()
+
+
+def test_graph_replays_match_eager_launches():
+    """With DEL_GRAPHS=1 round segments are captured into HIP graphs on first use and replayed.  Every
+    replay must give what eager launches give: same tokens, statistics and hidden rows, with
+    eager work (prefill, statistics, debug reads) between the replays."""
+    import os
+    from gpu_harness import gpu_context
+    cfg = get_config("mini_gqa")
+    prompt = gen_prompt(cfg).tolist()
+    eager, _ = gpu_context(cfg)
+    os.environ["DEL_GRAPHS"] = "1"
+    try:
+        graphed, _ = gpu_context(cfg)
+    finally:
+        del os.environ["DEL_GRAPHS"]
+    for rep in range(3):                      # the 2nd and 3rd pass replay the graphs captured in the 1st
+        fa = eager.prefill(prompt)
+        fb = graphed.prefill(prompt)
+        assert fa == fb
+        for k in range(10):
+            if k % 2 == 0:
+                st = eager.stats()
+                a = eager.round(st["next_E"], st["next_gamma"])
+                b = graphed.round(st["next_E"], st["next_gamma"])
+            else:
+                st = eager.stats()
+                E = st["next_E"]
+                a = eager.round_dynamic(E, st["tau"][E], cfg.d_max)
+                b = graphed.round_dynamic(E, st["tau"][E], cfg.d_max)
+            assert a == b, (rep, k, a, b)
+            sa, sb = eager.stats(), graphed.stats()
+            assert sa == sb, (rep, k)
+            g = sa["last_gamma"]
+            for l in (1, cfg.n_layers):
+                assert np.array_equal(eager.hidden(l, g), graphed.hidden(l, g))
+    eager.close(); graphed.close()
