@@ -107,7 +107,7 @@ struct del_ctx {
   uint16_t* xs_layer = nullptr; uint16_t* xs_shadow = nullptr; float* rowscale = nullptr;
   uint16_t* xs_h = nullptr; uint16_t* xs_attn = nullptr; uint16_t* xs_h1 = nullptr; uint16_t* xs_act = nullptr;
   float* ssq_h = nullptr; float* ssq_h1 = nullptr;
-  float* PM = nullptr; float* PL = nullptr; float* PA = nullptr; int nch_max = 0, attn_ct = 64, attn_S = 0, attn_dec_rows = 15;   // attn_S > 0: register decode kernel with S splits
+  float* PM = nullptr; float* PL = nullptr; float* PA = nullptr; int nch_max = 0, attn_ct = 64, attn_S = 0, attn_dec_rows = 16;   // attn_S > 0: register decode kernel with S splits
   float* pval = nullptr; int* pidx = nullptr; float* psum = nullptr;
   float* conf_dev = nullptr;   // [Rmax] shadow confidences, then [d_max+1] draft confidences
   float* conf_host = nullptr;  // pinned mirror

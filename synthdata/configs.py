@@ -89,6 +89,9 @@ CONFIGS = {
                             45, 48, 6, 11, norm_gain_std=0.1),
     "mini_mha": ModelConfig("mini_mha", 5, 384, 3, 3, 128, 1000, 5000, 1e4, False, "bf16", 0.7,
                             70, 40, 9, 12, norm_gain_std=0.1),
+    # one kv head for eight query heads, n_q*head_dim != d_model
+    "mini_g8": ModelConfig("mini_g8", 4, 256, 8, 1, 128, 704, 3000, 1e4, False, "bf16", 0.6,
+                           53, 40, 7, 14, norm_gain_std=0.1),
     "mini_fp32": ModelConfig("mini_fp32", 3, 192, 6, 2, 32, 520, 3000, 1e4, False, "fp32", 0.6,
                              21, 24, 5, 13, norm_gain_std=0.1),
 }

@@ -25,7 +25,7 @@ def _check_report(rep, name):
     assert rep.flips <= max(2, 0.02 * rep.compared_ids)
 
 
-@pytest.mark.parametrize("name", ["tiny", "mini_fp32", "mini_gqa", "mini_mha"])
+@pytest.mark.parametrize("name", ["tiny", "mini_fp32", "mini_gqa", "mini_mha", "mini_g8"])
 def test_del_driven_lockstep(name):
     from gpu_harness import lockstep
     cfg, ctx, oracle = _setup(name)
@@ -36,7 +36,7 @@ def test_del_driven_lockstep(name):
     ctx.close()
 
 
-@pytest.mark.parametrize("name", ["tiny", "mini_fp32", "mini_gqa", "mini_mha"])
+@pytest.mark.parametrize("name", ["tiny", "mini_fp32", "mini_gqa", "mini_mha", "mini_g8"])
 def test_full_del_with_draft_exiting_lockstep(name):
     """Algorithm 1 in full: the exit layer from the TPL arg-max, the draft loop stopped by tau_E."""
     from gpu_harness import lockstep
@@ -80,7 +80,7 @@ def test_tiny_all_exit_layers_and_lengths():
     ctx.close()
 
 
-@pytest.mark.parametrize("name,use_mfma", [("mini_gqa", False), ("mini_mha", False), ("mini_gqa", True)])
+@pytest.mark.parametrize("name,use_mfma", [("mini_gqa", False), ("mini_mha", False), ("mini_gqa", True), ("mini_g8", True)])
 def test_fixed_schedules_and_degenerate_rounds(name, use_mfma):
     """gamma = 0 (vanilla step), E = L with gamma = 1 (always accepted), gamma = d_max, and the
     vector-ALU multi-row path for bf16 weights (use_mfma = 0)."""
