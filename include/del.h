@@ -189,6 +189,16 @@ typedef struct {
 del_status del_profile_enable(del_ctx* ctx, int32_t on);   /* also clears the counters */
 del_status del_profile_read(const del_ctx* ctx, del_prof_entry* out, int32_t cap, int32_t* n);
 
+/* Host-only helpers (no context, no device): the policy arithmetic the library applies after
+ * every round, exposed so that it can be checked on its own.
+ * del_policy_step: one update of the running sums (Section 4.2: S <- omega*S + a for c^l, n, and
+ * Section 4.4 for tcs^l, fcs^l; arrays indexed by layer number 0..L, entry 0 unused; tcs/fcs and
+ * their sums may be NULL), then alpha_l (Eq. 2), tau_l (Eq. 3; NULL to skip) and the arg-max of
+ * TPL(l, d) over l in [1, L), d in [0, d_max] (Eq. 1, Section 4.3; first maximum, l then d ascending). */
+del_status del_policy_step(int32_t n_layers, int32_t d_max, double omega, const int32_t* c, int32_t n,
+                           const double* tcs, const double* fcs, double* S_c, double* S_n, double* S_tcs,
+                           double* S_fcs, double* alpha, double* tau, int32_t* next_E, int32_t* next_gamma);
+
 const char* del_strerror(del_status s);
 const char* del_last_error_text(const del_ctx* ctx);
 

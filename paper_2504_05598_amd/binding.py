@@ -15,7 +15,7 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 
 EXPORTS = ["del_create", "del_destroy", "del_load_weights", "del_prefill", "del_round", "del_round_dynamic",
            "del_layer_stats", "del_set_layer_stats", "del_last_timings", "del_debug_hidden",
-           "del_debug_logits", "del_debug_state", "del_debug_set_pending", "del_profile_enable", "del_profile_read", "del_bench_stream_read", "del_bench_stream_copy", "del_strerror",
+           "del_debug_logits", "del_debug_state", "del_debug_set_pending", "del_profile_enable", "del_profile_read", "del_policy_step", "del_bench_stream_read", "del_bench_stream_copy", "del_strerror",
            "del_last_error_text"]
 
 DEL_DTYPE_FP32, DEL_DTYPE_BF16 = 0, 1
@@ -100,6 +100,9 @@ def load_library():
     lib.del_profile_read.argtypes = [C.c_void_p, P(del_prof_entry), C.c_int32, P(C.c_int32)]
     lib.del_bench_stream_read.argtypes = [C.c_void_p, C.c_int64, C.c_int32, P(C.c_float)]
     lib.del_bench_stream_copy.argtypes = [C.c_void_p, C.c_int64, C.c_int32, P(C.c_float)]
+    lib.del_policy_step.argtypes = [C.c_int32, C.c_int32, C.c_double, P(C.c_int32), C.c_int32, P(C.c_double),
+                                    P(C.c_double), P(C.c_double), P(C.c_double), P(C.c_double), P(C.c_double),
+                                    P(C.c_double), P(C.c_double), P(C.c_int32), P(C.c_int32)]
     lib.del_strerror.argtypes = [C.c_int]
     lib.del_strerror.restype = C.c_char_p
     lib.del_last_error_text.argtypes = [C.c_void_p]
@@ -220,6 +223,22 @@ def del_last_timings(ctx) -> Tuple[float, float, float]:
     a, b, c = C.c_float(), C.c_float(), C.c_float()
     _check(load_library().del_last_timings(ctx, C.byref(a), C.byref(b), C.byref(c)), ctx)
     return a.value, b.value, c.value
+
+
+def del_policy_step(n_layers: int, d_max: int, omega: float, c: Sequence[int], n: int,
+                    tcs: Sequence[float], fcs: Sequence[float], state: dict) -> dict:
+    """One host-only policy update.  state: {"S_c", "S_n", "S_tcs", "S_fcs"} (lists indexed by layer
+    number); returns the new state plus alpha, tau, next_E, next_gamma."""
+    L = n_layers
+    D = C.c_double * (L + 1)
+    S_c, S_t, S_f = D(*state["S_c"]), D(*state["S_tcs"]), D(*state["S_fcs"])
+    S_n = C.c_double(state["S_n"])
+    alpha, tau = D(), D()
+    E, g = C.c_int32(), C.c_int32()
+    _check(load_library().del_policy_step(L, d_max, omega, (C.c_int32 * (L + 1))(*c), n, D(*tcs), D(*fcs),
+                                          S_c, C.byref(S_n), S_t, S_f, alpha, tau, C.byref(E), C.byref(g)))
+    return {"S_c": list(S_c), "S_n": S_n.value, "S_tcs": list(S_t), "S_fcs": list(S_f), "alpha": list(alpha),
+            "tau": list(tau), "next_E": E.value, "next_gamma": g.value}
 
 
 # ---- convenience wrapper ----------------------------------------------------------------

@@ -1055,6 +1055,34 @@ del_status del_profile_read(const del_ctx* ctx, del_prof_entry* out, int32_t cap
   return DEL_OK;
 }
 
+del_status del_policy_step(int32_t n_layers, int32_t d_max, double omega, const int32_t* c, int32_t n,
+                           const double* tcs, const double* fcs, double* S_c, double* S_n, double* S_tcs,
+                           double* S_fcs, double* alpha, double* tau, int32_t* next_E, int32_t* next_gamma) {
+  if (n_layers < 1 || d_max < 0 || !(omega >= 0.0 && omega <= 1.0) || !c || n < 0 || !S_c || !S_n || !alpha ||
+      !next_E || !next_gamma)
+    return DEL_E_ARG;
+  const bool conf = tcs && fcs && S_tcs && S_fcs;
+  Policy pol;
+  pol.reset(n_layers, d_max, omega);
+  std::vector<double> zero(n_layers + 1, 0.0);
+  for (int l = 1; l <= n_layers; ++l) {
+    pol.Sc[l] = S_c[l];
+    if (conf) { pol.St[l] = S_tcs[l]; pol.Sf[l] = S_fcs[l]; }
+  }
+  pol.Sn = *S_n;
+  pol.update(c, n, conf ? tcs : zero.data(), conf ? fcs : zero.data());
+  for (int l = 1; l <= n_layers; ++l) {
+    S_c[l] = pol.Sc[l];
+    alpha[l] = pol.alpha[l];
+    if (conf) { S_tcs[l] = pol.St[l]; S_fcs[l] = pol.Sf[l]; }
+    if (tau) tau[l] = pol.tau[l];
+  }
+  *S_n = pol.Sn;
+  *next_E = pol.next_E;
+  *next_gamma = pol.next_gamma;
+  return DEL_OK;
+}
+
 del_status del_debug_set_pending(del_ctx* ctx, int32_t token) {
   if (!ctx || token < 0 || token >= ctx->V) return DEL_E_ARG;
   if (ctx->phase != 1) return DEL_E_STATE;
