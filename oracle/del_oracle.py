@@ -52,6 +52,24 @@ the pins in tests/ cover the mathematics around them):
       row.  In Eq. 3 the mismatched count is n - c (reading R1) and a ratio
       whose denominator is zero (no matched, or no mismatched, token seen yet)
       counts as 0.
+  R19 speculative sampling (Section 2, "Speculative decoding"; Appendix on the
+      inference setup: temperature and top_p).  The paper names temperature and
+      top_p and leaves their definition to the sampling library; here a logits
+      row becomes a distribution by soft-max of logits/temperature, then the
+      nucleus: tokens ordered by falling logit (lower id first among equals),
+      the shortest leading run whose mass reaches top_p is kept and
+      renormalised.  A uniform number r in [0, 1) picks the first token, in
+      token-id order, whose cumulative probability exceeds r.  A drafted token
+      x is accepted when r * q(x) < p(x), which accepts with probability
+      min(1, p(x)/q(x)); after the first rejection the next token comes from
+      max(0, p - q) renormalised, and after gamma acceptances from p at the
+      last position.  The uniform numbers are inputs (gamma for the drafts,
+      gamma for the acceptances, one for the last token).  All of this runs in
+      fp64 on the fp32-rounded logits.
+  R20 statistics under sampling: shadow tokens are greedy at every layer,
+      layer L included (Section 4.2 obtains them by greedy decoding), u_r is
+      the number of drafted tokens the sampling rule accepted, and c^l, tcs^l,
+      fcs^l compare layer l's shadow tokens with layer L's over rows 0..u_r.
 """
 from __future__ import annotations
 
@@ -134,6 +152,60 @@ def matched_counts(shadow: Sequence[Sequence[int]], target: Sequence[int], u: in
     for l in range(1, len(shadow)):
         out.append(sum(1 for i in range(u + 1) if int(shadow[l][i]) == int(target[i])))
     return out
+
+
+# --------------------------------------------------------------------------
+# Speculative sampling (Section 2, "Speculative decoding"; reading R19)
+# --------------------------------------------------------------------------
+
+def tempered_nucleus(logits: torch.Tensor, temperature: float, top_p: float) -> torch.Tensor:
+    """Distribution a logits row is sampled from: soft-max(logits / temperature) restricted to the
+    nucleus of mass top_p and renormalised.  fp64 on the fp32-rounded logits."""
+    assert temperature > 0.0 and 0.0 < top_p
+    z = logits.reshape(-1).to(torch.float32).to(torch.float64)
+    p = torch.softmax(z / temperature, dim=0)
+    if top_p >= 1.0:
+        return p
+    order = torch.sort(-z, stable=True).indices          # falling logit, lower id first among equals
+    cum = torch.cumsum(p[order], dim=0)
+    reached = torch.nonzero(cum >= top_p)
+    k = int(reached[0, 0]) if reached.numel() else z.numel() - 1
+    kept = order[:k + 1]
+    out = torch.zeros_like(p)
+    out[kept] = p[kept]
+    return out / out.sum()
+
+
+def inverse_cdf(p: torch.Tensor, r: float) -> int:
+    """First token, in id order, whose cumulative mass exceeds r times the total mass."""
+    assert 0.0 <= r < 1.0
+    cdf = torch.cumsum(p.to(torch.float64), dim=0)
+    over = torch.nonzero(cdf > r * cdf[-1])
+    if over.numel():
+        return int(over[0, 0])
+    return int(torch.nonzero(p > 0)[-1, 0])
+
+
+def residual_distribution(p: torch.Tensor, q: torch.Tensor) -> torch.Tensor:
+    """max(0, p - q), renormalised: what a rejected position is resampled from."""
+    res = torch.clamp(p - q, min=0.0)
+    total = res.sum()
+    return res / total if float(total) > 0.0 else p.clone()
+
+
+def speculative_accept(drafts: Sequence[int], q: Sequence[torch.Tensor], p: Sequence[torch.Tensor],
+                       r_accept: Sequence[float], r_last: float) -> Tuple[int, int, torch.Tensor]:
+    """Acceptance of gamma = len(drafts) drafted tokens.  q[i] is the distribution drafts[i] was drawn
+    from, p[0..gamma] the target's distributions.  Returns (u, token, dist): u drafted tokens are
+    accepted and `token`, drawn from `dist` with r_last, follows them."""
+    gamma = len(drafts)
+    assert len(q) == gamma and len(p) == gamma + 1 and len(r_accept) >= gamma
+    for i in range(gamma):
+        x = int(drafts[i])
+        if not float(r_accept[i]) * float(q[i][x]) < float(p[i][x]):
+            dist = residual_distribution(p[i], q[i])
+            return i, inverse_cdf(dist, r_last), dist
+    return gamma, inverse_cdf(p[gamma], r_last), p[gamma]
 
 
 class DelStats:
@@ -248,6 +320,11 @@ class RoundRecord:
     tau: Optional[List[float]] = None               # thresholds after the update
     S_tcs: Optional[List[float]] = None
     S_fcs: Optional[List[float]] = None
+    # speculative sampling only (reading R19): the distributions every decision was taken from
+    q_dists: Optional[List[torch.Tensor]] = None    # [gamma] draft distributions
+    p_dists: Optional[List[torch.Tensor]] = None    # [gamma+1] target distributions
+    last_dist: Optional[torch.Tensor] = None        # what the round's last token was drawn from
+    uniforms: Optional[List[float]] = None
 
 
 @dataclass
@@ -391,6 +468,7 @@ class Oracle:
             h = self.layer(l, h, 0)
             hid[l] = h[P - w:]
         self.T = P
+        self._last_row = hid[self.L, w - 1].clone()
         shadow = [[0] * w]
         gaps = [[0.0] * w]
         conf = [[0.0] * w]
@@ -482,6 +560,75 @@ class Oracle:
                            [0.0] + [self.stats.S_tcs(l) for l in range(1, L + 1)],
                            [0.0] + [self.stats.S_fcs(l) for l in range(1, L + 1)])
 
+    # ---- speculative sampling (Section 2; readings R19, R20) ----
+    def sample_first(self, temperature: float, top_p: float, r: float) -> Tuple[int, torch.Tensor]:
+        """Replace the greedy first token of the prefill by one drawn from the target's
+        distribution at the last prompt position."""
+        dist = tempered_nucleus(self.logits(self._last_row[None, :])[0], temperature, top_p)
+        tok = inverse_cdf(dist, r)
+        self.pending = tok
+        return tok, dist
+
+    def round_sample(self, E: int, gamma: int, temperature: float, top_p: float,
+                     uniforms: Sequence[float], keep_hidden: bool = False) -> RoundRecord:
+        """One self-speculative round with sampled drafts and the sampling acceptance rule.
+        uniforms: gamma numbers for the drafts, gamma for the acceptances, one for the last token."""
+        L, d = self.L, self.cfg.d_model
+        assert 1 <= E <= L and 0 <= gamma and len(uniforms) >= 2 * gamma + 1
+        assert self.pending is not None, "prefill first"
+        T = self.T
+        assert T + gamma + 1 <= self.max_context
+        r_draft = [float(x) for x in uniforms[:gamma]]
+        r_acc = [float(x) for x in uniforms[gamma:2 * gamma]]
+        r_last = float(uniforms[2 * gamma])
+        hid = torch.zeros((L + 1, gamma + 1, d), dtype=self.dtype)
+        drafts: List[int] = []
+        q_dists: List[torch.Tensor] = []
+        tok = self.pending
+        for i in range(gamma + 1):
+            h = self.embed(tok)[None, :]
+            hid[0, i] = h[0]
+            for l in range(1, E + 1):
+                h = self.layer(l, h, T + i)
+                hid[l, i] = h[0]
+            if i < gamma:
+                qd = tempered_nucleus(self.logits(hid[E, i][None, :])[0], temperature, top_p)
+                tok = inverse_cdf(qd, r_draft[i])
+                q_dists.append(qd)
+                drafts.append(tok)
+        rows = hid[E].clone()
+        for l in range(E + 1, L + 1):
+            rows = self.layer(l, rows, T)
+            hid[l] = rows
+        shadow = [[0] * (gamma + 1)]
+        gaps = [[0.0] * (gamma + 1)]
+        conf = [[0.0] * (gamma + 1)]
+        for l in range(1, L + 1):
+            ids, g, cf = self.head_conf(hid[l])
+            shadow.append(ids)
+            gaps.append(g)
+            conf.append(cf)
+        target = shadow[L]
+        lgL = self.logits(hid[L])
+        p_dists = [tempered_nucleus(lgL[i], temperature, top_p) for i in range(gamma + 1)]
+        u, last, last_dist = speculative_accept(drafts, q_dists, p_dists, r_acc, r_last)
+        n = u + 1
+        out = drafts[:u] + [last]
+        c = matched_counts(shadow, target, u)
+        tcs, fcs = confidence_sums(shadow, conf, target, u)
+        self.stats.append(c, n, u, tcs, fcs)
+        alpha = self.stats.alpha()
+        nE, ng = self.stats.select()
+        self.T = T + u + 1
+        self.pending = last
+        return RoundRecord(E, gamma, T, drafts, target, u, n, out, shadow, gaps, c, alpha,
+                           [0.0] + [self.stats.S_c(l) for l in range(1, L + 1)],
+                           self.stats.S_n(), nE, ng, hid if keep_hidden else None,
+                           conf, None, False, tcs, fcs, self.stats.tau(),
+                           [0.0] + [self.stats.S_tcs(l) for l in range(1, L + 1)],
+                           [0.0] + [self.stats.S_fcs(l) for l in range(1, L + 1)],
+                           q_dists, p_dists, last_dist, list(map(float, uniforms[:2 * gamma + 1])))
+
     # ---- reference definitions used by the pins ----
     def vanilla_step(self) -> int:
         """One auto-regressive step of the full model on the pending token."""
@@ -563,6 +710,28 @@ def generate_del_full(oracle: Oracle, prompt: Sequence[int], n_tokens: int, keep
         recs.append(r)
         toks.extend(r.out_tokens)
         E, tau = r.next_E, r.tau[r.next_E]
+    return toks, pre, recs
+
+
+def generate_sample(oracle: Oracle, prompt: Sequence[int], n_tokens: int, temperature: float, top_p: float,
+                    uniforms_for, keep_hidden: bool = False, schedule=None,
+                    ) -> Tuple[List[int], PrefillRecord, List[RoundRecord]]:
+    """Speculative sampling with DEL choosing (E, gamma) every round (or schedule(round) if given).
+    uniforms_for(k, count) returns the uniform numbers of draw k: k = 0 is the first token (one
+    number), k = r + 1 is round r (2 * gamma + 1 numbers)."""
+    pre = oracle.prefill(prompt, keep_hidden)
+    first, _ = oracle.sample_first(temperature, top_p, float(uniforms_for(0, 1)[0]))
+    toks = [first]
+    E, gamma = pre.next_E, pre.next_gamma
+    recs = []
+    while len(toks) < n_tokens:
+        if schedule is not None:
+            E, gamma = schedule(len(recs))
+        g = min(gamma, n_tokens - len(toks) - 1)
+        r = oracle.round_sample(E, g, temperature, top_p, uniforms_for(len(recs) + 1, 2 * g + 1), keep_hidden)
+        recs.append(r)
+        toks.extend(r.out_tokens)
+        E, gamma = r.next_E, r.next_gamma
     return toks, pre, recs
 
 

@@ -7,8 +7,8 @@ that any element of any tensor can be produced on the CPU or on the GPU with
 identical bits.
 """
 from .configs import ModelConfig, CONFIGS, get_config
-from .generator import (gen_tensor, gen_prompt, tensor_shape, iter_tensor_specs,
+from .generator import (gen_tensor, gen_prompt, gen_uniforms, tensor_shape, iter_tensor_specs,
                         KINDS, GLOBAL_KINDS, LAYER_KINDS)
 
-__all__ = ["ModelConfig", "CONFIGS", "get_config", "gen_tensor", "gen_prompt",
+__all__ = ["ModelConfig", "CONFIGS", "get_config", "gen_tensor", "gen_prompt", "gen_uniforms",
            "tensor_shape", "iter_tensor_specs", "KINDS", "GLOBAL_KINDS", "LAYER_KINDS"]

@@ -146,6 +146,15 @@ def gen_prompt(cfg: ModelConfig, device="cpu", length: int | None = None) -> tor
     return (_lsr(z, 33) % cfg.vocab).to(torch.int32)
 
 
+def gen_uniforms(cfg: ModelConfig, stream: int, count: int) -> torch.Tensor:
+    """`count` numbers k / 2^24, k uniform in [0, 2^24), as float32 (exact): the random numbers a
+    sampling run consumes.  `stream` separates draws (e.g. the round number)."""
+    key = _s64(_mix_int(cfg.prompt_seed ^ _mix_int(0x756E6966 + 0x10001 * int(stream))))
+    e = torch.arange(1, count + 1, dtype=torch.int64)
+    z = _mix(e * _GOLDEN + key)
+    return (_lsr(z, 40).to(torch.float64) / float(1 << 24)).to(torch.float32)
+
+
 def iter_tensor_specs(cfg: ModelConfig) -> Iterator[Tuple[int, str]]:
     """(layer, kind) of every tensor a model needs, global tensors first."""
     yield (-1, "embed")
