@@ -189,6 +189,32 @@ typedef struct {
 del_status del_profile_enable(del_ctx* ctx, int32_t on);   /* also clears the counters */
 del_status del_profile_read(const del_ctx* ctx, del_prof_entry* out, int32_t cap, int32_t* n);
 
+/* Speculative sampling (Section 2, "Speculative decoding"; temperature and top_p of the inference
+ * setup in the appendix).  A logits row is turned into soft-max(logits / temperature) restricted to
+ * the nucleus of mass top_p (tokens by falling logit, lower id first among equals; the shortest
+ * leading run whose mass reaches top_p) and renormalised; a uniform number r in [0, 1) draws the
+ * first token, in id order, whose cumulative probability exceeds r.
+ *
+ * del_sample_first: only directly after del_prefill.  Replaces the greedy pending token by one drawn
+ *   with `r` from the target's distribution at the last prompt position; *token receives it.
+ * del_round_sample: one round like del_round, but the gamma drafts are drawn from the exit layer's
+ *   distributions, a draft x is accepted when r * q(x) < p(x) (probability min(1, p(x)/q(x))), the
+ *   first rejected position is redrawn from max(0, p - q) renormalised, and after gamma acceptances
+ *   one more token is drawn from p.  uniforms (host, 2*gamma+1 numbers in [0, 1)): gamma for the
+ *   drafts, gamma for the acceptances, one for the last token.  out_tokens (host, >= gamma+1) receives
+ *   the accepted drafts and the last token, *n_out their number.  Shadow tokens stay greedy at every
+ *   layer and the statistics count them over rows 0..u with u the number of accepted drafts.
+ *   temperature > 0, 0 < top_p <= 1, else DEL_E_ARG; otherwise the errors of del_round.
+ * del_debug_spec_sample: the same sampling arithmetic on logits the caller supplies (host,
+ *   q_logits [gamma][vocab], p_logits [gamma+1][vocab], row-major); no model, no state change.
+ *   drafts_out (host, gamma ints; may be NULL when gamma == 0), *u, *last_token. */
+del_status del_sample_first(del_ctx* ctx, double temperature, double top_p, float r, int32_t* token);
+del_status del_round_sample(del_ctx* ctx, int32_t E, int32_t gamma, double temperature, double top_p,
+                            const float* uniforms, int32_t* out_tokens, int32_t* n_out);
+del_status del_debug_spec_sample(del_ctx* ctx, const float* q_logits, const float* p_logits, int32_t gamma,
+                                 double temperature, double top_p, const float* uniforms, int32_t* drafts_out,
+                                 int32_t* u, int32_t* last_token);
+
 /* Host-only helpers (no context, no device): the policy arithmetic the library applies after
  * every round, exposed so that it can be checked on its own.
  * del_policy_step: one update of the running sums (Section 4.2: S <- omega*S + a for c^l, n, and

@@ -15,7 +15,7 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 
 EXPORTS = ["del_create", "del_destroy", "del_load_weights", "del_prefill", "del_round", "del_round_dynamic",
            "del_layer_stats", "del_set_layer_stats", "del_last_timings", "del_debug_hidden",
-           "del_debug_logits", "del_debug_state", "del_debug_set_pending", "del_profile_enable", "del_profile_read", "del_policy_step", "del_bench_stream_read", "del_bench_stream_copy", "del_strerror",
+           "del_debug_logits", "del_debug_state", "del_debug_set_pending", "del_profile_enable", "del_profile_read", "del_policy_step", "del_sample_first", "del_round_sample", "del_debug_spec_sample", "del_bench_stream_read", "del_bench_stream_copy", "del_strerror",
            "del_last_error_text"]
 
 DEL_DTYPE_FP32, DEL_DTYPE_BF16 = 0, 1
@@ -103,6 +103,11 @@ def load_library():
     lib.del_policy_step.argtypes = [C.c_int32, C.c_int32, C.c_double, P(C.c_int32), C.c_int32, P(C.c_double),
                                     P(C.c_double), P(C.c_double), P(C.c_double), P(C.c_double), P(C.c_double),
                                     P(C.c_double), P(C.c_double), P(C.c_int32), P(C.c_int32)]
+    lib.del_sample_first.argtypes = [C.c_void_p, C.c_double, C.c_double, C.c_float, P(C.c_int32)]
+    lib.del_round_sample.argtypes = [C.c_void_p, C.c_int32, C.c_int32, C.c_double, C.c_double, P(C.c_float),
+                                     P(C.c_int32), P(C.c_int32)]
+    lib.del_debug_spec_sample.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int32, C.c_double, C.c_double,
+                                          P(C.c_float), P(C.c_int32), P(C.c_int32), P(C.c_int32)]
     lib.del_strerror.argtypes = [C.c_int]
     lib.del_strerror.restype = C.c_char_p
     lib.del_last_error_text.argtypes = [C.c_void_p]
@@ -165,6 +170,37 @@ def del_round_dynamic(ctx, E: int, tau: float, d_cap: int) -> Tuple[List[int], i
     n, g, stop = C.c_int32(), C.c_int32(), C.c_int32()
     _check(load_library().del_round_dynamic(ctx, E, tau, d_cap, out, C.byref(n), C.byref(g), C.byref(stop)), ctx)
     return list(out[:n.value]), g.value, bool(stop.value)
+
+
+def del_sample_first(ctx, temperature: float, top_p: float, r: float) -> int:
+    tok = C.c_int32()
+    _check(load_library().del_sample_first(ctx, temperature, top_p, r, C.byref(tok)), ctx)
+    return tok.value
+
+
+def del_round_sample(ctx, E: int, gamma: int, temperature: float, top_p: float,
+                     uniforms: Sequence[float]) -> List[int]:
+    """uniforms: 2 * gamma + 1 numbers in [0, 1): drafts, acceptances, last token."""
+    if len(uniforms) < 2 * gamma + 1:
+        raise ValueError("need 2 * gamma + 1 uniform numbers")
+    un = (C.c_float * (2 * gamma + 1))(*[float(x) for x in uniforms[:2 * gamma + 1]])
+    out = (C.c_int32 * (gamma + 1))()
+    n = C.c_int32()
+    _check(load_library().del_round_sample(ctx, E, gamma, temperature, top_p, un, out, C.byref(n)), ctx)
+    return list(out[:n.value])
+
+
+def del_debug_spec_sample(ctx, q_logits, p_logits, gamma: int, temperature: float, top_p: float,
+                          uniforms: Sequence[float]) -> Tuple[List[int], int, int]:
+    """q_logits [gamma, vocab] and p_logits [gamma + 1, vocab]: contiguous float32 numpy arrays (host).
+    Returns (drafts, u, last token)."""
+    un = (C.c_float * (2 * gamma + 1))(*[float(x) for x in uniforms[:2 * gamma + 1]])
+    drafts = (C.c_int32 * max(1, gamma))()
+    u, last = C.c_int32(), C.c_int32()
+    qp = q_logits.ctypes.data if gamma > 0 else None
+    _check(load_library().del_debug_spec_sample(ctx, qp, p_logits.ctypes.data, gamma, temperature, top_p, un,
+                                                drafts, C.byref(u), C.byref(last)), ctx)
+    return list(drafts[:gamma]), u.value, last.value
 
 
 def del_layer_stats(ctx, n_layers: int, d_max: int) -> dict:
@@ -292,6 +328,15 @@ class DelContext:
 
     def round_dynamic(self, E: int, tau: float, d_cap: Optional[int] = None) -> Tuple[List[int], int, bool]:
         return del_round_dynamic(self.ctx, E, tau, self.cfg.d_max if d_cap is None else d_cap)
+
+    def sample_first(self, temperature: float, top_p: float, r: float) -> int:
+        return del_sample_first(self.ctx, temperature, top_p, r)
+
+    def round_sample(self, E: int, gamma: int, temperature: float, top_p: float, uniforms) -> List[int]:
+        return del_round_sample(self.ctx, E, gamma, temperature, top_p, uniforms)
+
+    def spec_sample(self, q_logits, p_logits, gamma: int, temperature: float, top_p: float, uniforms):
+        return del_debug_spec_sample(self.ctx, q_logits, p_logits, gamma, temperature, top_p, uniforms)
 
     def stats(self) -> dict:
         return del_layer_stats(self.ctx, self.cfg.n_layers, self.cfg.d_max)

@@ -8,7 +8,7 @@ import subprocess
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libdel_hip.so")
-SOURCES = ["del_kernels.hip", "del_api.hip"]
+SOURCES = ["del_kernels.hip", "del_sampling.hip", "del_api.hip"]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",
          # hipcc makes packed-fp32 instructions by itself from float code; keep them off
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",

@@ -115,6 +115,10 @@ struct del_ctx {
   int* state = nullptr; int* draft_ids = nullptr; int* shadow_ids = nullptr; int* result = nullptr;
   int* ids_dev = nullptr; int* result_host = nullptr;
   float* logits_dbg = nullptr; float* sink = nullptr;
+  // speculative sampling: logits and fixed-point weights of the draft rows [0, d_max] and of the
+  // target rows [d_max+1, 2*d_max+1], one SampRow each, and the round's uniform numbers
+  float* slog = nullptr; unsigned long long* swf = nullptr; SampRow* srows = nullptr; float* unif_dev = nullptr;
+  int64_t sld = 0;   // row stride of slog and swf, in elements
   void* stage = nullptr; size_t stage_bytes = 0;
   hipEvent_t ev[4] = {nullptr, nullptr, nullptr, nullptr};
   // host state
@@ -431,7 +435,7 @@ void free_all(del_ctx* c) {
                   c->rope, c->hid, c->q, c->attn, c->act, c->xs_layer, c->xs_shadow, c->rowscale, c->xs_h, c->xs_attn,
                   c->xs_h1, c->xs_act, c->ssq_h, c->ssq_h1, c->PM, c->PL,
                   c->PA, c->pval, c->pidx, c->psum, c->conf_dev, c->state, c->draft_ids, c->shadow_ids, c->result, c->ids_dev,
-                  c->logits_dbg, c->sink, c->stage};
+                  c->logits_dbg, c->sink, c->stage, c->slog, c->swf, c->srows, c->unif_dev};
   for (void* p : ptrs)
     if (p) (void)hipFree(p);
   if (c->result_host) (void)hipHostFree(c->result_host);
@@ -661,6 +665,14 @@ del_status del_create(const del_config* cfg, void* hip_stream, del_ctx** out) {
   CK(hipHostMalloc((void**)&ctx->result_host, (size_t)(3 + cfg->d_max + 1 + Rmax) * 4, hipHostMallocDefault));
   CK(dmalloc(&ctx->logits_dbg, (size_t)ctx->NBv * 16 * 4));
   CK(dmalloc(&ctx->sink, 16));
+  {
+    const size_t srow_n = (size_t)2 * (cfg->d_max + 1);
+    ctx->sld = (int64_t)ctx->NBv * 16;
+    CK(dmalloc(&ctx->slog, srow_n * ctx->sld * 4));
+    CK(dmalloc(&ctx->swf, srow_n * ctx->sld * 8));
+    CK(dmalloc(&ctx->srows, srow_n * sizeof(SampRow)));
+    CK(dmalloc(&ctx->unif_dev, (srow_n + 2) * 4));
+  }
   for (auto& e : ctx->ev) CK(hipEventCreate(&e));
   CK(hipStreamSynchronize(ctx->stream));
 #undef CK
@@ -812,6 +824,65 @@ del_status del_prefill(del_ctx* ctx, const int32_t* prompt, int32_t n_prompt, in
   return DEL_OK;
 }
 
+// After a round's last kernel is queued: wait, read the results back, update the statistics
+// (Sections 4.2, 4.4: over the valid positions 0..u, n = u + 1) and the host's mirror of the state.
+// sampled: the emitted tokens are the accepted drafts and the drawn last token, and layer E's shadow
+// tokens are its greedy ones; otherwise they are the target's tokens and the drafts stand in for
+// layer E's shadow tokens.
+static del_status finish_round(del_ctx* ctx, int E, int gamma, bool stopped, bool sampled, int32_t* out_tokens,
+                               int32_t* n_out) {
+  const int L = ctx->L, m = gamma + 1;
+  const int Rmax = L * ctx->maxrows;
+  HIPCHK(hipStreamSynchronize(ctx->stream));
+  prof_collect(ctx);
+  (void)hipEventElapsedTime(&ctx->t_draft, ctx->ev[0], ctx->ev[1]);
+  (void)hipEventElapsedTime(&ctx->t_verify, ctx->ev[1], ctx->ev[2]);
+  (void)hipEventElapsedTime(&ctx->t_shadow, ctx->ev[2], ctx->ev[3]);
+  const int* res = ctx->result_host;
+  const int u = res[0];
+  const int* drafts = res + 3;
+  const int* sh = res + 3 + gamma;  // [L][m]
+  const int* target = sh + (size_t)(L - 1) * m;
+  float* cf = ctx->conf_host;       // [L][m]
+  const float* dcf = ctx->conf_host + Rmax;
+  // greedy: the drafted tokens are layer E's shadow tokens, their confidences are the draft's too
+  if (!sampled)
+    for (int i = 0; i < gamma; ++i) cf[(size_t)(E - 1) * m + i] = dcf[i];
+  std::vector<int> c(L + 1, 0);
+  std::vector<double> tcs(L + 1, 0.0), fcs(L + 1, 0.0);
+  for (int l = 1; l <= L; ++l)
+    for (int i = 0; i <= u; ++i) {
+      const bool hit = sh[(size_t)(l - 1) * m + i] == target[i];
+      c[l] += hit;
+      (hit ? tcs : fcs)[l] += (double)cf[(size_t)(l - 1) * m + i];
+    }
+  ctx->pol.update(c.data(), u + 1, tcs.data(), fcs.data());
+  if (sampled) {
+    for (int i = 0; i < u; ++i) out_tokens[i] = drafts[i];
+    out_tokens[u] = res[2];
+  } else {
+    for (int i = 0; i <= u; ++i) out_tokens[i] = target[i];
+  }
+  *n_out = u + 1;
+  ctx->T = res[1]; ctx->pending = res[2];
+  ctx->rounds += 1; ctx->last_rows = m;
+  ctx->last_c = c; ctx->last_E = E; ctx->last_gamma = gamma; ctx->last_u = u; ctx->last_n = u + 1;
+  ctx->last_stopped = stopped ? 1 : 0;
+  const int stride = ctx->cfg.d_max + 1;
+  std::fill(ctx->last_shadow.begin(), ctx->last_shadow.end(), 0);
+  std::fill(ctx->last_conf.begin(), ctx->last_conf.end(), 0.f);
+  for (int l = 1; l <= L; ++l)
+    for (int i = 0; i < m; ++i) {
+      ctx->last_shadow[(size_t)l * stride + i] = sh[(size_t)(l - 1) * m + i];
+      ctx->last_conf[(size_t)l * stride + i] = cf[(size_t)(l - 1) * m + i];
+    }
+  for (int i = 0; i < gamma; ++i) ctx->last_draft[i] = drafts[i];
+  std::fill(ctx->last_draft_conf.begin(), ctx->last_draft_conf.end(), 0.f);
+  if (!sampled)
+    for (int i = 0; i < gamma + (stopped ? 1 : 0); ++i) ctx->last_draft_conf[i] = dcf[i];
+  return DEL_OK;
+}
+
 // One round.  tau < 0: draft exactly `gamma` tokens.  tau >= 0: dynamic draft-exiting (Section 4.4;
 // Algorithm 1 loop): draft up to `gamma` tokens, stop before appending the first one whose
 // confidence is below tau; the stopping step's exit state is the round's last row.
@@ -905,49 +976,10 @@ static del_status round_impl(del_ctx* ctx, int E, int gamma, double tau, int32_t
     if (st != DEL_OK) return st;
   }
   HIPCHK(hipEventRecord(ctx->ev[3], s));
-  HIPCHK(hipStreamSynchronize(s));
-  prof_collect(ctx);
-  (void)hipEventElapsedTime(&ctx->t_draft, ctx->ev[0], ctx->ev[1]);
-  (void)hipEventElapsedTime(&ctx->t_verify, ctx->ev[1], ctx->ev[2]);
-  (void)hipEventElapsedTime(&ctx->t_shadow, ctx->ev[2], ctx->ev[3]);
-  const int* res = ctx->result_host;
-  const int u = res[0];
-  const int* drafts = res + 3;
-  const int* sh = res + 3 + gamma;  // [L][m]
-  const int* target = sh + (size_t)(L - 1) * m;
-  float* cf = ctx->conf_host;       // [L][m]
-  const float* dcf = ctx->conf_host + Rmax;
-  // the drafted tokens are layer E's shadow tokens: their confidences are the draft's too
-  for (int i = 0; i < gamma; ++i) cf[(size_t)(E - 1) * m + i] = dcf[i];
-  // ---- statistics (Sections 4.2, 4.4): over the valid positions 0..u, n = u + 1
-  std::vector<int> c(L + 1, 0);
-  std::vector<double> tcs(L + 1, 0.0), fcs(L + 1, 0.0);
-  for (int l = 1; l <= L; ++l)
-    for (int i = 0; i <= u; ++i) {
-      const bool hit = sh[(size_t)(l - 1) * m + i] == target[i];
-      c[l] += hit;
-      (hit ? tcs : fcs)[l] += (double)cf[(size_t)(l - 1) * m + i];
-    }
-  ctx->pol.update(c.data(), u + 1, tcs.data(), fcs.data());
-  for (int i = 0; i <= u; ++i) out_tokens[i] = target[i];
-  *n_out = u + 1;
+  del_status fst = finish_round(ctx, E, gamma, stopped, false, out_tokens, n_out);
+  if (fst != DEL_OK) return fst;
   if (gamma_used) *gamma_used = gamma;
   if (stopped_early) *stopped_early = stopped ? 1 : 0;
-  ctx->T = res[1]; ctx->pending = res[2];
-  ctx->rounds += 1; ctx->last_rows = m;
-  ctx->last_c = c; ctx->last_E = E; ctx->last_gamma = gamma; ctx->last_u = u; ctx->last_n = u + 1;
-  ctx->last_stopped = stopped ? 1 : 0;
-  const int stride = ctx->cfg.d_max + 1;
-  std::fill(ctx->last_shadow.begin(), ctx->last_shadow.end(), 0);
-  std::fill(ctx->last_conf.begin(), ctx->last_conf.end(), 0.f);
-  for (int l = 1; l <= L; ++l)
-    for (int i = 0; i < m; ++i) {
-      ctx->last_shadow[(size_t)l * stride + i] = sh[(size_t)(l - 1) * m + i];
-      ctx->last_conf[(size_t)l * stride + i] = cf[(size_t)(l - 1) * m + i];
-    }
-  for (int i = 0; i < gamma; ++i) ctx->last_draft[i] = drafts[i];
-  std::fill(ctx->last_draft_conf.begin(), ctx->last_draft_conf.end(), 0.f);
-  for (int i = 0; i < gamma + (stopped ? 1 : 0); ++i) ctx->last_draft_conf[i] = dcf[i];
   return DEL_OK;
 }
 
@@ -959,6 +991,138 @@ del_status del_round_dynamic(del_ctx* ctx, int32_t E, double tau, int32_t d_cap,
                              int32_t* gamma_used, int32_t* stopped_early) {
   if (!(tau >= 0.0)) return DEL_E_ARG;
   return round_impl(ctx, E, d_cap, tau, out_tokens, n_out, gamma_used, stopped_early);
+}
+
+// Logits of rows [row0, row0+m) of layer `layer` into sampling rows [srow0, srow0+m).
+static del_status sample_logits(del_ctx* ctx, int layer, int row0, int m, int srow0) {
+  GemmP p = head_gemm(ctx);
+  p.X = ctx->hid_row(layer, row0);
+  p.Y = ctx->slog + (size_t)srow0 * ctx->sld; p.ldy = (int)ctx->sld;
+  const bool mf = ctx->cfg.use_mfma && ctx->wd == DEL_DTYPE_BF16 && m > 1;
+  return gemm(ctx, p, EPI_STORE, m, mf);
+}
+
+static bool sampling_args_ok(double temperature, double top_p) {
+  return temperature > 0.0 && top_p > 0.0 && top_p <= 1.0 && std::isfinite(temperature);
+}
+
+del_status del_sample_first(del_ctx* ctx, double temperature, double top_p, float r, int32_t* token) {
+  if (!ctx || !token || !sampling_args_ok(temperature, top_p) || !(r >= 0.f && r < 1.f)) return DEL_E_ARG;
+  if (ctx->phase != 1 || ctx->rounds != 0) return DEL_E_STATE;
+  hipStream_t s = ctx->stream;
+  const int VB = ctx->cfg.d_max + 1;
+  del_status st = sample_logits(ctx, ctx->L, ctx->last_rows - 1, 1, VB);
+  if (st != DEL_OK) return st;
+  HIPCHK(hipMemcpyAsync(ctx->unif_dev, &r, 4, hipMemcpyHostToDevice, s));
+  HIPCHK(launch_samp_rowstats(ctx->slog + (size_t)VB * ctx->sld, ctx->sld, ctx->V, 1, temperature, top_p,
+                              ctx->swf + (size_t)VB * ctx->sld, ctx->sld, ctx->srows + VB, s));
+  HIPCHK(launch_samp_draw(ctx->slog + (size_t)VB * ctx->sld, ctx->V, ctx->swf + (size_t)VB * ctx->sld,
+                          ctx->srows + VB, ctx->unif_dev, ctx->draft_ids, nullptr, ctx->state + 1, s));
+  HIPCHK(hipMemcpyAsync(ctx->step_host, ctx->draft_ids, 4, hipMemcpyDeviceToHost, s));
+  HIPCHK(hipStreamSynchronize(s));
+  ctx->pending = ctx->step_host[0];
+  *token = ctx->pending;
+  return DEL_OK;
+}
+
+del_status del_round_sample(del_ctx* ctx, int32_t E, int32_t gamma, double temperature, double top_p,
+                            const float* uniforms, int32_t* out_tokens, int32_t* n_out) {
+  if (!ctx || !out_tokens || !n_out || !uniforms || !sampling_args_ok(temperature, top_p)) return DEL_E_ARG;
+  if (ctx->phase != 1) return DEL_E_STATE;
+  const int L = ctx->L;
+  if (E < 1 || E > L || gamma < 0 || gamma > ctx->cfg.d_max) return DEL_E_ARG;
+  for (int i = 0; i < 2 * gamma + 1; ++i)
+    if (!(uniforms[i] >= 0.f && uniforms[i] < 1.f)) return DEL_E_ARG;
+  if (ctx->T + gamma + 1 > ctx->Tcap) return DEL_E_CAPACITY;
+  hipStream_t s = ctx->stream;
+  const int m = gamma + 1, VB = ctx->cfg.d_max + 1, V = ctx->V;
+  const int64_t ld = ctx->sld;
+  HIPCHK(hipMemcpyAsync(ctx->unif_dev, uniforms, (size_t)(2 * gamma + 1) * 4, hipMemcpyHostToDevice, s));
+  HIPCHK(hipEventRecord(ctx->ev[0], s));
+  // ---- draft: layers 1..E, the exit layer's logits, a draw from their nucleus
+  for (int i = 0; i <= gamma; ++i) {
+    const int* tok = i == 0 ? ctx->state + 1 : ctx->draft_ids + (i - 1);
+    HIPCHK(launch_embed(ctx->embed_t, ctx->wd, ctx->KTd, V, tok, 1, ctx->hid_row(0, i), ctx->dpad, ctx->d, s));
+    for (int l = 1; l <= E; ++l) {
+      del_status st = run_layer(ctx, l, i, 1, l > 1);
+      if (st != DEL_OK) return st;
+    }
+    if (i < gamma) {
+      del_status st = sample_logits(ctx, E, i, 1, i);
+      if (st != DEL_OK) return st;
+      HIPCHK(launch_samp_rowstats(ctx->slog + (size_t)i * ld, ld, V, 1, temperature, top_p, ctx->swf + (size_t)i * ld,
+                                  ld, ctx->srows + i, s));
+      HIPCHK(launch_samp_draw(ctx->slog + (size_t)i * ld, V, ctx->swf + (size_t)i * ld, ctx->srows + i,
+                              ctx->unif_dev + i, ctx->draft_ids + i, nullptr, nullptr, s));
+    }
+  }
+  HIPCHK(hipEventRecord(ctx->ev[1], s));
+  // ---- verify: the gamma+1 exit states through layers E+1..L
+  for (int l = E + 1; l <= L; ++l) {
+    del_status st = run_layer(ctx, l, 0, m, l > E + 1);
+    if (st != DEL_OK) return st;
+  }
+  HIPCHK(hipEventRecord(ctx->ev[2], s));
+  // ---- greedy shadow tokens of every layer; the target's distributions; acceptance on the device
+  {
+    del_status st = shadow_head(ctx, m);
+    if (st != DEL_OK) return st;
+    st = sample_logits(ctx, L, 0, m, VB);
+    if (st != DEL_OK) return st;
+    HIPCHK(launch_samp_rowstats(ctx->slog + (size_t)VB * ld, ld, V, m, temperature, top_p, ctx->swf + (size_t)VB * ld, ld,
+                                ctx->srows + VB, s));
+    HIPCHK(launch_samp_accept(ctx->slog, ctx->swf, ctx->srows, ctx->slog + (size_t)VB * ld, ctx->swf + (size_t)VB * ld,
+                              ctx->srows + VB, ld, ld, V, gamma, ctx->draft_ids, ctx->unif_dev + gamma, ctx->state,
+                              ctx->shadow_ids, L * m, ctx->result, s));
+    const size_t nres = (size_t)3 + gamma + (size_t)L * m;
+    HIPCHK(hipMemcpyAsync(ctx->result_host, ctx->result, nres * 4, hipMemcpyDeviceToHost, s));
+    HIPCHK(hipMemcpyAsync(ctx->conf_host, ctx->conf_dev, (size_t)L * m * 4, hipMemcpyDeviceToHost, s));
+  }
+  HIPCHK(hipEventRecord(ctx->ev[3], s));
+  return finish_round(ctx, E, gamma, false, true, out_tokens, n_out);
+}
+
+del_status del_debug_spec_sample(del_ctx* ctx, const float* q_logits, const float* p_logits, int32_t gamma,
+                                 double temperature, double top_p, const float* uniforms, int32_t* drafts_out,
+                                 int32_t* u, int32_t* last_token) {
+  if (!ctx || !p_logits || !uniforms || !u || !last_token || gamma < 0 || gamma > ctx->cfg.d_max ||
+      (gamma > 0 && (!q_logits || !drafts_out)) || !sampling_args_ok(temperature, top_p))
+    return DEL_E_ARG;
+  for (int i = 0; i < 2 * gamma + 1; ++i)
+    if (!(uniforms[i] >= 0.f && uniforms[i] < 1.f)) return DEL_E_ARG;
+  hipStream_t s = ctx->stream;
+  const int VB = ctx->cfg.d_max + 1, V = ctx->V;
+  const int64_t ld = ctx->sld;
+  HIPCHK(hipStreamSynchronize(s));
+  if (gamma > 0)
+    HIPCHK(hipMemcpy2D(ctx->slog, (size_t)ld * 4, q_logits, (size_t)V * 4, (size_t)V * 4, gamma, hipMemcpyHostToDevice));
+  HIPCHK(hipMemcpy2D(ctx->slog + (size_t)VB * ld, (size_t)ld * 4, p_logits, (size_t)V * 4, (size_t)V * 4, gamma + 1,
+                     hipMemcpyHostToDevice));
+  HIPCHK(hipMemcpy(ctx->unif_dev, uniforms, (size_t)(2 * gamma + 1) * 4, hipMemcpyHostToDevice));
+  // state, drafts and result live in the debug logits buffer, so that the context's own are untouched
+  const int DM = ctx->cfg.d_max + 1;
+  int* scratch = reinterpret_cast<int*>(ctx->logits_dbg);
+  int* st_s = scratch; int* dr_s = scratch + 4; int* rs_s = scratch + 4 + DM;
+  const size_t n_scr = (size_t)4 + DM + 3 + DM;
+  if ((size_t)ctx->NBv * 16 < n_scr) return DEL_E_CAPACITY;
+  HIPCHK(hipMemsetAsync(scratch, 0, n_scr * 4, s));
+  if (gamma > 0) {
+    HIPCHK(launch_samp_rowstats(ctx->slog, ld, V, gamma, temperature, top_p, ctx->swf, ld, ctx->srows, s));
+    for (int i = 0; i < gamma; ++i)
+      HIPCHK(launch_samp_draw(ctx->slog + (size_t)i * ld, V, ctx->swf + (size_t)i * ld, ctx->srows + i,
+                              ctx->unif_dev + i, dr_s + i, nullptr, nullptr, s));
+  }
+  HIPCHK(launch_samp_rowstats(ctx->slog + (size_t)VB * ld, ld, V, gamma + 1, temperature, top_p,
+                              ctx->swf + (size_t)VB * ld, ld, ctx->srows + VB, s));
+  HIPCHK(launch_samp_accept(ctx->slog, ctx->swf, ctx->srows, ctx->slog + (size_t)VB * ld, ctx->swf + (size_t)VB * ld,
+                            ctx->srows + VB, ld, ld, V, gamma, dr_s, ctx->unif_dev + gamma, st_s, nullptr, 0, rs_s, s));
+  HIPCHK(hipStreamSynchronize(s));
+  std::vector<int> host(n_scr);
+  HIPCHK(hipMemcpy(host.data(), scratch, n_scr * 4, hipMemcpyDeviceToHost));
+  *u = host[4 + DM];
+  *last_token = host[4 + DM + 2];
+  for (int i = 0; i < gamma; ++i) drafts_out[i] = host[4 + i];
+  return DEL_OK;
 }
 
 del_status del_layer_stats(const del_ctx* ctx, del_stats* out) {

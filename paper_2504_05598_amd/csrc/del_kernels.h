@@ -113,5 +113,28 @@ hipError_t launch_pad_gain(const float* src, int K, float* dst, int Kpad, hipStr
 hipError_t launch_stream_copy(const void* src, void* dst, int64_t bytes, hipStream_t s);
 hipError_t launch_stream_read(const void* base, int64_t bytes, float* sink, hipStream_t s);
 
+// ---- speculative sampling (del_sampling.hip) ----
+// What the sampling kernels keep of one logits row: token j is in the nucleus when the order key of
+// its logit is above kstar, or equal to it with j <= tie_id; its probability is then
+// weight[j] / Wkept with weight[j] = exp((z_j - zmax) / temperature) in 2^-44 fixed point.
+struct SampRow {
+  float zmax;
+  unsigned kstar;
+  int tie_id;
+  int argmax;                    // greedy token (lowest id at the maximum)
+  unsigned long long Wkept;      // mass of the nucleus
+  unsigned long long Wtot;       // mass of all tokens
+  float conf;                    // soft-max probability of the greedy token at temperature 1
+  int pad;
+};
+hipError_t launch_samp_rowstats(const float* Z, int64_t ldz, int V, int rows, double temperature, double top_p,
+                                unsigned long long* WF, int64_t ldw, SampRow* out, hipStream_t s);
+hipError_t launch_samp_draw(const float* z, int V, const unsigned long long* wf, const SampRow* row, const float* r,
+                            int* token_out, unsigned long long* weight_out, int* state_pending, hipStream_t s);
+hipError_t launch_samp_accept(const float* Zq, const unsigned long long* WFq, const SampRow* rq, const float* Zp,
+                              const unsigned long long* WFp, const SampRow* rp, int64_t ldz, int64_t ldw, int V,
+                              int gamma, const int* drafts, const float* unif, int* state, const int* shadow_ids,
+                              int n_shadow, int* result, hipStream_t s);
+
 
 }  // namespace del

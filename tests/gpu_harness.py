@@ -52,6 +52,7 @@ class ParityReport:
     resyncs: int = 0
     max_hidden_err: float = 0.0
     tokens: List[int] = field(default_factory=list)
+    decisions: int = 0
 
 
 def _rel_err(got: np.ndarray, want: np.ndarray) -> float:
@@ -212,3 +213,147 @@ def gpu_generate(ctx: DelContext, prompt, n_tokens, schedule=None, dynamic=False
             st = ctx.stats()
             E, gamma = st["next_E"], st["next_gamma"]
     return toks, rounds
+
+
+# ---- speculative sampling ------------------------------------------------------------------
+# A sampled decision is a uniform number against a boundary of a cumulative distribution (a draw) or
+# against a probability ratio (an acceptance).  The two sides' logits differ by rounding, so the
+# boundaries move by a little: a decision may differ only where the oracle's uniform number lies
+# within the tolerance of the boundary that decides for the GPU's outcome.
+CUT_TOL = 2e-2     # nucleus: a token may be in or out if the kept mass is this close to top_p
+
+
+def _interval_distance(dist: torch.Tensor, token: int, r: float) -> float:
+    """How far r lies from the interval of `token` in the cumulative distribution (0 inside)."""
+    cdf = torch.cumsum(dist, dim=0)
+    hi = float(cdf[token])
+    lo = float(cdf[token - 1]) if token > 0 else 0.0
+    return max(lo - r, r - hi, 0.0)
+
+
+def _cut_slack(oracle: Oracle, h_row: torch.Tensor, dist: torch.Tensor, temperature: float, top_p: float) -> float:
+    """Mass that moves when the token at the nucleus cut flips in or out; 0 if the cut is clear."""
+    from oracle.del_oracle import tempered_nucleus
+    if top_p >= 1.0:
+        return 0.0
+    full = tempered_nucleus(oracle.logits(h_row[None, :])[0], temperature, 1.0)
+    kept = dist > 0
+    mass = float(full[kept].sum())
+    last_in = float(full[kept].min())
+    out = full[~kept]
+    first_out = float(out.max()) if out.numel() else 0.0
+    if mass - top_p < CUT_TOL * top_p or top_p - (mass - last_in) < CUT_TOL * top_p:
+        return 2.0 * max(last_in, first_out) / mass
+    return 0.0
+
+
+def lockstep_sample(cfg, oracle: Oracle, ctx: DelContext, prompt, n_tokens, temperature, top_p,
+                    sample_tol, ratio_tol, schedule=None, stream0=0) -> ParityReport:
+    """Speculative sampling in lock-step: the same uniform numbers on both sides; drafts, acceptance
+    count, emitted tokens, greedy shadow tokens, statistics and the next (E, gamma) are compared.
+    A differing sampled decision must be a near-boundary one (see above) and is followed by a
+    re-prefill of the GPU context on the oracle's tokens."""
+    from synthdata import gen_uniforms
+    rep = ParityReport()
+    L = cfg.n_layers
+    pre = oracle.prefill(prompt, keep_hidden=True)
+    first, gE, gg = ctx.prefill(prompt)
+    assert first == pre.first_token or pre.first_gap < GAP_TOL
+    r0 = float(gen_uniforms(cfg, stream0, 1)[0])
+    tok_o, dist0 = oracle.sample_first(temperature, top_p, r0)
+    tok_g = ctx.sample_first(temperature, top_p, r0)
+    emitted = [tok_o]
+    decisions = 1
+    if tok_g != tok_o:
+        d = _interval_distance(dist0, tok_g, r0)
+        slack = _cut_slack(oracle, pre.hidden[L, -1], dist0, temperature, top_p)
+        assert d <= sample_tol + slack, f"first token gpu {tok_g} oracle {tok_o} r {r0} distance {d}"
+        rep.flips += 1
+        ctx.set_pending(tok_o)
+    if (gE, gg) != (pre.next_E, pre.next_gamma):
+        _resync(ctx, oracle, prompt, emitted, rep)
+    E, gamma = (pre.next_E, pre.next_gamma) if schedule is None else schedule
+    while len(emitted) < n_tokens:
+        g = min(gamma, n_tokens - len(emitted) - 1)
+        un = gen_uniforms(cfg, stream0 + 1 + rep.rounds, 2 * g + 1).tolist()
+        r = oracle.round_sample(E, g, temperature, top_p, un, keep_hidden=True)
+        out = ctx.round_sample(E, g, temperature, top_p, un)
+        st = ctx.stats()
+        rep.rounds += 1
+        decisions += 2 * g + 1
+        diverged = None
+        # the drafts, in order; after a differing draft the two sides see different inputs
+        same_rows = g + 1
+        for i in range(g):
+            if st["last_draft"][i] != r.draft_ids[i]:
+                d = _interval_distance(r.q_dists[i], st["last_draft"][i], un[i])
+                slack = _cut_slack(oracle, r.hidden[E, i], r.q_dists[i], temperature, top_p)
+                assert d <= sample_tol + slack, (
+                    f"round {rep.rounds} E={E} g={g} draft {i}: gpu {st['last_draft'][i]} oracle {r.draft_ids[i]} "
+                    f"r {un[i]} distance {d} slack {slack}")
+                diverged = ("draft", i)
+                same_rows = i + 1
+                break
+        # greedy shadow tokens and hidden states of the rows with equal inputs
+        flipped = False
+        for l in range(1, L + 1):
+            for i in range(same_rows):
+                rep.compared_ids += 1
+                if st["last_shadow"][l][i] != r.shadow[l][i]:
+                    assert r.gaps[l][i] < GAP_TOL, ("shadow", rep.rounds, l, i, r.gaps[l][i])
+                    flipped = True
+                else:
+                    assert _close(st["last_conf"][l][i], r.conf[l][i], CONF_RTOL)
+            err = _rel_err(np.stack([ctx.hidden(l, i) for i in range(same_rows)]),
+                           r.hidden[l, :same_rows].float().numpy())
+            rep.max_hidden_err = max(rep.max_hidden_err, err)
+            assert err <= HID_TOL, ("hidden", rep.rounds, l, err)
+        if diverged is None:
+            u_g = len(out) - 1
+            if u_g != r.u:
+                # the acceptance at the first position where the two sides differ
+                k = min(u_g, r.u)
+                x = r.draft_ids[k]
+                ratio = float(r.p_dists[k][x]) / float(r.q_dists[k][x])
+                slack = (_cut_slack(oracle, r.hidden[L, k], r.p_dists[k], temperature, top_p) +
+                         _cut_slack(oracle, r.hidden[E, k], r.q_dists[k], temperature, top_p))
+                in_p_cut = float(r.p_dists[k][x]) == 0.0 and slack > 0.0
+                assert abs(un[g + k] - min(ratio, 1.0)) <= ratio_tol * max(ratio, 1e-3) + slack or in_p_cut, (
+                    f"round {rep.rounds} E={E} g={g}: gpu accepted {u_g}, oracle {r.u}; at {k} r {un[g + k]} ratio {ratio}")
+                diverged = ("accept", k)
+            elif out[:r.u] != r.out_tokens[:r.u]:
+                raise AssertionError(("accepted drafts differ", out, r.out_tokens))
+            elif out[-1] != r.out_tokens[-1]:
+                d = _interval_distance(r.last_dist, out[-1], un[2 * g])
+                slack = _cut_slack(oracle, r.hidden[L, r.u], r.p_dists[r.u], temperature, top_p)
+                if r.u < g:
+                    slack += _cut_slack(oracle, r.hidden[E, r.u], r.q_dists[r.u], temperature, top_p)
+                    # the residual is renormalised by its own total: boundary shifts scale with 1 / total
+                    total = float(torch.clamp(r.p_dists[r.u] - r.q_dists[r.u], min=0).sum())
+                    tol = sample_tol / max(total, 1e-6)
+                else:
+                    tol = sample_tol
+                assert d <= tol + slack, (
+                    f"round {rep.rounds} E={E} g={g} last token: gpu {out[-1]} oracle {r.out_tokens[-1]} "
+                    f"r {un[2 * g]} distance {d} tol {tol} slack {slack}")
+                diverged = ("last", r.u)
+        emitted.extend(r.out_tokens)
+        if diverged is None and not flipped:
+            assert out == r.out_tokens and st["last_u"] == r.u and st["last_n"] == r.n
+            assert st["last_c"][1:] == r.c[1:]
+            for l in range(1, L + 1):
+                assert abs(st["alpha"][l] - r.alpha[l]) <= 1e-9
+                assert _close(st["tau"][l], r.tau[l], CONF_RTOL)
+            assert (st["next_E"], st["next_gamma"]) == (r.next_E, r.next_gamma)
+            T, pend = ctx.state()
+            assert T == oracle.T and pend == oracle.pending
+        else:
+            if diverged is not None:
+                rep.flips += 1
+                log(f"  sampled decision differs within tolerance: round {rep.rounds} {diverged}")
+            _resync(ctx, oracle, prompt, emitted, rep)
+        if schedule is None:
+            E, gamma = r.next_E, r.next_gamma
+    rep.tokens = emitted
+    rep.decisions = decisions
+    return rep
