@@ -176,6 +176,34 @@ def main():
     dyn_tokens, dyn_drafted = run_dynamic(K)
     torch.cuda.synchronize()
     dyn_tps = dyn_tokens / (time.perf_counter() - t0)
+    # ---- the same K rounds with speculative sampling (Section 2; temperature 0.6, top_p 0.95 as in the
+    #      paper's sampling runs), DEL-selected (E, gamma); and its auto-regressive counterpart (gamma = 0)
+    from synthdata import gen_uniforms
+    ctx.prefill(prompt)
+    ctx.sample_first(0.6, 0.95, 0.5)
+
+    def run_sampled(n_rounds, stream0, fixed=None):
+        tokens = 0
+        st = ctx.stats()
+        for k in range(n_rounds):
+            E, g = fixed if fixed else (st["next_E"], st["next_gamma"])
+            tokens += len(ctx.round_sample(E, g, 0.6, 0.95, gen_uniforms(cfg, stream0 + k, 2 * g + 1).tolist()))
+            st = ctx.stats()
+        return tokens
+    run_sampled(W, 10000)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    smp_tokens = run_sampled(K, 20000)
+    torch.cuda.synchronize()
+    smp_tps = smp_tokens / (time.perf_counter() - t0)
+    ctx.prefill(prompt)
+    ctx.sample_first(0.6, 0.95, 0.5)
+    run_sampled(2, 30000, fixed=(1, 0))
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    run_sampled(8, 40000, fixed=(1, 0))
+    torch.cuda.synchronize()
+    smp_vanilla_tps = 8 / (time.perf_counter() - t0)
     stream_gbs = ctx.stream_read_gbps(min(4 << 30, cfg.layer_weight_bytes() * cfg.n_layers), 10)
     copy_gbs = ctx.stream_copy_gbps(1 << 30, 5)     # also the known-size kernel for counter calibration
 
@@ -213,6 +241,9 @@ def main():
             "speedup_over_vanilla": round(value / vanilla_tps, 3),
             "with_draft_exiting_tokens_per_s": round(dyn_tps, 2),
             "with_draft_exiting_mean_gamma": round(dyn_drafted / K, 2),
+            "sampling_tokens_per_s": round(smp_tps, 2),
+            "sampling_tokens_per_round": round(smp_tokens / K, 3),
+            "sampling_autoregressive_tokens_per_s": round(smp_vanilla_tps, 2),
             "stream_read_GBs": round(stream_gbs, 1), "stream_copy_GBs": round(copy_gbs, 1),
             "paper_speedup_over_autoregressive": "2.16-2.62x on A100-40G / 2xH100-PCIe (context only)",
         },

@@ -20,9 +20,12 @@ def fs_next_gamma(gamma: int, accepted_all: bool, d_max: int) -> int:
 
 
 def generate(ctx, prompt: Sequence[int], n_tokens: int, controller: str = "del", E: int = 1, gamma: int = 1,
-             ) -> Tuple[List[int], List[Tuple[int, int, int]]]:
+             sampling=None) -> Tuple[List[int], List[Tuple[int, int, int]]]:
     """Generate n_tokens (the first comes from the prefill).  Returns the tokens and, per round,
-    (E, tokens drafted, tokens emitted)."""
+    (E, tokens drafted, tokens emitted).
+    sampling: None for greedy decoding, or (temperature, top_p, uniforms) for speculative sampling
+    (Section 2), where uniforms(k, count) returns the `count` numbers in [0, 1) of draw k: k = 0 is
+    the first token, k = r + 1 is round r (2 * gamma + 1 numbers: drafts, acceptances, last token)."""
     cfg = ctx.cfg
     first, dE, dg = ctx.prefill(list(prompt))
     if controller in ("del", "del_full"):
@@ -31,6 +34,11 @@ def generate(ctx, prompt: Sequence[int], n_tokens: int, controller: str = "del",
         E, gamma = 1, 0
     elif controller not in ("ls", "fs"):
         raise ValueError(controller)
+    if sampling is not None:
+        if controller == "del_full":
+            raise ValueError("draft-exiting is offered for greedy decoding only")
+        temperature, top_p, uniforms = sampling
+        first = ctx.sample_first(temperature, top_p, float(uniforms(0, 1)[0]))
     toks = [first]
     log = []
     while len(toks) < n_tokens:
@@ -41,7 +49,10 @@ def generate(ctx, prompt: Sequence[int], n_tokens: int, controller: str = "del",
             out, g, _ = ctx.round_dynamic(E, st["tau"][E], min(cfg.d_max, room))
         else:
             g = min(gamma, room)
-            out = ctx.round(E, g)
+            if sampling is not None:
+                out = ctx.round_sample(E, g, temperature, top_p, [float(x) for x in uniforms(len(log) + 1, 2 * g + 1)])
+            else:
+                out = ctx.round(E, g)
         toks.extend(out)
         log.append((E, g, len(out)))
         if controller == "del":

@@ -26,6 +26,15 @@ class _FakeCtx:
         self.calls.append((E, g))
         return [1] * (g + 1 if g % 2 else 1)
 
+    def sample_first(self, temperature, top_p, r):
+        self.first_r = r
+        return 9
+
+    def round_sample(self, E, g, temperature, top_p, un):
+        assert len(un) == 2 * g + 1 and all(0.0 <= x < 1.0 for x in un)
+        self.calls.append((E, g))
+        return [2] * (g + 1 if g % 2 else 1)
+
     def stats(self):
         return {"next_E": 2, "next_gamma": 3, "tau": [0.0] * 9}
 
@@ -43,3 +52,16 @@ def test_generate_bookkeeping_and_fs_trajectory():
     ctx = _FakeCtx()
     toks, log = generate(ctx, [1], 20, "ls", E=2, gamma=3)
     assert all(E == 2 for E, _ in ctx.calls) and ctx.calls[-1][1] <= 3 and len(toks) == 20
+
+
+def test_generate_with_sampling_draws_the_first_token_and_passes_the_right_number_of_uniforms():
+    ctx = _FakeCtx()
+    draws = []
+
+    def uniforms(k, count):
+        draws.append((k, count))
+        return [0.25] * count
+    toks, log = generate(ctx, [1, 2], 10, "del", sampling=(0.6, 0.95, uniforms))
+    assert toks[0] == 9 and ctx.first_r == 0.25 and len(toks) == 10
+    assert draws[0] == (0, 1) and [k for k, _ in draws] == list(range(len(draws)))
+    assert all(count == 2 * g + 1 for (_, count), (_, g) in zip(draws[1:], ctx.calls))

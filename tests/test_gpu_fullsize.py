@@ -78,3 +78,82 @@ def test_speculative_equals_autoregressive_on_gpu(name, n):
         f"({len(rounds_full)} rounds with draft-exiting)")
     assert all(1 <= e < cfg.n_layers and 0 <= g <= cfg.d_max for e, g, _ in rounds)
     ctx.close()
+
+
+# ---- speculative sampling at full size ------------------------------------------------------
+
+@pytest.mark.timeout(900)
+def test_llama1b_sampled_lockstep_prefix():
+    """Sampled rounds (the paper's temperature 0.6, top_p 0.95) in lock-step with the fp32 oracle at the
+    1B shape: 128256-token vocabulary, tied head, 4 query heads per kv head."""
+    from gpu_harness import gpu_context, lockstep_sample, log
+    from oracle.del_oracle import Oracle
+    cfg = get_config("llama1b")
+    ctx, host = gpu_context(cfg, keep_host=True)
+    oracle = Oracle(cfg, host, dtype=torch.float32)
+    prompt = gen_prompt(cfg).tolist()
+    rep = lockstep_sample(cfg, oracle, ctx, prompt, 24, 0.6, 0.95, 5e-3, 3e-2)
+    log(f"[llama1b sampled] rounds={rep.rounds} decisions={rep.decisions} near-boundary={rep.flips} "
+        f"resyncs={rep.resyncs} max_hidden_err={rep.max_hidden_err:.2e}")
+    assert rep.flips <= max(2, rep.decisions // 5)
+    ctx.close()
+
+
+@pytest.mark.timeout(900)
+def test_llama7b_sampled_rounds_properties():
+    """At the benchmark's shape: a one-token nucleus reproduces the greedy rounds; sampled generation is
+    reproducible, emits between 1 and gamma+1 tokens a round and keeps the state consistent; drafting
+    with the whole model (E = L) has its drafts accepted (draft and target distributions then differ
+    only by the rounding of two GEMM paths)."""
+    from gpu_harness import gpu_context, log
+    from synthdata import gen_uniforms
+    cfg = get_config("llama7b")
+    ctx, _ = gpu_context(cfg)
+    prompt = gen_prompt(cfg).tolist()
+    L = cfg.n_layers
+    sched = [(8, 4), (12, 3), (4, 8), (16, 2), (1, 1), (24, 5)]
+    # greedy reference
+    first, _, _ = ctx.prefill(prompt)
+    greedy = [first]
+    for (E, g) in sched:
+        greedy += ctx.round(E, g)
+    # one-token nucleus
+    ctx.prefill(prompt)
+    one = [ctx.sample_first(0.6, 1e-9, 0.9)]
+    for k, (E, g) in enumerate(sched):
+        one += ctx.round_sample(E, g, 0.6, 1e-9, gen_uniforms(cfg, 70 + k, 2 * g + 1).tolist())
+    kk = _first_divergence_is_near_tie(ctx, cfg, prompt, greedy, one)
+    log(f"[llama7b] one-token nucleus == greedy for {kk}/{min(len(greedy), len(one))} tokens")
+    # sampled generation, DEL-driven, twice
+    runs = []
+    for _ in range(2):
+        _, E, g = ctx.prefill(prompt)
+        toks = [ctx.sample_first(0.6, 0.95, 0.4321)]
+        T0 = ctx.state()[0]
+        k = 0
+        while len(toks) < 64:
+            g = min(g, 64 - len(toks) - 1)
+            out = ctx.round_sample(E, g, 0.6, 0.95, gen_uniforms(cfg, 200 + k, 2 * g + 1).tolist())
+            assert 1 <= len(out) <= g + 1 and all(0 <= t < cfg.vocab for t in out)
+            toks += out
+            T, pend = ctx.state()
+            assert T == T0 + len(toks) - 1 and pend == toks[-1]
+            st = ctx.stats()
+            assert st["last_u"] == len(out) - 1 and st["last_draft"][:len(out) - 1] == out[:-1]
+            E, g = st["next_E"], st["next_gamma"]
+            assert 1 <= E < L and 0 <= g <= cfg.d_max
+            k += 1
+        runs.append((toks, k))
+    assert runs[0] == runs[1]
+    log(f"[llama7b sampled] 64 tokens in {runs[0][1]} rounds, {len(set(runs[0][0]))} distinct tokens")
+    # E = L
+    ctx.prefill(prompt)
+    ctx.sample_first(0.6, 0.95, 0.5)
+    acc = tot = 0
+    for k in range(6):
+        out = ctx.round_sample(L, 4, 0.6, 0.95, gen_uniforms(cfg, 300 + k, 9).tolist())
+        acc += len(out) - 1
+        tot += 4
+    log(f"[llama7b sampled] E=L: {acc}/{tot} drafts accepted")
+    assert acc >= tot - 2
+    ctx.close()

@@ -111,10 +111,12 @@ def _setup(name):
     return cfg, Oracle(cfg, weights), ctx, prompt
 
 
-# fp32 shapes: rounding differences are ~1e-6, a flat distribution can be compared; bf16 shapes: a low
-# temperature gives distributions whose intervals are wide against the rounding of the logits
-CASES = [("tiny", 0.8, 0.9, 2e-4, 2e-3), ("mini_fp32", 0.7, 0.95, 2e-4, 2e-3),
-         ("mini_gqa", 0.15, 0.9, 2e-2, 6e-2), ("mini_mha", 0.15, 0.95, 2e-2, 6e-2), ("mini_g8", 0.2, 0.9, 2e-2, 6e-2)]
+# temperature 0.6 and top_p 0.95 are the paper's sampling settings (appendix, inference setup); the
+# low-temperature cases give peaked distributions.  Tolerances: fp32 shapes differ from the oracle by
+# ~1e-6 in the logits, bf16 shapes by ~1e-3.
+CASES = [("tiny", 0.6, 0.95, 2e-4, 2e-3), ("mini_fp32", 0.6, 0.95, 2e-4, 2e-3),
+         ("mini_gqa", 0.6, 0.95, 5e-3, 3e-2), ("mini_mha", 0.6, 0.95, 5e-3, 3e-2), ("mini_g8", 0.6, 0.95, 5e-3, 3e-2),
+         ("mini_gqa", 0.15, 0.9, 5e-3, 3e-2), ("mini_fp32", 0.05, 0.8, 2e-4, 2e-3)]
 
 
 @pytest.mark.parametrize("name,T,top_p,stol,rtol", CASES)
@@ -128,7 +130,7 @@ def test_sampled_rounds_in_lockstep_del_driven(name, T, top_p, stol, rtol):
     assert rep.flips <= max(2, rep.decisions // 5)
 
 
-@pytest.mark.parametrize("name,T,top_p,stol,rtol", [CASES[0], CASES[2]])
+@pytest.mark.parametrize("name,T,top_p,stol,rtol", [CASES[0], CASES[2], CASES[5]])
 def test_sampled_rounds_in_lockstep_fixed_schedules(name, T, top_p, stol, rtol):
     from gpu_harness import lockstep_sample, log
     cfg, oracle, ctx, prompt = _setup(name)
