@@ -1015,9 +1015,8 @@ del_status del_sample_first(del_ctx* ctx, double temperature, double top_p, floa
   if (st != DEL_OK) return st;
   HIPCHK(hipMemcpyAsync(ctx->unif_dev, &r, 4, hipMemcpyHostToDevice, s));
   HIPCHK(launch_samp_rowstats(ctx->slog + (size_t)VB * ctx->sld, ctx->sld, ctx->V, 1, temperature, top_p,
-                              ctx->swf + (size_t)VB * ctx->sld, ctx->sld, ctx->srows + VB, s));
-  HIPCHK(launch_samp_draw(ctx->slog + (size_t)VB * ctx->sld, ctx->V, ctx->swf + (size_t)VB * ctx->sld,
-                          ctx->srows + VB, ctx->unif_dev, ctx->draft_ids, nullptr, ctx->state + 1, s));
+                              ctx->swf + (size_t)VB * ctx->sld, ctx->sld, ctx->srows + VB, ctx->unif_dev,
+                              ctx->draft_ids, ctx->state + 1, s));
   HIPCHK(hipMemcpyAsync(ctx->step_host, ctx->draft_ids, 4, hipMemcpyDeviceToHost, s));
   HIPCHK(hipStreamSynchronize(s));
   ctx->pending = ctx->step_host[0];
@@ -1051,9 +1050,7 @@ del_status del_round_sample(del_ctx* ctx, int32_t E, int32_t gamma, double tempe
       del_status st = sample_logits(ctx, E, i, 1, i);
       if (st != DEL_OK) return st;
       HIPCHK(launch_samp_rowstats(ctx->slog + (size_t)i * ld, ld, V, 1, temperature, top_p, ctx->swf + (size_t)i * ld,
-                                  ld, ctx->srows + i, s));
-      HIPCHK(launch_samp_draw(ctx->slog + (size_t)i * ld, V, ctx->swf + (size_t)i * ld, ctx->srows + i,
-                              ctx->unif_dev + i, ctx->draft_ids + i, nullptr, nullptr, s));
+                                  ld, ctx->srows + i, ctx->unif_dev + i, ctx->draft_ids + i, nullptr, s));
     }
   }
   HIPCHK(hipEventRecord(ctx->ev[1], s));
@@ -1070,7 +1067,7 @@ del_status del_round_sample(del_ctx* ctx, int32_t E, int32_t gamma, double tempe
     st = sample_logits(ctx, L, 0, m, VB);
     if (st != DEL_OK) return st;
     HIPCHK(launch_samp_rowstats(ctx->slog + (size_t)VB * ld, ld, V, m, temperature, top_p, ctx->swf + (size_t)VB * ld, ld,
-                                ctx->srows + VB, s));
+                                ctx->srows + VB, nullptr, nullptr, nullptr, s));
     HIPCHK(launch_samp_accept(ctx->slog, ctx->swf, ctx->srows, ctx->slog + (size_t)VB * ld, ctx->swf + (size_t)VB * ld,
                               ctx->srows + VB, ld, ld, V, gamma, ctx->draft_ids, ctx->unif_dev + gamma, ctx->state,
                               ctx->shadow_ids, L * m, ctx->result, s));
@@ -1106,14 +1103,11 @@ del_status del_debug_spec_sample(del_ctx* ctx, const float* q_logits, const floa
   const size_t n_scr = (size_t)4 + DM + 3 + DM;
   if ((size_t)ctx->NBv * 16 < n_scr) return DEL_E_CAPACITY;
   HIPCHK(hipMemsetAsync(scratch, 0, n_scr * 4, s));
-  if (gamma > 0) {
-    HIPCHK(launch_samp_rowstats(ctx->slog, ld, V, gamma, temperature, top_p, ctx->swf, ld, ctx->srows, s));
-    for (int i = 0; i < gamma; ++i)
-      HIPCHK(launch_samp_draw(ctx->slog + (size_t)i * ld, V, ctx->swf + (size_t)i * ld, ctx->srows + i,
-                              ctx->unif_dev + i, dr_s + i, nullptr, nullptr, s));
-  }
+  if (gamma > 0)
+    HIPCHK(launch_samp_rowstats(ctx->slog, ld, V, gamma, temperature, top_p, ctx->swf, ld, ctx->srows, ctx->unif_dev,
+                                dr_s, nullptr, s));
   HIPCHK(launch_samp_rowstats(ctx->slog + (size_t)VB * ld, ld, V, gamma + 1, temperature, top_p,
-                              ctx->swf + (size_t)VB * ld, ld, ctx->srows + VB, s));
+                              ctx->swf + (size_t)VB * ld, ld, ctx->srows + VB, nullptr, nullptr, nullptr, s));
   HIPCHK(launch_samp_accept(ctx->slog, ctx->swf, ctx->srows, ctx->slog + (size_t)VB * ld, ctx->swf + (size_t)VB * ld,
                             ctx->srows + VB, ld, ld, V, gamma, dr_s, ctx->unif_dev + gamma, st_s, nullptr, 0, rs_s, s));
   HIPCHK(hipStreamSynchronize(s));
