@@ -161,6 +161,9 @@ del_status del_last_timings(const del_ctx* ctx, float* draft_ms, float* verify_m
 del_status del_debug_hidden(const del_ctx* ctx, int32_t layer, int32_t row, float* dst);
 /* Logits (vocab floats) of the LM head applied, after the final norm, to that row. */
 del_status del_debug_logits(del_ctx* ctx, int32_t layer, int32_t row, float* dst);
+/* Rows of the hidden-state buffer the last pass filled: after del_prefill the last prompt position is row
+ * rows - 1 (for del_debug_hidden / del_debug_logits). */
+del_status del_debug_last_rows(const del_ctx* ctx, int32_t* rows);
 /* Current KV length T and the pending input token. */
 del_status del_debug_state(const del_ctx* ctx, int32_t* kv_len, int32_t* pending_token);
 /* Replace the pending input token (the token the next round starts from).  A lock-step
@@ -179,7 +182,7 @@ del_status del_bench_stream_copy(del_ctx* ctx, int64_t bytes, int32_t iters, flo
  * carries a pair of HIP events that receive the kernel's own start and stop timestamps
  * (hipExtLaunchKernel); per kernel class the launch count and the summed duration are
  * accumulated (throughput is still measured with profiling off).  A class is one kernel instantiation:
- * flavour (0 vector-ALU GEMV/GEMM, 1 matrix-core skinny GEMM, 2 shadow-head GEMM), epilogue (0 store, 1 residual, 2 qkv+rotary,
+ * flavour (0 vector-ALU GEMV/GEMM, 1 matrix-core skinny GEMM, 2 shadow-head GEMM, 3 wide prefill GEMM), epilogue (0 store, 1 residual, 2 qkv+rotary,
  * 3 swiglu, 4 argmax), rows m.  weight_bytes is what one launch of the class streams. */
 typedef struct {
   int32_t flavour, epilogue, rows, launches;

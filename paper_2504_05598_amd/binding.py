@@ -15,7 +15,7 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 
 EXPORTS = ["del_create", "del_destroy", "del_load_weights", "del_prefill", "del_round", "del_round_dynamic",
            "del_layer_stats", "del_set_layer_stats", "del_last_timings", "del_debug_hidden",
-           "del_debug_logits", "del_debug_state", "del_debug_set_pending", "del_profile_enable", "del_profile_read", "del_policy_step", "del_sample_first", "del_round_sample", "del_debug_spec_sample", "del_bench_stream_read", "del_bench_stream_copy", "del_strerror",
+           "del_debug_logits", "del_debug_state", "del_debug_set_pending", "del_debug_last_rows", "del_profile_enable", "del_profile_read", "del_policy_step", "del_sample_first", "del_round_sample", "del_debug_spec_sample", "del_bench_stream_read", "del_bench_stream_copy", "del_strerror",
            "del_last_error_text"]
 
 DEL_DTYPE_FP32, DEL_DTYPE_BF16 = 0, 1
@@ -103,6 +103,7 @@ def load_library():
     lib.del_policy_step.argtypes = [C.c_int32, C.c_int32, C.c_double, P(C.c_int32), C.c_int32, P(C.c_double),
                                     P(C.c_double), P(C.c_double), P(C.c_double), P(C.c_double), P(C.c_double),
                                     P(C.c_double), P(C.c_double), P(C.c_int32), P(C.c_int32)]
+    lib.del_debug_last_rows.argtypes = [C.c_void_p, P(C.c_int32)]
     lib.del_sample_first.argtypes = [C.c_void_p, C.c_double, C.c_double, C.c_float, P(C.c_int32)]
     lib.del_round_sample.argtypes = [C.c_void_p, C.c_int32, C.c_int32, C.c_double, C.c_double, P(C.c_float),
                                      P(C.c_int32), P(C.c_int32)]
@@ -338,6 +339,12 @@ class DelContext:
     def spec_sample(self, q_logits, p_logits, gamma: int, temperature: float, top_p: float, uniforms):
         return del_debug_spec_sample(self.ctx, q_logits, p_logits, gamma, temperature, top_p, uniforms)
 
+    def last_rows(self) -> int:
+        """Rows the last pass filled; after a prefill the last prompt position is row last_rows() - 1."""
+        n = C.c_int32()
+        _check(load_library().del_debug_last_rows(self.ctx, C.byref(n)), self.ctx)
+        return n.value
+
     def stats(self) -> dict:
         return del_layer_stats(self.ctx, self.cfg.n_layers, self.cfg.d_max)
 
@@ -382,7 +389,8 @@ class DelContext:
         for e in arr[:min(n.value, cap)]:
             if e.launches:
                 kernel = (f"gemm_valu_k<8,{e.rows},{e.epilogue}>" if e.flavour == 0
-                          else f"gemm_mfma_k<{e.epilogue}>" if e.flavour == 1 else "head_gemm_k")
+                          else f"gemm_mfma_k<{e.epilogue}>" if e.flavour == 1
+                          else f"gemm_wide_k<{e.epilogue}>" if e.flavour == 3 else "head_gemm_k")
                 out.append({"kernel": kernel, "flavour": ("valu", "mfma", "mfma")[e.flavour],
                             "epilogue": names[e.epilogue], "rows": e.rows, "launches": e.launches,
                             "total_ms": e.total_ms, "avg_us": 1e3 * e.total_ms / e.launches,

@@ -95,6 +95,9 @@ struct del_ctx {
   int qdim = 0, kvdim = 0, dpad = 0, qpad = 0, fpad = 0;
   int KTd = 0, KTq = 0, KTf = 0, NBqkv = 0, NBd = 0, NBgu = 0, NBv = 0;
   int maxrows = 0, Tcap = 0;
+  int prows = 0;    // token rows of a wide prefill pass (0: prefill runs in 16-row passes)
+  int hrows = 0;    // rows per layer of the hidden buffer and of the per-row work buffers
+  float* rowscale_w = nullptr;   // [hrows] RMS scales of a wide pass
   // device memory
   char* arena = nullptr;
   size_t off_qkv = 0, off_o = 0, off_gu = 0, off_dn = 0, layer_stride = 0, arena_bytes = 0;
@@ -151,7 +154,7 @@ struct del_ctx {
     err = std::string(what) + ": " + hipGetErrorString(e);
     return e == hipErrorOutOfMemory ? DEL_E_NOMEM : DEL_E_DEVICE;
   }
-  float* hid_row(int layer, int row) const { return hid + ((size_t)layer * maxrows + row) * dpad; }
+  float* hid_row(int layer, int row) const { return hid + ((size_t)layer * hrows + row) * dpad; }
   float* gain_attn(int li) const { return gains + ((size_t)li * 2) * gpad; }
   float* gain_ffn(int li) const { return gains + ((size_t)li * 2 + 1) * gpad; }
   float* gain_final() const { return gains + (size_t)L * 2 * gpad; }
@@ -227,6 +230,8 @@ void prof_collect(del_ctx* ctx) {
 
 // One GEMM of the path: on the matrix cores (split the fp32 rows first) or as vector-ALU
 // groups of 8/4/2/1 rows.
+constexpr int WIDE_S = 8;   // most context splits (partials per row and head) of a wide pass's attention
+
 del_status gemm(del_ctx* ctx, GemmP p, int epi, int m, bool mfma) {
   const int waves = ctx->pick_waves(p.NB, p.KT);
   const int64_t wbytes = (int64_t)p.NB * p.KT * 1024;
@@ -383,6 +388,82 @@ del_status run_layer(del_ctx* ctx, int l, int row0, int m, bool chained) {
   return gemm(ctx, p, EPI_RESID, m, false);
 }
 
+// Transformer_l on rows [0, m) of the hidden buffer in one wide pass (prefill): the same five steps
+// as run_layer on the wide GEMM, every GEMM leaving the next one's split tiles behind.
+// `chained`: the previous layer's down projection has left this layer's input tiles in xs_h and
+// their sums of squares in ssq_h.
+del_status run_layer_wide(del_ctx* ctx, int l, int m, bool chained) {
+  const int li = l - 1;
+  hipStream_t s = ctx->stream;
+  char* base = ctx->arena + (size_t)li * ctx->layer_stride;
+  float* hin = ctx->hid_row(l - 1, 0);
+  float* hout = ctx->hid_row(l, 0);
+  auto wide = [&](GemmP& p, int epi) -> del_status {
+    p.M = m;
+    const int pr = prof_begin(ctx, 3, epi, m, (int64_t)p.NB * p.KT * 1024);
+    if (pr >= 0) { p.ev_start = ctx->prof_ev[2 * pr]; p.ev_stop = ctx->prof_ev[2 * pr + 1]; }
+    HIPCHK(launch_gemm_wide(p, epi, s));
+    prof_end(ctx, pr);
+    return DEL_OK;
+  };
+  del_status st;
+  // 1. RMSNorm + fused QKV + rotary + KV append
+  GemmP p = base_gemm(ctx);
+  p.Wt = base + ctx->off_qkv; p.NB = ctx->NBqkv; p.KT = ctx->KTd; p.N = ctx->NBqkv * 16; p.K = ctx->d;
+  p.Q = ctx->q; p.ldq = ctx->qpad;
+  p.Kc = ctx->kc + (size_t)li * ctx->kv_layer_bytes; p.Vc = ctx->vc + (size_t)li * ctx->kv_layer_bytes;
+  p.n_q = ctx->nq; p.n_kv = ctx->nkv; p.hd = ctx->hd; p.Tcap = ctx->Tcap;
+  p.state = ctx->state; p.row_off = 0; p.rope = ctx->rope;
+  void* Kc = p.Kc; void* Vc = p.Vc;
+  if (chained)
+    HIPCHK(launch_rowscale(ctx->ssq_h, ctx->NBd, m, ctx->d, ctx->cfg.rms_eps, ctx->rowscale_w, s));
+  else
+    HIPCHK(launch_prep_split(hin, m, m, 0, ctx->dpad, ctx->d, ctx->KTd, ctx->gain_attn(li), 1, ctx->cfg.rms_eps, ctx->xs_h,
+                             ctx->rowscale_w, s));
+  p.Xs = ctx->xs_h; p.rowscale = ctx->rowscale_w;
+  if ((st = wide(p, EPI_QKV)) != DEL_OK) return st;
+  // 2. causal attention: groups of token rows share the cache reads; then the merge
+  AttnP a;
+  memset(&a, 0, sizeof(a));
+  a.Q = ctx->q; a.ldq = ctx->qpad; a.Kc = Kc; a.Vc = Vc; a.kvdtype = ctx->wd;
+  a.n_q = ctx->nq; a.n_kv = ctx->nkv; a.hd = ctx->hd; a.Tcap = ctx->Tcap; a.m = m;
+  a.state = ctx->state; a.row_off = 0;
+  a.PM = ctx->PM; a.PL = ctx->PL; a.PA = ctx->PA; a.nch_max = WIDE_S; a.ct = ctx->attn_ct;
+  a.O = ctx->attn; a.ldo = ctx->qpad;
+  a.XsOut = ctx->xs_attn; a.xs_cb_stride = (long long)ctx->KTq * 1024;
+  const int groups = ctx->nkv * ceil_div(m, 8);
+  const int S = std::max(1, std::min(WIDE_S, ceil_div(512, groups)));
+  HIPCHK(launch_attention_decode(a, S, s, 8));
+  a.nsplit = S;
+  HIPCHK(launch_attention_merge(a, s));
+  // 3. output projection + residual; leaves the FFN's input tiles
+  p = base_gemm(ctx);
+  p.Wt = base + ctx->off_o; p.NB = ctx->NBd; p.KT = ctx->KTq; p.N = ctx->d; p.K = ctx->qdim;
+  p.R = hin; p.ldr = ctx->dpad; p.Y = hout; p.ldy = ctx->dpad;
+  p.Xs = ctx->xs_attn;
+  p.XsOut = ctx->xs_h1; p.xs_out_cb_stride = (long long)ctx->KTd * 1024; p.gain_out = ctx->gain_ffn(li);
+  p.ssq_out = ctx->ssq_h1;
+  if ((st = wide(p, EPI_RESID)) != DEL_OK) return st;
+  // 4. RMSNorm + fused gate/up + SiLU(gate) * up
+  HIPCHK(launch_rowscale(ctx->ssq_h1, ctx->NBd, m, ctx->d, ctx->cfg.rms_eps, ctx->rowscale_w, s));
+  p = base_gemm(ctx);
+  p.Wt = base + ctx->off_gu; p.NB = ctx->NBgu; p.KT = ctx->KTd; p.N = ctx->NBgu * 16; p.K = ctx->d;
+  p.ACT = ctx->act; p.ldact = ctx->fpad; p.d_ffn = ctx->f;
+  p.Xs = ctx->xs_h1; p.rowscale = ctx->rowscale_w;
+  p.XsOut = ctx->xs_act; p.xs_out_cb_stride = (long long)ctx->KTf * 1024;
+  if ((st = wide(p, EPI_SWIGLU)) != DEL_OK) return st;
+  // 5. down projection + residual (in place); leaves the next layer's input tiles
+  p = base_gemm(ctx);
+  p.Wt = base + ctx->off_dn; p.NB = ctx->NBd; p.KT = ctx->KTf; p.N = ctx->d; p.K = ctx->f;
+  p.R = hout; p.ldr = ctx->dpad; p.Y = hout; p.ldy = ctx->dpad;
+  p.Xs = ctx->xs_act;
+  if (l < ctx->L) {
+    p.XsOut = ctx->xs_h; p.xs_out_cb_stride = (long long)ctx->KTd * 1024; p.gain_out = ctx->gain_attn(li + 1);
+    p.ssq_out = ctx->ssq_h;
+  }
+  return wide(p, EPI_RESID);
+}
+
 GemmP head_gemm(const del_ctx* ctx) {
   GemmP p = base_gemm(ctx);
   p.Wt = ctx->head_t; p.NB = ctx->NBv; p.KT = ctx->KTd; p.N = ctx->V; p.K = ctx->d;
@@ -404,12 +485,12 @@ del_status head_one(del_ctx* ctx, int layer, int row, int* out_id, float* out_co
 
 // Shadow tokens (Section 4.2): final norm + LM head + arg-max of rows 0..m-1 of every layer
 // 1..L, into shadow_ids[(l-1)*m + i], and their confidences into conf_dev[(l-1)*m + i].
-del_status shadow_head(del_ctx* ctx, int m) {
+del_status shadow_head(del_ctx* ctx, int m, int row0 = 0) {
   const int R = ctx->L * m;
   const bool mf = ctx->cfg.use_mfma && ctx->wd == DEL_DTYPE_BF16;
   int nparts = ctx->NBv;
   if (mf) {
-    HIPCHK(launch_prep_split(ctx->hid_row(1, 0), R, m, (int64_t)ctx->maxrows * ctx->dpad, ctx->dpad, ctx->d,
+    HIPCHK(launch_prep_split(ctx->hid_row(1, row0), R, m, (int64_t)ctx->hrows * ctx->dpad, ctx->dpad, ctx->d,
                              ctx->KTd, ctx->gain_final(), 1, ctx->cfg.rms_eps, ctx->xs_shadow, ctx->rowscale,
                              ctx->stream));
     const int pr = prof_begin(ctx, 2, EPI_ARGMAX, R, (int64_t)ctx->NBv * ctx->KTd * 1024);
@@ -420,7 +501,7 @@ del_status shadow_head(del_ctx* ctx, int m) {
   } else {
     for (int l = 1; l <= ctx->L; ++l) {
       GemmP p = head_gemm(ctx);
-      p.X = ctx->hid_row(l, 0);
+      p.X = ctx->hid_row(l, row0);
       p.prow0 = (l - 1) * m;
       del_status st = gemm(ctx, p, EPI_ARGMAX, m, false);
       if (st != DEL_OK) return st;
@@ -435,7 +516,7 @@ void free_all(del_ctx* c) {
                   c->rope, c->hid, c->q, c->attn, c->act, c->xs_layer, c->xs_shadow, c->rowscale, c->xs_h, c->xs_attn,
                   c->xs_h1, c->xs_act, c->ssq_h, c->ssq_h1, c->PM, c->PL,
                   c->PA, c->pval, c->pidx, c->psum, c->conf_dev, c->state, c->draft_ids, c->shadow_ids, c->result, c->ids_dev,
-                  c->logits_dbg, c->sink, c->stage, c->slog, c->swf, c->srows, c->unif_dev};
+                  c->logits_dbg, c->sink, c->stage, c->slog, c->swf, c->srows, c->unif_dev, c->rowscale_w};
   for (void* p : ptrs)
     if (p) (void)hipFree(p);
   if (c->result_host) (void)hipHostFree(c->result_host);
@@ -532,6 +613,7 @@ del_status del_create(const del_config* cfg, void* hip_stream, del_ctx** out) {
   ctx->NBgu = ceil_div(ctx->f, 8);
   ctx->NBv = ceil_div(ctx->V, 16);
   ctx->maxrows = std::max(16, cfg->d_max + 1);
+  ctx->hrows = ctx->maxrows;
   ctx->Tcap = cfg->max_context;
   ctx->gpad = std::max(ctx->dpad, std::max(ctx->qpad, ctx->fpad));
   ctx->loaded.assign((size_t)(ctx->L + 1) * 12, 0);
@@ -578,8 +660,19 @@ del_status del_create(const del_config* cfg, void* hip_stream, del_ctx** out) {
       if (v >= 1 && v <= 64) ctx->attn_dec_rows = v;
     }
   }
+  // wide prefill passes: bf16 weights on the matrix cores with the register attention kernel
+  if (cfg->use_mfma && ctx->wd == DEL_DTYPE_BF16 && ctx->attn_S > 0) {
+    int want = 1024;
+    if (const char* e = getenv("DEL_PREFILL_ROWS")) want = atoi(e);
+    want = std::min(want, ceil_div(ctx->Tcap, 16) * 16);
+    if (want >= 32) {
+      ctx->prows = want / 16 * 16;
+      ctx->hrows = std::max(ctx->maxrows, ctx->prows);
+    }
+  }
   const int Rmax = ctx->L * ctx->maxrows;
   const int KTmax = std::max(ctx->KTd, std::max(ctx->KTq, ctx->KTf));
+  const size_t CBmax = (size_t)ceil_div(ctx->hrows, 16);
 
 #define CK(call)                                                     \
   do {                                                               \
@@ -622,31 +715,33 @@ del_status del_create(const del_config* cfg, void* hip_stream, del_ctx** out) {
     CK(dmalloc(&ctx->rope, tab.size() * sizeof(float2)));
     CK(hipMemcpy(ctx->rope, tab.data(), tab.size() * sizeof(float2), hipMemcpyHostToDevice));
   }
-  const size_t hid_bytes = (size_t)(ctx->L + 1) * ctx->maxrows * ctx->dpad * sizeof(float);
+  const size_t hid_bytes = (size_t)(ctx->L + 1) * ctx->hrows * ctx->dpad * sizeof(float);
   CK(dmalloc(&ctx->hid, hid_bytes));
   CK(hipMemsetAsync(ctx->hid, 0, hid_bytes, ctx->stream));
-  CK(dmalloc(&ctx->q, (size_t)ctx->maxrows * ctx->qpad * 4));
-  CK(dmalloc(&ctx->attn, (size_t)ctx->maxrows * ctx->qpad * 4));
-  CK(dmalloc(&ctx->act, (size_t)ctx->maxrows * ctx->fpad * 4));
-  CK(hipMemsetAsync(ctx->q, 0, (size_t)ctx->maxrows * ctx->qpad * 4, ctx->stream));
-  CK(hipMemsetAsync(ctx->attn, 0, (size_t)ctx->maxrows * ctx->qpad * 4, ctx->stream));
-  CK(hipMemsetAsync(ctx->act, 0, (size_t)ctx->maxrows * ctx->fpad * 4, ctx->stream));
+  CK(dmalloc(&ctx->q, (size_t)ctx->hrows * ctx->qpad * 4));
+  CK(dmalloc(&ctx->attn, (size_t)ctx->hrows * ctx->qpad * 4));
+  CK(dmalloc(&ctx->act, (size_t)ctx->hrows * ctx->fpad * 4));
+  CK(hipMemsetAsync(ctx->q, 0, (size_t)ctx->hrows * ctx->qpad * 4, ctx->stream));
+  CK(hipMemsetAsync(ctx->attn, 0, (size_t)ctx->hrows * ctx->qpad * 4, ctx->stream));
+  CK(hipMemsetAsync(ctx->act, 0, (size_t)ctx->hrows * ctx->fpad * 4, ctx->stream));
   CK(dmalloc(&ctx->xs_layer, (size_t)KTmax * 2048));
   CK(hipMemsetAsync(ctx->xs_layer, 0, (size_t)KTmax * 2048, ctx->stream));
   {
     uint16_t** bufs[4] = {&ctx->xs_h, &ctx->xs_attn, &ctx->xs_h1, &ctx->xs_act};
-    for (auto b : bufs) {
-      CK(dmalloc(b, (size_t)KTmax * 2048));
-      CK(hipMemsetAsync(*b, 0, (size_t)KTmax * 2048, ctx->stream));
+    for (auto b : bufs) {   // one set of tiles per block of 16 token rows
+      CK(dmalloc(b, CBmax * KTmax * 2048));
+      CK(hipMemsetAsync(*b, 0, CBmax * KTmax * 2048, ctx->stream));
     }
-    CK(dmalloc(&ctx->ssq_h, (size_t)16 * ctx->NBd * 4));
-    CK(dmalloc(&ctx->ssq_h1, (size_t)16 * ctx->NBd * 4));
+    CK(dmalloc(&ctx->ssq_h, CBmax * 16 * ctx->NBd * 4));
+    CK(dmalloc(&ctx->ssq_h1, CBmax * 16 * ctx->NBd * 4));
+    CK(dmalloc(&ctx->rowscale_w, CBmax * 16 * 4));
   }
   const size_t xs_sh = (size_t)ceil_div(Rmax, 16) * ctx->KTd * 2048;
   CK(dmalloc(&ctx->xs_shadow, xs_sh));
   CK(hipMemsetAsync(ctx->xs_shadow, 0, xs_sh, ctx->stream));
   CK(dmalloc(&ctx->rowscale, (size_t)(Rmax + 16) * 4));
-  const size_t prow = (size_t)ctx->maxrows * ctx->nq * ctx->nch_max;
+  // attention partials: [row][head][nch_max] for the short passes, [row][head][WIDE_S] for the wide ones
+  const size_t prow = std::max((size_t)ctx->maxrows * ctx->nq * ctx->nch_max, (size_t)ctx->hrows * ctx->nq * WIDE_S);
   CK(dmalloc(&ctx->PM, prow * 4));
   CK(dmalloc(&ctx->PL, prow * 4));
   CK(dmalloc(&ctx->PA, prow * ctx->hd * 4));
@@ -772,30 +867,33 @@ del_status del_prefill(del_ctx* ctx, const int32_t* prompt, int32_t n_prompt, in
   const int w = std::min(ctx->cfg.prefill_window, P);
   std::vector<int> shadow((size_t)L * w, 0);  // [l-1][window position]
   std::vector<float> sconf((size_t)L * w, 0.f);
-  // chunks of up to 16 rows; a ragged chunk, if any, comes first so the last ones are full
-  const int CH = 16;
+  // passes of up to CH rows (16, or the wide pass's rows); a ragged pass, if any, comes first so that
+  // the last ones are full; a pass of more than 16 rows takes the wide path
+  const int CH = ctx->prows > 0 ? ctx->prows : 16;
   int start = 0;
   while (start < P) {
     const int mc = (start == 0 && P % CH != 0) ? P % CH : CH;
+    const bool widep = ctx->prows > 0 && mc > 16;
     HIPCHK(launch_embed(ctx->embed_t, ctx->wd, ctx->KTd, ctx->V, ctx->ids_dev + start, mc, ctx->hid_row(0, 0),
                         ctx->dpad, ctx->d, ctx->stream));
     for (int l = 1; l <= L; ++l) {
-      del_status st = run_layer(ctx, l, 0, mc, l > 1);
+      del_status st = widep ? run_layer_wide(ctx, l, mc, l > 1) : run_layer(ctx, l, 0, mc, l > 1);
       if (st != DEL_OK) return st;
     }
-    if (start + mc > P - w) {  // overlaps the statistics window
-      del_status st = shadow_head(ctx, mc);
+    // rows of this pass inside the statistics window, in groups of up to 16
+    for (int r0 = std::max(0, P - w - start); r0 < mc; r0 += 16) {
+      const int cnt = std::min(16, mc - r0);
+      del_status st = shadow_head(ctx, cnt, r0);
       if (st != DEL_OK) return st;
-      HIPCHK(hipMemcpyAsync(ctx->result_host, ctx->shadow_ids, (size_t)L * mc * 4, hipMemcpyDeviceToHost,
+      HIPCHK(hipMemcpyAsync(ctx->result_host, ctx->shadow_ids, (size_t)L * cnt * 4, hipMemcpyDeviceToHost,
                             ctx->stream));
-      HIPCHK(hipMemcpyAsync(ctx->conf_host, ctx->conf_dev, (size_t)L * mc * 4, hipMemcpyDeviceToHost, ctx->stream));
+      HIPCHK(hipMemcpyAsync(ctx->conf_host, ctx->conf_dev, (size_t)L * cnt * 4, hipMemcpyDeviceToHost, ctx->stream));
       HIPCHK(hipStreamSynchronize(ctx->stream));
-      for (int i = 0; i < mc; ++i) {
-        const int pos = start + i;
-        if (pos < P - w) continue;
+      for (int i = 0; i < cnt; ++i) {
+        const int wpos = start + r0 + i - (P - w);
         for (int l = 1; l <= L; ++l) {
-          shadow[(size_t)(l - 1) * w + (pos - (P - w))] = ctx->result_host[(l - 1) * mc + i];
-          sconf[(size_t)(l - 1) * w + (pos - (P - w))] = ctx->conf_host[(l - 1) * mc + i];
+          shadow[(size_t)(l - 1) * w + wpos] = ctx->result_host[(l - 1) * cnt + i];
+          sconf[(size_t)(l - 1) * w + wpos] = ctx->conf_host[(l - 1) * cnt + i];
         }
       }
     }
@@ -1170,14 +1268,14 @@ del_status del_last_timings(const del_ctx* ctx, float* draft_ms, float* verify_m
 
 del_status del_debug_hidden(const del_ctx* c, int32_t layer, int32_t row, float* dst) {
   del_ctx* ctx = const_cast<del_ctx*>(c);
-  if (!ctx || !dst || layer < 0 || layer > ctx->L || row < 0 || row >= ctx->maxrows) return DEL_E_ARG;
+  if (!ctx || !dst || layer < 0 || layer > ctx->L || row < 0 || row >= ctx->hrows) return DEL_E_ARG;
   HIPCHK(hipStreamSynchronize(ctx->stream));
   HIPCHK(hipMemcpy(dst, ctx->hid_row(layer, row), (size_t)ctx->d * 4, hipMemcpyDeviceToHost));
   return DEL_OK;
 }
 
 del_status del_debug_logits(del_ctx* ctx, int32_t layer, int32_t row, float* dst) {
-  if (!ctx || !dst || layer < 0 || layer > ctx->L || row < 0 || row >= ctx->maxrows) return DEL_E_ARG;
+  if (!ctx || !dst || layer < 0 || layer > ctx->L || row < 0 || row >= ctx->hrows) return DEL_E_ARG;
   if (!ctx->all_loaded()) return DEL_E_STATE;
   GemmP p = head_gemm(ctx);
   p.X = ctx->hid_row(layer, row);
@@ -1186,6 +1284,12 @@ del_status del_debug_logits(del_ctx* ctx, int32_t layer, int32_t row, float* dst
   if (st != DEL_OK) return st;
   HIPCHK(hipStreamSynchronize(ctx->stream));
   HIPCHK(hipMemcpy(dst, ctx->logits_dbg, (size_t)ctx->V * 4, hipMemcpyDeviceToHost));
+  return DEL_OK;
+}
+
+del_status del_debug_last_rows(const del_ctx* ctx, int32_t* rows) {
+  if (!ctx || !rows) return DEL_E_ARG;
+  *rows = ctx->last_rows;
   return DEL_OK;
 }
 

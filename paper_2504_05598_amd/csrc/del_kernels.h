@@ -61,6 +61,9 @@ struct GemmP {
   const float* gain_out;
   float* ssq_out;
   const float* ssq_in; int ssq_nb;
+  // wide path (many token rows per launch): XsOut holds one set of tiles per block of 16 token
+  // rows, this many 16-bit elements apart
+  long long xs_out_cb_stride;
   // vector path, one row: the input row is the attention output given as att_S per-split
   // softmax partials per head (max, sum, weighted values [hd]), merged while staging
   const float* att_PM; const float* att_PL; const float* att_PA;
@@ -83,6 +86,8 @@ struct AttnP {
   int nsplit;                   // > 0: the partials come from the decode kernel, this many per row
   float* O; int ldo;            // combined output [m][n_q*hd]
   uint16_t* XsOut;              // optional: the same rows as split tiles (input of the O projection)
+  long long xs_cb_stride;       // 16-bit elements between the tiles of consecutive blocks of 16 token rows
+  int rw;                       // token rows per work-group of the register kernel (set by the launcher)
 };
 
 hipError_t launch_gemm_valu(const GemmP& p, int epi, int waves, hipStream_t s);
@@ -91,11 +96,18 @@ hipError_t launch_gemm_mfma(const GemmP& p, int epi, int waves, int col_blocks, 
 hipError_t launch_head_gemm(const void* Wt, int NB, int KT, int N, const uint16_t* Xs, int R, const float* rowscale,
                             float* pval, int* pidx, float* psum, int* n_slabs, hipStream_t s,
                             hipEvent_t ev_start = nullptr, hipEvent_t ev_stop = nullptr);
+// Many token rows at once (prefill): 8 row blocks x up to 256 token rows per work-group, the split
+// activation tiles ([cb][kt] for p.M rows) staged through LDS.  epi: EPI_RESID, EPI_QKV or EPI_SWIGLU.
+hipError_t launch_gemm_wide(const GemmP& p, int epi, hipStream_t s);
+// rowscale[row] = 1 / sqrt(sum_b ssq[row][b] / K + eps) for rows < M.
+hipError_t launch_rowscale(const float* ssq, int nb, int M, int K, float eps, float* rowscale, hipStream_t s);
 hipError_t launch_prep_split(const float* src, int rows, int rows_per_group, int64_t group_stride,
                              int ld, int K, int KT, const float* gain, int rms, float eps,
                              uint16_t* Xs, float* rowscale, hipStream_t s);
 hipError_t launch_attention(const AttnP& p, hipStream_t s);
-hipError_t launch_attention_decode(const AttnP& p, int S, hipStream_t s);
+// rows_per_wg > 1: that many consecutive token rows share a work-group's cache reads (prefill);
+// the launcher rounds it down to what the shape's instantiation offers.
+hipError_t launch_attention_decode(const AttnP& p, int S, hipStream_t s, int rows_per_wg = 1);
 hipError_t launch_attention_merge(const AttnP& p, hipStream_t s);
 bool attention_decode_supported(int kvdtype, int hd, int G);
 hipError_t launch_embed(const void* Et, int wdtype, int KT, int vocab, const int* ids, int m,

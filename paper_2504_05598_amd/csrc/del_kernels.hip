@@ -63,24 +63,29 @@ __device__ __forceinline__ void split_store8(uint16_t* Xs, int k8, int token, co
 // ---------------------------------------------------------------------------------------
 // Epilogues.  fin[mi][r] holds the finished 16 outputs of row-block nb for token row mi.
 // ---------------------------------------------------------------------------------------
-template <int EPI, bool BF16KV>
-__device__ __forceinline__ void epilogue(const GemmP& p, int nb, float (*fin)[16], int m, int rowbase) {
-  const int nthr = blockDim.x;
+// WAVE: run by one wave on its own tile (thread index = lane) instead of the whole work-group.
+// XsOut / ssq_out: where this block of 16 token rows puts its split tiles / sums of squares
+// (token row mi of the block is row mi there).
+template <int EPI, bool BF16KV, bool WAVE = false>
+__device__ __forceinline__ void epilogue(const GemmP& p, int nb, float (*fin)[16], int m, int rowbase,
+                                         uint16_t* XsOut, float* ssq_out) {
+  const int nthr = WAVE ? 64 : blockDim.x;
+  const int t0 = WAVE ? (threadIdx.x & 63) : threadIdx.x;
   if (EPI == EPI_STORE || EPI == EPI_RESID) {
-    for (int tid = threadIdx.x; tid < m * 16; tid += nthr) {
+    for (int tid = t0; tid < m * 16; tid += nthr) {
       const int mi = tid >> 4, r = tid & 15, n = nb * 16 + r;
       if (n < p.N) {
         float v = fin[mi][r];
         if (EPI == EPI_RESID) v += p.R[(size_t)(rowbase + mi) * p.ldr + n];
         p.Y[(size_t)(rowbase + mi) * p.ldy + n] = v;
-        if (EPI == EPI_RESID && p.XsOut) fin[mi][r] = v;   // keep the residual-added value for the split below
-      } else if (EPI == EPI_RESID && p.XsOut) {
+        if (EPI == EPI_RESID && XsOut) fin[mi][r] = v;   // keep the residual-added value for the split below
+      } else if (EPI == EPI_RESID && XsOut) {
         fin[mi][r] = 0.f;
       }
     }
-    if (EPI == EPI_RESID && p.XsOut) {   // rowbase == 0 on this path (one block of <= 16 token rows)
-      __syncthreads();
-      for (int tid = threadIdx.x; tid < m * 2; tid += nthr) {
+    if (EPI == EPI_RESID && XsOut) {   // rowbase == 0 on this path (one block of <= 16 token rows)
+      if (WAVE) __builtin_amdgcn_wave_barrier(); else __syncthreads();
+      for (int tid = t0; tid < m * 2; tid += nthr) {
         const int mi = tid >> 1, half = tid & 1;
         float v[8];
 #pragma unroll
@@ -88,19 +93,19 @@ __device__ __forceinline__ void epilogue(const GemmP& p, int nb, float (*fin)[16
           const int n = nb * 16 + half * 8 + e;
           v[e] = fin[mi][half * 8 + e] * (p.gain_out ? p.gain_out[n] : 1.f);
         }
-        split_store8(p.XsOut, nb * 2 + half, mi, v);
+        split_store8(XsOut, nb * 2 + half, mi, v);
       }
-      if (p.ssq_out) {
-        for (int tid = threadIdx.x; tid < m; tid += nthr) {
+      if (ssq_out) {
+        for (int tid = t0; tid < m; tid += nthr) {
           float q = 0.f;
 #pragma unroll
           for (int r = 0; r < 16; ++r) q += fin[tid][r] * fin[tid][r];
-          p.ssq_out[(size_t)tid * p.NB + nb] = q;
+          ssq_out[(size_t)tid * p.NB + nb] = q;
         }
       }
     }
   } else if (EPI == EPI_QKV) {
-    for (int tid = threadIdx.x; tid < m * 16; tid += nthr) {
+    for (int tid = t0; tid < m * 16; tid += nthr) {
       const int mi = tid >> 4, r = tid & 15;
       const int hd = p.hd, half = hd >> 1;
       const int v0 = nb * 16;
@@ -129,7 +134,7 @@ __device__ __forceinline__ void epilogue(const GemmP& p, int nb, float (*fin)[16
       }
     }
   } else if (EPI == EPI_SWIGLU) {
-    for (int tid = threadIdx.x; tid < m * 8; tid += nthr) {
+    for (int tid = t0; tid < m * 8; tid += nthr) {
       const int mi = tid >> 3, r = tid & 7, j = nb * 8 + r;
       float a = 0.f;
       if (j < p.d_ffn) {
@@ -137,15 +142,15 @@ __device__ __forceinline__ void epilogue(const GemmP& p, int nb, float (*fin)[16
         a = gt / (1.0f + expf(-gt)) * up;
         p.ACT[(size_t)(rowbase + mi) * p.ldact + j] = a;
       }
-      if (p.XsOut) {   // gather the 8 activations of this token row in one lane, store them split
+      if (XsOut) {   // gather the 8 activations of this token row in one lane, store them split
         float v[8];
 #pragma unroll
         for (int e = 0; e < 8; ++e) v[e] = __shfl(a, (threadIdx.x & 56) + e);
-        if (r == 0) split_store8(p.XsOut, nb, mi, v);
+        if (r == 0) split_store8(XsOut, nb, mi, v);
       }
     }
   } else if (EPI == EPI_ARGMAX) {
-    for (int tid = threadIdx.x; tid < m; tid += nthr) {
+    for (int tid = t0; tid < m; tid += nthr) {
       const int mi = tid;
       float best = -INFINITY;
       int bi = 0x7FFFFFFF;
@@ -351,7 +356,7 @@ __global__ void __launch_bounds__(1024) gemm_valu_k(GemmP p) {
     fin[mi][r] = s;
   }
   __syncthreads();
-  epilogue<EPI, KPL == 8>(p, nb, fin, M, 0);
+  epilogue<EPI, KPL == 8>(p, nb, fin, M, 0, p.XsOut, p.ssq_out);
 }
 
 // ---------------------------------------------------------------------------------------
@@ -448,7 +453,7 @@ __global__ void __launch_bounds__(1024) gemm_mfma_k(GemmP p) {
     }
   }
   __syncthreads();
-  epilogue<EPI, true>(p, nb, fin, mvalid, cb * 16);
+  epilogue<EPI, true>(p, nb, fin, mvalid, cb * 16, p.XsOut, p.ssq_out);
 }
 
 // ---------------------------------------------------------------------------------------
@@ -603,6 +608,113 @@ __global__ void __launch_bounds__(512) head_gemm_k(const uint4* __restrict__ Wt,
       }
     }
   }
+}
+
+// ---------------------------------------------------------------------------------------
+// Wide GEMM for passes over many token rows (prefill): the loop of the shadow-head GEMM (a slab
+// of 8 row blocks per work-group, one per wave, streamed once; up to 16 blocks of 16 token rows
+// whose split tiles are staged in LDS and shared by the waves) with the layer epilogues: every
+// wave hands its 16x16 tiles through a 1 KiB LDS patch of its own to the epilogue, block of
+// token rows by block of token rows.
+// ---------------------------------------------------------------------------------------
+template <int EPI>
+__global__ void __launch_bounds__(512) gemm_wide_k(GemmP p) {
+  extern __shared__ __align__(16) uint4 bs[];   // [2][HG_CB * 128]
+  constexpr int U = 4;
+  const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
+  const int NB = p.NB, KT = p.KT;
+  const int CB = (p.M + 15) >> 4;
+  const int slab = blockIdx.x, cb0 = blockIdx.y * HG_CB;
+  const int ncb = min(HG_CB, CB - cb0);
+  const int nb = slab * HG_W + wave;
+  const bool rowok = nb < NB;
+  const uint4* Wt = (const uint4*)p.Wt;
+  const uint4* Xs = (const uint4*)p.Xs;
+  const uint4* wp = Wt + (size_t)(rowok ? nb : NB - 1) * KT * 64 + lane;
+  floatx4 acc[HG_CB];
+#pragma unroll
+  for (int c = 0; c < HG_CB; ++c) acc[c] = (floatx4){0.f, 0.f, 0.f, 0.f};
+  uint4 br[4], a[U], an[U];
+  auto loadB = [&](int kt) {
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      const int idx = tid + 512 * j, cbi = idx >> 7;
+      br[j] = cbi < ncb ? Xs[((size_t)(cb0 + cbi) * KT + kt) * 128 + (idx & 127)] : make_uint4(0, 0, 0, 0);
+    }
+  };
+  auto storeB = [&](int buf) {
+#pragma unroll
+    for (int j = 0; j < 4; ++j) bs[buf * (HG_CB * 128) + tid + 512 * j] = br[j];
+  };
+  auto tile = [&](const uint4& aw, int kt) {
+    const int cur = kt & 1;
+    loadB(min(kt + 1, KT - 1));
+    const bf16x8 av = __builtin_bit_cast(bf16x8, aw);
+    const uint4* bp = bs + cur * (HG_CB * 128) + lane;
+#pragma unroll
+    for (int c = 0; c < HG_CB; ++c) {
+      if (c < ncb) {
+        acc[c] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(av, __builtin_bit_cast(bf16x8, bp[c * 128]), acc[c], 0, 0, 0);
+        acc[c] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(av, __builtin_bit_cast(bf16x8, bp[c * 128 + 64]), acc[c], 0, 0, 0);
+      }
+    }
+    storeB(cur ^ 1);
+    __syncthreads();
+  };
+  const int ngroups = KT / U;
+  loadB(0);
+  if (ngroups > 0) {
+#pragma unroll
+    for (int u = 0; u < U; ++u) a[u] = ld_stream(wp + u * 64);
+  }
+  storeB(0);
+  __syncthreads();
+  for (int gi = 0; gi + 1 < ngroups; ++gi) {
+    const uint4* wn = wp + (size_t)(gi + 1) * U * 64;
+#pragma unroll
+    for (int u = 0; u < U; ++u) an[u] = ld_stream(wn + u * 64);
+#pragma unroll
+    for (int u = 0; u < U; ++u) tile(a[u], gi * U + u);
+#pragma unroll
+    for (int u = 0; u < U; ++u) a[u] = an[u];
+  }
+  if (ngroups > 0) {
+#pragma unroll
+    for (int u = 0; u < U; ++u) tile(a[u], (ngroups - 1) * U + u);
+  }
+  for (int kt = ngroups * U; kt < KT; ++kt) {
+    const uint4 aw = ld_stream(wp + (size_t)kt * 64);
+    tile(aw, kt);
+  }
+  // epilogue: lane holds rows 4g+j of its row block for token lane%16 of every block of token rows
+  float (*fin)[16] = reinterpret_cast<float (*)[16]>(reinterpret_cast<float*>(bs) + wave * 256);
+  const int g = lane >> 4, token = lane & 15;
+  if (!rowok) return;   // no barrier below: each wave works on its own LDS patch
+#pragma unroll
+  for (int c = 0; c < HG_CB; ++c) {
+    if (c < ncb) {
+      const int rowbase = (cb0 + c) * 16;
+      const int mvalid = min(16, p.M - rowbase);
+      const float sc = (p.rowscale && token < mvalid) ? p.rowscale[rowbase + token] : 1.0f;
+#pragma unroll
+      for (int j = 0; j < 4; ++j) fin[token][4 * g + j] = acc[c][j] * sc;
+      __builtin_amdgcn_wave_barrier();
+      epilogue<EPI, true, true>(p, nb, fin, mvalid, rowbase,
+                                p.XsOut ? p.XsOut + (size_t)(cb0 + c) * p.xs_out_cb_stride : nullptr,
+                                p.ssq_out ? p.ssq_out + (size_t)rowbase * p.NB : nullptr);
+      __builtin_amdgcn_wave_barrier();
+    }
+  }
+}
+
+// One wave per token row: the RMS scale from the per-block sums of squares a RESID epilogue left.
+__global__ void __launch_bounds__(256) rowscale_k(const float* ssq, int nb, int M, int K, float eps, float* rowscale) {
+  const int row = blockIdx.x * 4 + (threadIdx.x >> 6), lane = threadIdx.x & 63;
+  if (row >= M) return;
+  float q = 0.f;
+  for (int b = lane; b < nb; b += 64) q += ssq[(size_t)row * nb + b];
+  for (int o = 32; o > 0; o >>= 1) q += __shfl_xor(q, o);
+  if (lane == 0) rowscale[row] = 1.0f / sqrtf(q / (float)K + eps);
 }
 
 // ---------------------------------------------------------------------------------------
@@ -803,36 +915,42 @@ __global__ void __launch_bounds__(256) attn_partial_k(AttnP p) {
 // ---------------------------------------------------------------------------------------
 struct SoftAcc { float m, l; };
 
-template <typename KVT, int HD, int G>
+// RW > 1 (prefill): RW consecutive token rows share the work-group's cache reads; query q = r * G + g
+// is head g of the kv group for token row mi0 + r and sees cache rows up to its own position only.
+template <typename KVT, int HD, int G, int RW>
 __global__ void __launch_bounds__(512) attn_decode_k(AttnP p) {
+  constexpr int NQ = G * RW;
   constexpr int EPL = 16 / sizeof(KVT);   // elements per lane and load
   constexpr int LPR = HD / EPL;           // lanes per cache row
   constexpr int RPL = 64 / LPR;           // cache rows per wave-wide load
   constexpr int UL = 4;                   // loads in flight per wave, matrix and pipeline stage
   constexpr int NWV = 8;
-  __shared__ float sm[NWV][G], sl[NWV][G];
-  __shared__ float sa[NWV][G][HD];
+  __shared__ float sm[NWV][NQ], sl[NWV][NQ];
+  __shared__ float sa[NWV][NQ][HD];
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
   const int split = blockIdx.x, kvh = blockIdx.y, S = gridDim.x;
-  const int mi = blockIdx.z;                              // token row of this pass; attends rows <= its own
-  const int T_end = p.state[0] + p.row_off + mi + 1;
+  const int mi0 = blockIdx.z * RW;                        // first token row of this work-group
+  const int nrow = min(RW, p.m - mi0);                    // rows it really has
+  const int T0 = p.state[0] + p.row_off + mi0;            // row mi0 + r attends cache rows <= T0 + r
+  const int T_end = T0 + nrow;
   const int rps = ((T_end + S - 1) / S + RPL - 1) / RPL * RPL;   // rows per split, whole loads
   const int t_lo = split * rps, t_hi = min(T_end, t_lo + rps);
   const int rs = lane / LPR, dl = lane % LPR;
   const float scale = 1.0f / sqrtf((float)HD);
-  float q[G][EPL];
+  float q[NQ][EPL];
 #pragma unroll
-  for (int g = 0; g < G; ++g) {
-    const float* qp = p.Q + (size_t)mi * p.ldq + (size_t)(kvh * G + g) * HD + dl * EPL;
+  for (int g = 0; g < NQ; ++g) {
+    // a ragged last group re-reads its last row; those queries' results are dropped
+    const float* qp = p.Q + (size_t)(mi0 + min(g / G, nrow - 1)) * p.ldq + (size_t)(kvh * G + g % G) * HD + dl * EPL;
 #pragma unroll
     for (int e = 0; e < EPL; e += 4) {
       const float4 t = *(const float4*)(qp + e);
       q[g][e] = t.x * scale; q[g][e + 1] = t.y * scale; q[g][e + 2] = t.z * scale; q[g][e + 3] = t.w * scale;
     }
   }
-  float m[G], l[G], acc[G][EPL];
+  float m[NQ], l[NQ], acc[NQ][EPL];
 #pragma unroll
-  for (int g = 0; g < G; ++g) {
+  for (int g = 0; g < NQ; ++g) {
     m[g] = -INFINITY; l[g] = 0.f;
 #pragma unroll
     for (int e = 0; e < EPL; ++e) acc[g][e] = 0.f;
@@ -845,18 +963,19 @@ __global__ void __launch_bounds__(512) attn_decode_k(AttnP p) {
   auto row_of = [&](int j) { return min(t_lo + j * RPL + rs, t_hi - 1); };
   uint4 kc[UL], vc[UL], kn[UL], vn[UL];
   auto consume = [&](const uint4& kk, const uint4& vv, int j) {
-    const bool valid = j < ngrp && t_lo + j * RPL + rs < t_hi;
+    const int trow = t_lo + j * RPL + rs;
+    const bool valid = j < ngrp && trow < t_hi;
     float kf[EPL], vf[EPL];
     if (sizeof(KVT) == 2) { WDec<8>::dec(kk, kf); WDec<8>::dec(vv, vf); }
     else { WDec<4>::dec(kk, kf); WDec<4>::dec(vv, vf); }
 #pragma unroll
-    for (int g = 0; g < G; ++g) {
+    for (int g = 0; g < NQ; ++g) {
       float sdot = 0.f;
 #pragma unroll
       for (int e = 0; e < EPL; ++e) sdot += q[g][e] * kf[e];
 #pragma unroll
       for (int o = 1; o < LPR; o <<= 1) sdot += __shfl_xor(sdot, o);
-      if (valid) {
+      if (valid && (RW == 1 || trow <= T0 + g / G)) {
         const float mn = fmaxf(m[g], sdot);
         const float c = expf(m[g] - mn);      // m = -inf at the first row: exp(-inf) = 0
         const float pr = expf(sdot - mn);
@@ -893,7 +1012,7 @@ __global__ void __launch_bounds__(512) attn_decode_k(AttnP p) {
   }
   // merge the lane groups of a wave (same value dims, different rows) ...
 #pragma unroll
-  for (int g = 0; g < G; ++g) {
+  for (int g = 0; g < NQ; ++g) {
 #pragma unroll
     for (int o = LPR; o < 64; o <<= 1) {
       const float m2 = __shfl_xor(m[g], o), l2 = __shfl_xor(l[g], o);
@@ -913,8 +1032,9 @@ __global__ void __launch_bounds__(512) attn_decode_k(AttnP p) {
   }
   __syncthreads();
   // ... then the waves, in a fixed order; one partial per (query row, split)
-  for (int i = tid; i < G * HD; i += 512) {
+  for (int i = tid; i < NQ * HD; i += 512) {
     const int g = i / HD, d = i - g * HD;
+    if (g / G >= nrow) continue;
     float M = -INFINITY;
 #pragma unroll
     for (int w = 0; w < NWV; ++w) M = fmaxf(M, sm[w][g]);
@@ -925,7 +1045,7 @@ __global__ void __launch_bounds__(512) attn_decode_k(AttnP p) {
       L += c * sl[w][g];
       A += c * sa[w][g][d];
     }
-    const size_t prow = ((size_t)mi * p.n_q + kvh * G + g) * p.nch_max + split;
+    const size_t prow = ((size_t)(mi0 + g / G) * p.n_q + kvh * G + g % G) * p.nch_max + split;
     if (d == 0) { p.PM[prow] = M; p.PL[prow] = L; }
     p.PA[prow * HD + d] = A;
   }
@@ -960,7 +1080,8 @@ __global__ void __launch_bounds__(128) attn_combine_k(AttnP p) {
     const int k = h * p.hd + d;
     const uint16_t hi = f32_to_bf16_rne(o);
     const uint16_t lo = f32_to_bf16_rne(o - bf16_bits_to_f32(hi));
-    uint16_t* dst = p.XsOut + (size_t)(k >> 5) * 1024 + (((k & 31) >> 3) * 16 + mi) * 8 + (k & 7);
+    uint16_t* dst = p.XsOut + (size_t)(mi >> 4) * p.xs_cb_stride + (size_t)(k >> 5) * 1024 +
+                    (((k & 31) >> 3) * 16 + (mi & 15)) * 8 + (k & 7);
     dst[0] = hi;
     dst[512] = lo;
   }
@@ -1217,6 +1338,41 @@ hipError_t launch_gemm_mfma(const GemmP& p, int epi, int waves, int col_blocks, 
   return hipGetLastError();
 }
 
+hipError_t launch_gemm_wide(const GemmP& p, int epi, hipStream_t s) {
+  if (p.NB <= 0 || p.KT <= 0 || p.M < 1 || p.wdtype != 1 || !p.Xs) return hipErrorInvalidValue;
+  const int CB = (p.M + 15) / 16, NS = (p.NB + HG_W - 1) / HG_W;
+  const size_t lds = (size_t)2 * HG_CB * 128 * sizeof(uint4);
+  static bool raised[5] = {false, false, false, false, false};
+  dim3 grid(NS, (CB + HG_CB - 1) / HG_CB), block(512);
+  const bool timed = p.ev_start && p.ev_stop;
+#define DEL_WIDE_CASE(E)                                                                                              \
+  case E: {                                                                                                           \
+    if (!raised[E]) {                                                                                                 \
+      hipError_t e = hipFuncSetAttribute((const void*)gemm_wide_k<E>, hipFuncAttributeMaxDynamicSharedMemorySize,     \
+                                         (int)lds);                                                                   \
+      if (e != hipSuccess) return e;                                                                                  \
+      raised[E] = true;                                                                                               \
+    }                                                                                                                 \
+    if (timed) hipExtLaunchKernelGGL((gemm_wide_k<E>), grid, block, (uint32_t)lds, s, p.ev_start, p.ev_stop, 0, p);   \
+    else hipLaunchKernelGGL((gemm_wide_k<E>), grid, block, lds, s, p);                                                \
+    break;                                                                                                            \
+  }
+  switch (epi) {
+    DEL_WIDE_CASE(EPI_RESID)
+    DEL_WIDE_CASE(EPI_QKV)
+    DEL_WIDE_CASE(EPI_SWIGLU)
+    default: return hipErrorInvalidValue;
+  }
+#undef DEL_WIDE_CASE
+  return hipGetLastError();
+}
+
+hipError_t launch_rowscale(const float* ssq, int nb, int M, int K, float eps, float* rowscale, hipStream_t s) {
+  if (M < 1 || nb < 1) return hipErrorInvalidValue;
+  hipLaunchKernelGGL(rowscale_k, dim3((M + 3) / 4), dim3(256), 0, s, ssq, nb, M, K, eps, rowscale);
+  return hipGetLastError();
+}
+
 hipError_t launch_head_gemm(const void* Wt, int NB, int KT, int N, const uint16_t* Xs, int R, const float* rowscale,
                             float* pval, int* pidx, float* psum, int* n_slabs, hipStream_t s, hipEvent_t ev_start,
                             hipEvent_t ev_stop) {
@@ -1255,15 +1411,19 @@ static size_t attn_lds_bytes(int hd, int esize, int ct, int qb) {
 
 // Decode path (m == 1) for the shapes the register kernel is built for; S = number of splits.
 // Returns hipErrorNotSupported for other shapes (the caller falls back to the staged kernels).
-hipError_t launch_attention_decode(const AttnP& p, int S, hipStream_t s) {
+hipError_t launch_attention_decode(const AttnP& p, int S, hipStream_t s, int rows_per_wg) {
   if (p.m < 1 || S < 1 || S > p.nch_max) return hipErrorInvalidValue;
   const int G = p.n_q / p.n_kv;
-  dim3 grid(S, p.n_kv, p.m), block(512);   // one work-group per (split, kv head, token row)
-  if (p.kvdtype == 1 && p.hd == 128 && G == 1) hipLaunchKernelGGL((attn_decode_k<uint16_t, 128, 1>), grid, block, 0, s, p);
-  else if (p.kvdtype == 1 && p.hd == 64 && G == 4) hipLaunchKernelGGL((attn_decode_k<uint16_t, 64, 4>), grid, block, 0, s, p);
-  else if (p.kvdtype == 1 && p.hd == 128 && G == 8) hipLaunchKernelGGL((attn_decode_k<uint16_t, 128, 8>), grid, block, 0, s, p);
-  else if (p.kvdtype == 0 && p.hd == 64 && G == 1) hipLaunchKernelGGL((attn_decode_k<float, 64, 1>), grid, block, 0, s, p);
+  const bool many = rows_per_wg > 1;
+  // one work-group per (split, kv head, group of token rows); G * rows per group <= 8 queries
+#define DEL_ATT(KVT, HD, GG, RW)                                                                    \
+  hipLaunchKernelGGL((attn_decode_k<KVT, HD, GG, RW>), dim3(S, p.n_kv, (p.m + RW - 1) / RW), dim3(512), 0, s, p)
+  if (p.kvdtype == 1 && p.hd == 128 && G == 1) { if (many) DEL_ATT(uint16_t, 128, 1, 8); else DEL_ATT(uint16_t, 128, 1, 1); }
+  else if (p.kvdtype == 1 && p.hd == 64 && G == 4) { if (many) DEL_ATT(uint16_t, 64, 4, 2); else DEL_ATT(uint16_t, 64, 4, 1); }
+  else if (p.kvdtype == 1 && p.hd == 128 && G == 8) DEL_ATT(uint16_t, 128, 8, 1);
+  else if (p.kvdtype == 0 && p.hd == 64 && G == 1) { if (many) DEL_ATT(float, 64, 1, 4); else DEL_ATT(float, 64, 1, 1); }
   else return hipErrorNotSupported;
+#undef DEL_ATT
   return hipGetLastError();
 }
 

@@ -100,8 +100,8 @@ def lockstep(cfg, oracle: Oracle, ctx: DelContext, prompt, n_tokens, schedule=No
     exact = all(st["last_c"][l] == pre.c[l] for l in range(1, L + 1)) and first == pre.first_token
     if check_hidden:
         for l in (1, L // 2 + 1, L):
-            # the last prompt position is the last row of the last prefill chunk (<= 16 rows)
-            err = _rel_err(ctx.hidden(l, min(len(prompt), 16) - 1), pre.hidden[l, -1].float().numpy())
+            # the last prompt position is the last row of the last prefill pass
+            err = _rel_err(ctx.hidden(l, ctx.last_rows() - 1), pre.hidden[l, -1].float().numpy())
             rep.max_hidden_err = max(rep.max_hidden_err, err)
             assert err <= HID_TOL, ("prefill hidden", l, err)
     emitted = [pre.first_token]

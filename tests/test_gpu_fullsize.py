@@ -51,7 +51,7 @@ def _first_divergence_is_near_tie(ctx, cfg, prompt, a, b):
     for i in range(n):
         if a[i] != b[i]:
             ctx.prefill(list(prompt) + a[:i])
-            row = min(len(prompt) + i, 16) - 1
+            row = ctx.last_rows() - 1
             lg = np.sort(ctx.logits(cfg.n_layers, row))
             gap = float(lg[-1] - lg[-2])
             assert gap < 1e-2, f"streams differ at {i} ({a[i]} vs {b[i]}) with top-2 gap {gap}"
