@@ -617,45 +617,60 @@ __global__ void __launch_bounds__(512) head_gemm_k(const uint4* __restrict__ Wt,
 // wave hands its 16x16 tiles through a 1 KiB LDS patch of its own to the epilogue, block of
 // token rows by block of token rows.
 // ---------------------------------------------------------------------------------------
-template <int EPI>
+// RB row blocks per wave (a staged activation tile then feeds RB matrix instructions, which halves
+// the LDS traffic per instruction at RB = 2), CBW blocks of 16 token rows per work-group (fewer for
+// the matrices with few rows, so that the launch still fills the chip).
+template <int EPI, int RB, int CBW>
 __global__ void __launch_bounds__(512) gemm_wide_k(GemmP p) {
-  extern __shared__ __align__(16) uint4 bs[];   // [2][HG_CB * 128]
+  extern __shared__ __align__(16) uint4 bs[];   // [2][CBW * 128]
   constexpr int U = 4;
+  constexpr int BL = CBW * 128 / 512;           // 16-byte pieces of the activation tiles per thread
+  static_assert(CBW * 128 % 512 == 0 && BL >= 1, "CBW must be a multiple of 4");
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
   const int NB = p.NB, KT = p.KT;
   const int CB = (p.M + 15) >> 4;
-  const int slab = blockIdx.x, cb0 = blockIdx.y * HG_CB;
-  const int ncb = min(HG_CB, CB - cb0);
-  const int nb = slab * HG_W + wave;
-  const bool rowok = nb < NB;
+  const int slab = blockIdx.x, cb0 = blockIdx.y * CBW;
+  const int ncb = min(CBW, CB - cb0);
+  const int nb0 = (slab * HG_W + wave) * RB;
   const uint4* Wt = (const uint4*)p.Wt;
   const uint4* Xs = (const uint4*)p.Xs;
-  const uint4* wp = Wt + (size_t)(rowok ? nb : NB - 1) * KT * 64 + lane;
-  floatx4 acc[HG_CB];
+  // loads are unconditional (clamped row block) so that the steady-state loop has no branches
+  // around memory operations; results of a row block beyond the last are dropped
+  const uint4* wp[RB];
 #pragma unroll
-  for (int c = 0; c < HG_CB; ++c) acc[c] = (floatx4){0.f, 0.f, 0.f, 0.f};
-  uint4 br[4], a[U], an[U];
+  for (int r = 0; r < RB; ++r) wp[r] = Wt + (size_t)min(nb0 + r, NB - 1) * KT * 64 + lane;
+  floatx4 acc[RB][CBW];
+#pragma unroll
+  for (int r = 0; r < RB; ++r)
+#pragma unroll
+    for (int c = 0; c < CBW; ++c) acc[r][c] = (floatx4){0.f, 0.f, 0.f, 0.f};
+  uint4 br[BL], a[RB][U], an[RB][U];
   auto loadB = [&](int kt) {
 #pragma unroll
-    for (int j = 0; j < 4; ++j) {
+    for (int j = 0; j < BL; ++j) {
       const int idx = tid + 512 * j, cbi = idx >> 7;
       br[j] = cbi < ncb ? Xs[((size_t)(cb0 + cbi) * KT + kt) * 128 + (idx & 127)] : make_uint4(0, 0, 0, 0);
     }
   };
   auto storeB = [&](int buf) {
 #pragma unroll
-    for (int j = 0; j < 4; ++j) bs[buf * (HG_CB * 128) + tid + 512 * j] = br[j];
+    for (int j = 0; j < BL; ++j) bs[buf * (CBW * 128) + tid + 512 * j] = br[j];
   };
-  auto tile = [&](const uint4& aw, int kt) {
+  auto tile = [&](const uint4 (&aw)[RB][U], int u, int kt) {
     const int cur = kt & 1;
     loadB(min(kt + 1, KT - 1));
-    const bf16x8 av = __builtin_bit_cast(bf16x8, aw);
-    const uint4* bp = bs + cur * (HG_CB * 128) + lane;
+    const uint4* bp = bs + cur * (CBW * 128) + lane;
 #pragma unroll
-    for (int c = 0; c < HG_CB; ++c) {
+    for (int c = 0; c < CBW; ++c) {
       if (c < ncb) {
-        acc[c] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(av, __builtin_bit_cast(bf16x8, bp[c * 128]), acc[c], 0, 0, 0);
-        acc[c] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(av, __builtin_bit_cast(bf16x8, bp[c * 128 + 64]), acc[c], 0, 0, 0);
+        const bf16x8 bh = __builtin_bit_cast(bf16x8, bp[c * 128]);
+        const bf16x8 bl = __builtin_bit_cast(bf16x8, bp[c * 128 + 64]);
+#pragma unroll
+        for (int r = 0; r < RB; ++r) {
+          const bf16x8 av = __builtin_bit_cast(bf16x8, aw[r][u]);
+          acc[r][c] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(av, bh, acc[r][c], 0, 0, 0);
+          acc[r][c] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(av, bl, acc[r][c], 0, 0, 0);
+        }
       }
     }
     storeB(cur ^ 1);
@@ -665,44 +680,55 @@ __global__ void __launch_bounds__(512) gemm_wide_k(GemmP p) {
   loadB(0);
   if (ngroups > 0) {
 #pragma unroll
-    for (int u = 0; u < U; ++u) a[u] = ld_stream(wp + u * 64);
+    for (int r = 0; r < RB; ++r)
+#pragma unroll
+      for (int u = 0; u < U; ++u) a[r][u] = ld_stream(wp[r] + u * 64);
   }
   storeB(0);
   __syncthreads();
   for (int gi = 0; gi + 1 < ngroups; ++gi) {
-    const uint4* wn = wp + (size_t)(gi + 1) * U * 64;
 #pragma unroll
-    for (int u = 0; u < U; ++u) an[u] = ld_stream(wn + u * 64);
+    for (int r = 0; r < RB; ++r)
 #pragma unroll
-    for (int u = 0; u < U; ++u) tile(a[u], gi * U + u);
+      for (int u = 0; u < U; ++u) an[r][u] = ld_stream(wp[r] + (size_t)(gi + 1) * U * 64 + u * 64);
 #pragma unroll
-    for (int u = 0; u < U; ++u) a[u] = an[u];
+    for (int u = 0; u < U; ++u) tile(a, u, gi * U + u);
+#pragma unroll
+    for (int r = 0; r < RB; ++r)
+#pragma unroll
+      for (int u = 0; u < U; ++u) a[r][u] = an[r][u];
   }
   if (ngroups > 0) {
 #pragma unroll
-    for (int u = 0; u < U; ++u) tile(a[u], (ngroups - 1) * U + u);
+    for (int u = 0; u < U; ++u) tile(a, u, (ngroups - 1) * U + u);
   }
   for (int kt = ngroups * U; kt < KT; ++kt) {
-    const uint4 aw = ld_stream(wp + (size_t)kt * 64);
-    tile(aw, kt);
+#pragma unroll
+    for (int r = 0; r < RB; ++r) a[r][0] = ld_stream(wp[r] + (size_t)kt * 64);
+    tile(a, 0, kt);
   }
-  // epilogue: lane holds rows 4g+j of its row block for token lane%16 of every block of token rows
+  // epilogue: lane holds rows 4g+j of its row block for token lane%16 of every block of token rows;
+  // each wave works on an LDS patch of its own, so no barrier is needed below
   float (*fin)[16] = reinterpret_cast<float (*)[16]>(reinterpret_cast<float*>(bs) + wave * 256);
   const int g = lane >> 4, token = lane & 15;
-  if (!rowok) return;   // no barrier below: each wave works on its own LDS patch
 #pragma unroll
-  for (int c = 0; c < HG_CB; ++c) {
-    if (c < ncb) {
-      const int rowbase = (cb0 + c) * 16;
-      const int mvalid = min(16, p.M - rowbase);
-      const float sc = (p.rowscale && token < mvalid) ? p.rowscale[rowbase + token] : 1.0f;
+  for (int r = 0; r < RB; ++r) {
+    const int nb = nb0 + r;
+    if (nb >= NB) break;
 #pragma unroll
-      for (int j = 0; j < 4; ++j) fin[token][4 * g + j] = acc[c][j] * sc;
-      __builtin_amdgcn_wave_barrier();
-      epilogue<EPI, true, true>(p, nb, fin, mvalid, rowbase,
-                                p.XsOut ? p.XsOut + (size_t)(cb0 + c) * p.xs_out_cb_stride : nullptr,
-                                p.ssq_out ? p.ssq_out + (size_t)rowbase * p.NB : nullptr);
-      __builtin_amdgcn_wave_barrier();
+    for (int c = 0; c < CBW; ++c) {
+      if (c < ncb) {
+        const int rowbase = (cb0 + c) * 16;
+        const int mvalid = min(16, p.M - rowbase);
+        const float sc = (p.rowscale && token < mvalid) ? p.rowscale[rowbase + token] : 1.0f;
+#pragma unroll
+        for (int j = 0; j < 4; ++j) fin[token][4 * g + j] = acc[r][c][j] * sc;
+        __builtin_amdgcn_wave_barrier();
+        epilogue<EPI, true, true>(p, nb, fin, mvalid, rowbase,
+                                  p.XsOut ? p.XsOut + (size_t)(cb0 + c) * p.xs_out_cb_stride : nullptr,
+                                  p.ssq_out ? p.ssq_out + (size_t)rowbase * p.NB : nullptr);
+        __builtin_amdgcn_wave_barrier();
+      }
     }
   }
 }
@@ -1338,33 +1364,38 @@ hipError_t launch_gemm_mfma(const GemmP& p, int epi, int waves, int col_blocks, 
   return hipGetLastError();
 }
 
+namespace {
+template <int EPI, int RB, int CBW>
+hipError_t launch_wide_inst(const GemmP& p, hipStream_t s) {
+  const int CB = (p.M + 15) / 16, NS = (p.NB + HG_W * RB - 1) / (HG_W * RB);
+  const size_t lds = (size_t)2 * CBW * 128 * sizeof(uint4);
+  static bool raised = false;
+  if (!raised) {
+    hipError_t e = hipFuncSetAttribute((const void*)gemm_wide_k<EPI, RB, CBW>,
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+    if (e != hipSuccess) return e;
+    raised = true;
+  }
+  dim3 grid(NS, (CB + CBW - 1) / CBW), block(512);
+  if (p.ev_start && p.ev_stop)
+    hipExtLaunchKernelGGL((gemm_wide_k<EPI, RB, CBW>), grid, block, (uint32_t)lds, s, p.ev_start, p.ev_stop, 0, p);
+  else
+    hipLaunchKernelGGL((gemm_wide_k<EPI, RB, CBW>), grid, block, lds, s, p);
+  return hipGetLastError();
+}
+}  // namespace
+
 hipError_t launch_gemm_wide(const GemmP& p, int epi, hipStream_t s) {
   if (p.NB <= 0 || p.KT <= 0 || p.M < 1 || p.wdtype != 1 || !p.Xs) return hipErrorInvalidValue;
-  const int CB = (p.M + 15) / 16, NS = (p.NB + HG_W - 1) / HG_W;
-  const size_t lds = (size_t)2 * HG_CB * 128 * sizeof(uint4);
-  static bool raised[5] = {false, false, false, false, false};
-  dim3 grid(NS, (CB + HG_CB - 1) / HG_CB), block(512);
-  const bool timed = p.ev_start && p.ev_stop;
-#define DEL_WIDE_CASE(E)                                                                                              \
-  case E: {                                                                                                           \
-    if (!raised[E]) {                                                                                                 \
-      hipError_t e = hipFuncSetAttribute((const void*)gemm_wide_k<E>, hipFuncAttributeMaxDynamicSharedMemorySize,     \
-                                         (int)lds);                                                                   \
-      if (e != hipSuccess) return e;                                                                                  \
-      raised[E] = true;                                                                                               \
-    }                                                                                                                 \
-    if (timed) hipExtLaunchKernelGGL((gemm_wide_k<E>), grid, block, (uint32_t)lds, s, p.ev_start, p.ev_stop, 0, p);   \
-    else hipLaunchKernelGGL((gemm_wide_k<E>), grid, block, lds, s, p);                                                \
-    break;                                                                                                            \
-  }
+  // matrices with many row blocks: two per wave, 256 token rows per work-group; the square ones
+  // (output and down projection): one per wave and 128 token rows, which doubles their work-groups
+  const bool tall = p.NB >= 512;
   switch (epi) {
-    DEL_WIDE_CASE(EPI_RESID)
-    DEL_WIDE_CASE(EPI_QKV)
-    DEL_WIDE_CASE(EPI_SWIGLU)
+    case EPI_RESID: return tall ? launch_wide_inst<EPI_RESID, 2, 16>(p, s) : launch_wide_inst<EPI_RESID, 1, 8>(p, s);
+    case EPI_QKV: return tall ? launch_wide_inst<EPI_QKV, 2, 16>(p, s) : launch_wide_inst<EPI_QKV, 1, 8>(p, s);
+    case EPI_SWIGLU: return tall ? launch_wide_inst<EPI_SWIGLU, 2, 16>(p, s) : launch_wide_inst<EPI_SWIGLU, 1, 8>(p, s);
     default: return hipErrorInvalidValue;
   }
-#undef DEL_WIDE_CASE
-  return hipGetLastError();
 }
 
 hipError_t launch_rowscale(const float* ssq, int nb, int M, int K, float eps, float* rowscale, hipStream_t s) {
