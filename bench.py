@@ -204,6 +204,33 @@ def main():
     run_sampled(8, 40000, fixed=(1, 0))
     torch.cuda.synchronize()
     smp_vanilla_tps = 8 / (time.perf_counter() - t0)
+    # ---- the prefill on its own (not part of the metric): steady-state time, and the wide GEMMs'
+    #      matrix-core rate from their own start/stop timestamps
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    ctx.prefill(prompt)
+    torch.cuda.synchronize()
+    prefill_steady_s = time.perf_counter() - t0
+    ctx.profile_enable(True)
+    ctx.prefill(prompt)
+    pprof = [e for e in ctx.profile_read() if e["kernel"].startswith("gemm_wide_k")]
+    ctx.profile_enable(False)
+    prefill_info = {"tokens": len(prompt), "ms": round(1e3 * prefill_steady_s, 2),
+                    "tokens_per_s": round(len(prompt) / prefill_steady_s, 1)}
+    if pprof:
+        # multiply-adds of a launch = weight elements x token rows; the activations enter as a bf16
+        # high and low part, so the matrix cores execute twice that
+        pw = max(pprof, key=lambda e: e["total_ms"])
+        macs = sum(e["weight_bytes"] / 2 * e["rows"] * e["launches"] for e in pprof)
+        ms = sum(e["total_ms"] for e in pprof)
+        pw_tf = 2 * 2 * (pw["weight_bytes"] / 2) * pw["rows"] * pw["launches"] / (pw["total_ms"] * 1e-3) / 1e12
+        prefill_info["mfma"] = {"bound": "mfma", "kernel": pw["kernel"], "rows": pw["rows"],
+                                "achieved": round(pw_tf, 1), "peak": 2500.0, "unit": "TFLOP/s",
+                                "frac": round(pw_tf / 2500.0, 4),
+                                "all_wide_gemms_TFLOPs": round(4 * macs / (ms * 1e-3) / 1e12, 1),
+                                "all_wide_gemms_ms": round(ms, 2),
+                                "note": "bf16 matrix instructions executed (activations as high + low part: "
+                                        "twice the model's multiply-adds)"}
     stream_gbs = ctx.stream_read_gbps(min(4 << 30, cfg.layer_weight_bytes() * cfg.n_layers), 10)
     copy_gbs = ctx.stream_copy_gbps(1 << 30, 5)     # also the known-size kernel for counter calibration
 
@@ -247,6 +274,7 @@ def main():
             "stream_read_GBs": round(stream_gbs, 1), "stream_copy_GBs": round(copy_gbs, 1),
             "paper_speedup_over_autoregressive": "2.16-2.62x on A100-40G / 2xH100-PCIe (context only)",
         },
+        "prefill": prefill_info,
         "kernels": {n: {"launches": k["launches"], "avg_us": round(1e3 * k["total_ms"] / k["launches"], 2),
                         "GBs": round(k["bytes"] / (k["total_ms"] * 1e-3) / 1e9, 1)}
                     for n, k in sorted(by_kernel.items())},

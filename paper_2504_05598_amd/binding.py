@@ -391,7 +391,7 @@ class DelContext:
                 kernel = (f"gemm_valu_k<8,{e.rows},{e.epilogue}>" if e.flavour == 0
                           else f"gemm_mfma_k<{e.epilogue}>" if e.flavour == 1
                           else f"gemm_wide_k<{e.epilogue}>" if e.flavour == 3 else "head_gemm_k")
-                out.append({"kernel": kernel, "flavour": ("valu", "mfma", "mfma")[e.flavour],
+                out.append({"kernel": kernel, "flavour": ("valu", "mfma", "mfma", "mfma")[e.flavour],
                             "epilogue": names[e.epilogue], "rows": e.rows, "launches": e.launches,
                             "total_ms": e.total_ms, "avg_us": 1e3 * e.total_ms / e.launches,
                             "weight_bytes": e.weight_bytes})
