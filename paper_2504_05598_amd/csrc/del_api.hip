@@ -98,6 +98,8 @@ struct del_ctx {
   int prows = 0;    // token rows of a wide prefill pass (0: prefill runs in 16-row passes)
   int hrows = 0;    // rows per layer of the hidden buffer and of the per-row work buffers
   float* rowscale_w = nullptr;   // [hrows] RMS scales of a wide pass
+  char* vct = nullptr; int TcapT = 0; size_t vct_layer_bytes = 0;   // feature-major copy of the values for the
+                                                                     // prefill's matrix-core attention (0: off)
   // device memory
   char* arena = nullptr;
   size_t off_qkv = 0, off_o = 0, off_gu = 0, off_dn = 0, layer_stride = 0, arena_bytes = 0;
@@ -415,6 +417,8 @@ del_status run_layer_wide(del_ctx* ctx, int l, int m, bool chained) {
   p.n_q = ctx->nq; p.n_kv = ctx->nkv; p.hd = ctx->hd; p.Tcap = ctx->Tcap;
   p.state = ctx->state; p.row_off = 0; p.rope = ctx->rope;
   void* Kc = p.Kc; void* Vc = p.Vc;
+  void* VcT = ctx->vct ? ctx->vct + (size_t)li * ctx->vct_layer_bytes : nullptr;
+  p.VcT = VcT; p.TcapT = ctx->TcapT;
   if (chained)
     HIPCHK(launch_rowscale(ctx->ssq_h, ctx->NBd, m, ctx->d, ctx->cfg.rms_eps, ctx->rowscale_w, s));
   else
@@ -431,11 +435,16 @@ del_status run_layer_wide(del_ctx* ctx, int l, int m, bool chained) {
   a.PM = ctx->PM; a.PL = ctx->PL; a.PA = ctx->PA; a.nch_max = WIDE_S; a.ct = ctx->attn_ct;
   a.O = ctx->attn; a.ldo = ctx->qpad;
   a.XsOut = ctx->xs_attn; a.xs_cb_stride = (long long)ctx->KTq * 1024;
-  const int groups = ctx->nkv * ceil_div(m, 8);
-  const int S = std::max(1, std::min(WIDE_S, ceil_div(512, groups)));
-  HIPCHK(launch_attention_decode(a, S, s, 8));
-  a.nsplit = S;
-  HIPCHK(launch_attention_merge(a, s));
+  if (VcT) {   // on the matrix cores, straight to the output rows and their tiles
+    a.VcT = VcT; a.TcapT = ctx->TcapT;
+    HIPCHK(launch_attention_flash(a, s));
+  } else {
+    const int groups = ctx->nkv * ceil_div(m, 8);
+    const int S = std::max(1, std::min(WIDE_S, ceil_div(512, groups)));
+    HIPCHK(launch_attention_decode(a, S, s, 8));
+    a.nsplit = S;
+    HIPCHK(launch_attention_merge(a, s));
+  }
   // 3. output projection + residual; leaves the FFN's input tiles
   p = base_gemm(ctx);
   p.Wt = base + ctx->off_o; p.NB = ctx->NBd; p.KT = ctx->KTq; p.N = ctx->d; p.K = ctx->qdim;
@@ -516,7 +525,7 @@ void free_all(del_ctx* c) {
                   c->rope, c->hid, c->q, c->attn, c->act, c->xs_layer, c->xs_shadow, c->rowscale, c->xs_h, c->xs_attn,
                   c->xs_h1, c->xs_act, c->ssq_h, c->ssq_h1, c->PM, c->PL,
                   c->PA, c->pval, c->pidx, c->psum, c->conf_dev, c->state, c->draft_ids, c->shadow_ids, c->result, c->ids_dev,
-                  c->logits_dbg, c->sink, c->stage, c->slog, c->swf, c->srows, c->unif_dev, c->rowscale_w};
+                  c->logits_dbg, c->sink, c->stage, c->slog, c->swf, c->srows, c->unif_dev, c->rowscale_w, c->vct};
   for (void* p : ptrs)
     if (p) (void)hipFree(p);
   if (c->result_host) (void)hipHostFree(c->result_host);
@@ -735,6 +744,13 @@ del_status del_create(const del_config* cfg, void* hip_stream, del_ctx** out) {
     CK(dmalloc(&ctx->ssq_h, CBmax * 16 * ctx->NBd * 4));
     CK(dmalloc(&ctx->ssq_h1, CBmax * 16 * ctx->NBd * 4));
     CK(dmalloc(&ctx->rowscale_w, CBmax * 16 * 4));
+    const char* fl = getenv("DEL_PREFILL_FLASH");
+    if (ctx->prows > 0 && (ctx->hd == 64 || ctx->hd == 128) && !(fl && atoi(fl) == 0)) {
+      ctx->TcapT = ceil_div(ctx->Tcap, 32) * 32;
+      ctx->vct_layer_bytes = (size_t)ctx->nkv * ctx->hd * ctx->TcapT * 2;
+      CK(dmalloc(&ctx->vct, ctx->vct_layer_bytes * ctx->L));
+      CK(hipMemsetAsync(ctx->vct, 0, ctx->vct_layer_bytes * ctx->L, ctx->stream));
+    }
   }
   const size_t xs_sh = (size_t)ceil_div(Rmax, 16) * ctx->KTd * 2048;
   CK(dmalloc(&ctx->xs_shadow, xs_sh));
@@ -873,7 +889,8 @@ del_status del_prefill(del_ctx* ctx, const int32_t* prompt, int32_t n_prompt, in
   int start = 0;
   while (start < P) {
     const int mc = (start == 0 && P % CH != 0) ? P % CH : CH;
-    const bool widep = ctx->prows > 0 && mc > 16;
+    // with the feature-major value copy every pass must keep it filled: all passes take the wide path
+    const bool widep = ctx->prows > 0 && (mc > 16 || ctx->vct);
     HIPCHK(launch_embed(ctx->embed_t, ctx->wd, ctx->KTd, ctx->V, ctx->ids_dev + start, mc, ctx->hid_row(0, 0),
                         ctx->dpad, ctx->d, ctx->stream));
     for (int l = 1; l <= L; ++l) {

@@ -45,6 +45,7 @@ struct GemmP {
   const float* R; int ldr;      // RESID: residual source
   float* Q; int ldq;            // QKV: rotated queries [M][n_q*hd]
   void* Kc; void* Vc;           // QKV: this layer's caches [n_kv][Tcap][hd] (weight dtype)
+  void* VcT; int TcapT;         // QKV, optional: the values also feature-major, [n_kv][hd][TcapT] (bf16)
   int n_q, n_kv, hd, Tcap;
   const int* state;             // state[0] = KV length T
   int row_off;                  // position of row mi is state[0] + row_off + mi
@@ -76,6 +77,7 @@ struct GemmP {
 struct AttnP {
   const float* Q; int ldq;      // [m][n_q*hd]
   const void* Kc; const void* Vc;  // this layer's caches
+  const void* VcT; int TcapT;      // matrix-core kernel: the values feature-major, [n_kv][hd][TcapT]
   int kvdtype;
   int n_q, n_kv, hd, Tcap, m;
   const int* state; int row_off;
@@ -109,6 +111,9 @@ hipError_t launch_attention(const AttnP& p, hipStream_t s);
 // the launcher rounds it down to what the shape's instantiation offers.
 hipError_t launch_attention_decode(const AttnP& p, int S, hipStream_t s, int rows_per_wg = 1);
 hipError_t launch_attention_merge(const AttnP& p, hipStream_t s);
+// Causal attention of p.m token rows on the matrix cores (bf16 caches, head_dim 64 or 128); writes O and
+// XsOut directly (no partials).  Needs VcT.
+hipError_t launch_attention_flash(const AttnP& p, hipStream_t s);
 bool attention_decode_supported(int kvdtype, int hd, int G);
 hipError_t launch_embed(const void* Et, int wdtype, int KT, int vocab, const int* ids, int m,
                         float* out, int ld, int d_model, hipStream_t s);

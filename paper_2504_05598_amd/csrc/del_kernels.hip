@@ -131,6 +131,8 @@ __device__ __forceinline__ void epilogue(const GemmP& p, int nb, float (*fin)[16
       } else {
         const size_t base = ((size_t)(hh - p.n_q - p.n_kv) * p.Tcap + pos) * hd;
         kv_store<BF16KV>(p.Vc, base + s0 + r, fin[mi][r]);
+        if (BF16KV && p.VcT)
+          ((uint16_t*)p.VcT)[((size_t)(hh - p.n_q - p.n_kv) * hd + s0 + r) * p.TcapT + pos] = f32_to_bf16_rne(fin[mi][r]);
       }
     }
   } else if (EPI == EPI_SWIGLU) {
@@ -950,7 +952,7 @@ __global__ void __launch_bounds__(512) attn_decode_k(AttnP p) {
   constexpr int LPR = HD / EPL;           // lanes per cache row
   constexpr int RPL = 64 / LPR;           // cache rows per wave-wide load
   constexpr int UL = 4;                   // loads in flight per wave, matrix and pipeline stage
-  constexpr int NWV = 8;
+  constexpr int NWV = RW > 1 ? 4 : 8;           // waves per work-group (launched with 64 * NWV threads)
   __shared__ float sm[NWV][NQ], sl[NWV][NQ];
   __shared__ float sa[NWV][NQ][HD];
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
@@ -1058,7 +1060,7 @@ __global__ void __launch_bounds__(512) attn_decode_k(AttnP p) {
   }
   __syncthreads();
   // ... then the waves, in a fixed order; one partial per (query row, split)
-  for (int i = tid; i < NQ * HD; i += 512) {
+  for (int i = tid; i < NQ * HD; i += 64 * NWV) {
     const int g = i / HD, d = i - g * HD;
     if (g / G >= nrow) continue;
     float M = -INFINITY;
@@ -1074,6 +1076,144 @@ __global__ void __launch_bounds__(512) attn_decode_k(AttnP p) {
     const size_t prow = ((size_t)(mi0 + g / G) * p.n_q + kvh * G + g % G) * p.nch_max + split;
     if (d == 0) { p.PM[prow] = M; p.PL[prow] = L; }
     p.PA[prow * HD + d] = A;
+  }
+}
+
+// ---------------------------------------------------------------------------------------
+// Causal attention of many token rows on the matrix cores (prefill).  One wave = 16 consecutive
+// token rows of one query head; a work-group = 4 such waves.  Per tile of 32 cache rows:
+//   S^T[32 rows][16 queries] = K[32][hd] * Q^T      (A = cache rows as stored, B = queries as
+//                                                    bf16 high + low parts, kept in registers)
+//   online soft-max per query (a lane holds 8 rows of one query; two cross-lane steps)
+//   O^T[hd][16 queries] += V^T[hd][32 rows] * P     (A = the feature-major copy of the values,
+//                                                    B = the probabilities, high + low parts)
+// The A operand of the first product takes cache row t0 + 8*(i/4) + i%4 (+4 for the second block
+// of 16) as its row i, so that the 8 scores a lane ends up with are 8 consecutive cache rows:
+// exactly the B operand slice it must supply to the second product.  Nothing passes through LDS.
+// ---------------------------------------------------------------------------------------
+__device__ __forceinline__ void split8(const float* v, uint4& hi, uint4& lo) {
+  uint32_t h[4], l[4];
+#pragma unroll
+  for (int e = 0; e < 8; e += 2) {
+    const uint16_t h0 = f32_to_bf16_rne(v[e]), h1 = f32_to_bf16_rne(v[e + 1]);
+    const uint16_t l0 = f32_to_bf16_rne(v[e] - bf16_bits_to_f32(h0));
+    const uint16_t l1 = f32_to_bf16_rne(v[e + 1] - bf16_bits_to_f32(h1));
+    h[e >> 1] = (uint32_t)h0 | ((uint32_t)h1 << 16);
+    l[e >> 1] = (uint32_t)l0 | ((uint32_t)l1 << 16);
+  }
+  hi = make_uint4(h[0], h[1], h[2], h[3]);
+  lo = make_uint4(l[0], l[1], l[2], l[3]);
+}
+
+template <int HD>
+__global__ void __launch_bounds__(256) attn_flash_k(AttnP p) {
+  constexpr int KT = HD / 32, DT = HD / 16;
+  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63, g = lane >> 4, qi = lane & 15;
+  const int h = blockIdx.y, kvh = h / (p.n_q / p.n_kv);
+  const int r0 = blockIdx.x * 64 + wave * 16;
+  if (r0 >= p.m) return;                       // wave-uniform; the kernel has no barriers
+  const int nrow = min(16, p.m - r0);
+  const int T0 = p.state[0] + p.row_off;       // cache position of token row 0
+  const int pos = T0 + r0 + qi;                // this lane's query attends cache rows <= pos
+  const int t_end = T0 + r0 + nrow;            // cache rows this wave needs: [0, t_end)
+  // queries: row r0 + qi (a ragged last block re-reads its last row; those results are dropped)
+  uint4 qh[KT], ql[KT];
+  {
+    const float scale = 1.0f / sqrtf((float)HD);
+    const float* qp = p.Q + (size_t)(r0 + min(qi, nrow - 1)) * p.ldq + (size_t)h * HD + 8 * g;
+#pragma unroll
+    for (int kt = 0; kt < KT; ++kt) {
+      const float4 a = *(const float4*)(qp + 32 * kt), b = *(const float4*)(qp + 32 * kt + 4);
+      const float v[8] = {a.x * scale, a.y * scale, a.z * scale, a.w * scale,
+                          b.x * scale, b.y * scale, b.z * scale, b.w * scale};
+      split8(v, qh[kt], ql[kt]);
+    }
+  }
+  floatx4 o[DT];
+#pragma unroll
+  for (int dt = 0; dt < DT; ++dt) o[dt] = (floatx4){0.f, 0.f, 0.f, 0.f};
+  float mrun = -INFINITY, lrun = 0.f;
+  const uint16_t* Kb = (const uint16_t*)p.Kc + (size_t)kvh * p.Tcap * HD + 8 * g;
+  const uint16_t* Vt = (const uint16_t*)p.VcT + ((size_t)kvh * HD + qi) * p.TcapT + 8 * g;
+  const int rho = 8 * (qi >> 2) + (qi & 3);
+  for (int t0 = 0; t0 < t_end; t0 += 32) {
+    floatx4 s0 = {0.f, 0.f, 0.f, 0.f}, s1 = {0.f, 0.f, 0.f, 0.f};
+    // rows past the wave's last one are read from that last row and masked below
+    const uint16_t* k0 = Kb + (size_t)min(t0 + rho, t_end - 1) * HD;
+    const uint16_t* k1 = Kb + (size_t)min(t0 + rho + 4, t_end - 1) * HD;
+    uint4 a0[KT], a1[KT], av[DT];
+#pragma unroll
+    for (int kt = 0; kt < KT; ++kt) {
+      a0[kt] = *(const uint4*)(k0 + 32 * kt);
+      a1[kt] = *(const uint4*)(k1 + 32 * kt);
+    }
+#pragma unroll
+    for (int dt = 0; dt < DT; ++dt) av[dt] = *(const uint4*)(Vt + (size_t)(16 * dt) * p.TcapT + t0);
+#pragma unroll
+    for (int kt = 0; kt < KT; ++kt) {
+      const bf16x8 x0 = __builtin_bit_cast(bf16x8, a0[kt]), x1 = __builtin_bit_cast(bf16x8, a1[kt]);
+      const bf16x8 bh = __builtin_bit_cast(bf16x8, qh[kt]), bl = __builtin_bit_cast(bf16x8, ql[kt]);
+      s0 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(x0, bh, s0, 0, 0, 0);
+      s1 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(x1, bh, s1, 0, 0, 0);
+      s0 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(x0, bl, s0, 0, 0, 0);
+      s1 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(x1, bl, s1, 0, 0, 0);
+    }
+    // this lane: scores of cache rows t0 + 8g + e, e = 0..7, for query qi
+    float sv[8] = {s0[0], s0[1], s0[2], s0[3], s1[0], s1[1], s1[2], s1[3]};
+    float mx = -INFINITY;
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+      if (t0 + 8 * g + e > pos) sv[e] = -INFINITY;
+      mx = fmaxf(mx, sv[e]);
+    }
+    mx = fmaxf(mx, __shfl_xor(mx, 16));
+    mx = fmaxf(mx, __shfl_xor(mx, 32));
+    const float mnew = fmaxf(mrun, mx);          // finite from the first tile on (row 0 is never masked)
+    const float c = expf(mrun - mnew);
+    float pv[8], ls = 0.f;
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+      pv[e] = expf(sv[e] - mnew);
+      ls += pv[e];
+    }
+    ls += __shfl_xor(ls, 16);
+    ls += __shfl_xor(ls, 32);
+    lrun = lrun * c + ls;
+    mrun = mnew;
+    uint4 ph, pl;
+    split8(pv, ph, pl);
+    const bf16x8 bh = __builtin_bit_cast(bf16x8, ph), bl = __builtin_bit_cast(bf16x8, pl);
+#pragma unroll
+    for (int dt = 0; dt < DT; ++dt) {
+#pragma unroll
+      for (int j = 0; j < 4; ++j) o[dt][j] *= c;
+      const bf16x8 x = __builtin_bit_cast(bf16x8, av[dt]);
+      o[dt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(x, bh, o[dt], 0, 0, 0);
+      o[dt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(x, bl, o[dt], 0, 0, 0);
+    }
+  }
+  if (qi >= nrow) return;
+  // this lane: features 16*dt + 4g + j of head h for token row r0 + qi
+  const float inv = 1.0f / lrun;
+  const int row = r0 + qi;
+  float* orow = p.O + (size_t)row * p.ldo + (size_t)h * HD + 4 * g;
+  uint16_t* xs = p.XsOut ? p.XsOut + (size_t)(row >> 4) * p.xs_cb_stride : nullptr;
+#pragma unroll
+  for (int dt = 0; dt < DT; ++dt) {
+    const float v[4] = {o[dt][0] * inv, o[dt][1] * inv, o[dt][2] * inv, o[dt][3] * inv};
+    *(float4*)(orow + 16 * dt) = make_float4(v[0], v[1], v[2], v[3]);
+    if (xs) {
+      const int k = h * HD + 16 * dt + 4 * g;     // first of 4 consecutive features; k % 4 == 0
+      uint16_t hi[4], lo[4];
+#pragma unroll
+      for (int j = 0; j < 4; ++j) {
+        hi[j] = f32_to_bf16_rne(v[j]);
+        lo[j] = f32_to_bf16_rne(v[j] - bf16_bits_to_f32(hi[j]));
+      }
+      uint16_t* dst = xs + (size_t)(k >> 5) * 1024 + (((k & 31) >> 3) * 16 + (row & 15)) * 8 + (k & 7);
+      *(uint2*)dst = make_uint2((uint32_t)hi[0] | ((uint32_t)hi[1] << 16), (uint32_t)hi[2] | ((uint32_t)hi[3] << 16));
+      *(uint2*)(dst + 512) = make_uint2((uint32_t)lo[0] | ((uint32_t)lo[1] << 16), (uint32_t)lo[2] | ((uint32_t)lo[3] << 16));
+    }
   }
 }
 
@@ -1448,7 +1588,7 @@ hipError_t launch_attention_decode(const AttnP& p, int S, hipStream_t s, int row
   const bool many = rows_per_wg > 1;
   // one work-group per (split, kv head, group of token rows); G * rows per group <= 8 queries
 #define DEL_ATT(KVT, HD, GG, RW)                                                                    \
-  hipLaunchKernelGGL((attn_decode_k<KVT, HD, GG, RW>), dim3(S, p.n_kv, (p.m + RW - 1) / RW), dim3(512), 0, s, p)
+  hipLaunchKernelGGL((attn_decode_k<KVT, HD, GG, RW>), dim3(S, p.n_kv, (p.m + RW - 1) / RW), dim3(RW > 1 ? 256 : 512), 0, s, p)
   if (p.kvdtype == 1 && p.hd == 128 && G == 1) { if (many) DEL_ATT(uint16_t, 128, 1, 8); else DEL_ATT(uint16_t, 128, 1, 1); }
   else if (p.kvdtype == 1 && p.hd == 64 && G == 4) { if (many) DEL_ATT(uint16_t, 64, 4, 2); else DEL_ATT(uint16_t, 64, 4, 1); }
   else if (p.kvdtype == 1 && p.hd == 128 && G == 8) DEL_ATT(uint16_t, 128, 8, 1);
@@ -1461,6 +1601,16 @@ hipError_t launch_attention_decode(const AttnP& p, int S, hipStream_t s, int row
 bool attention_decode_supported(int kvdtype, int hd, int G) {
   return (kvdtype == 1 && hd == 128 && (G == 1 || G == 8)) || (kvdtype == 1 && hd == 64 && G == 4) ||
          (kvdtype == 0 && hd == 64 && G == 1);
+}
+
+hipError_t launch_attention_flash(const AttnP& p, hipStream_t s) {
+  if (p.m < 1 || p.kvdtype != 1 || !p.VcT || p.TcapT % 32 != 0 || p.TcapT < p.Tcap || p.n_q % p.n_kv != 0 ||
+      (p.hd != 64 && p.hd != 128))
+    return hipErrorInvalidValue;
+  dim3 grid((p.m + 63) / 64, p.n_q), block(256);
+  if (p.hd == 128) hipLaunchKernelGGL((attn_flash_k<128>), grid, block, 0, s, p);
+  else hipLaunchKernelGGL((attn_flash_k<64>), grid, block, 0, s, p);
+  return hipGetLastError();
 }
 
 // Merge p.nsplit partials per row (written by the decode kernel) into O (and XsOut).
