@@ -258,3 +258,20 @@ def test_wide_prefill_passes_match_the_oracle_and_the_short_passes(name, plen, r
     _check_report(rep, f"{name} P={plen} wide rows={rows}")
     wide.close()
     short.close()
+
+
+def test_statistics_seeded_from_every_prompt_position():
+    """prefill_window = prompt length: the statistics' pseudo-round covers all positions (several
+    groups of 16 shadow rows inside one wide pass)."""
+    import dataclasses
+    from gpu_harness import gpu_context, lockstep
+    from oracle.del_oracle import Oracle, load_weights
+    base = get_config("mini_gqa")
+    prompt = gen_prompt(base, length=77).tolist()
+    cfg = dataclasses.replace(base, prefill_window=77, prompt_len=77)
+    ctx, _ = gpu_context(cfg)
+    oracle = Oracle(cfg, load_weights(cfg))
+    rep = lockstep(cfg, oracle, ctx, prompt, 10)
+    assert ctx.stats()["rounds"] > 0
+    _check_report(rep, "mini_gqa window=77")
+    ctx.close()
