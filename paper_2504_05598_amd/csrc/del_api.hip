@@ -137,7 +137,7 @@ struct del_ctx {
   std::vector<float> last_conf, last_draft_conf;   // like last_shadow / last_draft
   int last_stopped = 0;
   float t_draft = 0, t_verify = 0, t_shadow = 0;
-  int target_waves = 4096;
+  int target_waves = 3072;
   // Optional (DEL_GRAPHS=1): the segments of a round are captured once per (kind, E, gamma) into HIP
   // graphs and replayed; positions and token ids live in device memory, so a graph depends on
   // nothing else.  Off by default: on this GPU the kernels of a round already run back to back
