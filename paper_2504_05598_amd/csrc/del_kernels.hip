@@ -613,122 +613,97 @@ __global__ void __launch_bounds__(512) head_gemm_k(const uint4* __restrict__ Wt,
 }
 
 // ---------------------------------------------------------------------------------------
-// Wide GEMM for passes over many token rows (prefill): the loop of the shadow-head GEMM (a slab
-// of 8 row blocks per work-group, one per wave, streamed once; up to 16 blocks of 16 token rows
-// whose split tiles are staged in LDS and shared by the waves) with the layer epilogues: every
-// wave hands its 16x16 tiles through a 1 KiB LDS patch of its own to the epilogue, block of
-// token rows by block of token rows.
+// Wide GEMM for passes over many token rows (prefill).  A work-group takes RBW row blocks of the
+// matrix times 8 * CPW blocks of 16 token rows.  The weight tiles of a k tile (RBW KiB) are staged
+// in LDS, double-buffered, and shared by the 8 waves; every wave owns CPW blocks of token rows,
+// whose hi/lo activation tiles it reads straight into registers, so that one weight tile fetched
+// from LDS feeds 2 * CPW matrix instructions.  Work-groups that share a slab of the matrix are
+// given consecutive slots on one XCD (the slab then comes from that XCD's L2 after its first
+// read).  Every wave hands its 16x16 results through a 1 KiB LDS patch of its own to the layer
+// epilogues, block of token rows by block of token rows.
 // ---------------------------------------------------------------------------------------
-// RB row blocks per wave (a staged activation tile then feeds RB matrix instructions, which halves
-// the LDS traffic per instruction at RB = 2), CBW blocks of 16 token rows per work-group (fewer for
-// the matrices with few rows, so that the launch still fills the chip).
-template <int EPI, int RB, int CBW>
-__global__ void __launch_bounds__(512) gemm_wide_k(GemmP p) {
-  extern __shared__ __align__(16) uint4 bs[];   // [2][CBW * 128]
-  constexpr int U = 4;
-  constexpr int BL = CBW * 128 / 512;           // 16-byte pieces of the activation tiles per thread
-  static_assert(CBW * 128 % 512 == 0 && BL >= 1, "CBW must be a multiple of 4");
+template <int EPI, int RBW, int CPW>
+__global__ void __launch_bounds__(512) gemm_wide_k(GemmP p, int NS, int NCG) {
+  extern __shared__ __align__(16) uint4 as[];   // [2][RBW * 64]; reused by the epilogue ([8 waves][256] floats)
+  constexpr int CBW = 8 * CPW;
+  constexpr int AL = RBW * 64 / 512;            // 16-byte pieces of the weight tiles per thread
+  static_assert(RBW * 64 % 512 == 0 && AL >= 1 && RBW * 64 * 2 * 16 >= 8 * 1024, "RBW must be a multiple of 8");
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
+  // slot -> (slab, group of token-row blocks): the NCG groups of a slab follow each other on one XCD
+  const int xcd = blockIdx.x & 7, local = blockIdx.x >> 3;
+  const int cg = local % NCG, slab = (local / NCG) * 8 + xcd;
+  if (slab >= NS) return;
   const int NB = p.NB, KT = p.KT;
   const int CB = (p.M + 15) >> 4;
-  const int slab = blockIdx.x, cb0 = blockIdx.y * CBW;
-  const int ncb = min(CBW, CB - cb0);
-  const int nb0 = (slab * HG_W + wave) * RB;
+  const int nb0 = slab * RBW, cb0 = cg * CBW + wave * CPW;
   const uint4* Wt = (const uint4*)p.Wt;
   const uint4* Xs = (const uint4*)p.Xs;
-  // loads are unconditional (clamped row block) so that the steady-state loop has no branches
-  // around memory operations; results of a row block beyond the last are dropped
-  const uint4* wp[RB];
+  floatx4 acc[RBW][CPW];
 #pragma unroll
-  for (int r = 0; r < RB; ++r) wp[r] = Wt + (size_t)min(nb0 + r, NB - 1) * KT * 64 + lane;
-  floatx4 acc[RB][CBW];
+  for (int r = 0; r < RBW; ++r)
 #pragma unroll
-  for (int r = 0; r < RB; ++r)
+    for (int c = 0; c < CPW; ++c) acc[r][c] = (floatx4){0.f, 0.f, 0.f, 0.f};
+  // addresses are clamped (row blocks past the matrix, token-row blocks past the pass) so that the
+  // loop has no branches around memory operations; such results are dropped in the epilogue
+  const uint4* wsrc[AL];
 #pragma unroll
-    for (int c = 0; c < CBW; ++c) acc[r][c] = (floatx4){0.f, 0.f, 0.f, 0.f};
-  uint4 br[BL], a[RB][U], an[RB][U];
-  auto loadB = [&](int kt) {
+  for (int j = 0; j < AL; ++j) {
+    const int idx = tid + 512 * j;
+    wsrc[j] = Wt + (size_t)min(nb0 + (idx >> 6), NB - 1) * KT * 64 + (idx & 63);
+  }
+  const uint4* xsrc[CPW];
 #pragma unroll
-    for (int j = 0; j < BL; ++j) {
-      const int idx = tid + 512 * j, cbi = idx >> 7;
-      br[j] = cbi < ncb ? Xs[((size_t)(cb0 + cbi) * KT + kt) * 128 + (idx & 127)] : make_uint4(0, 0, 0, 0);
-    }
-  };
-  auto storeB = [&](int buf) {
+  for (int c = 0; c < CPW; ++c) xsrc[c] = Xs + (size_t)min(cb0 + c, CB - 1) * KT * 128 + lane;
+  uint4 ar[AL], bh[CPW], bl[CPW], bhn[CPW], bln[CPW];
 #pragma unroll
-    for (int j = 0; j < BL; ++j) bs[buf * (CBW * 128) + tid + 512 * j] = br[j];
-  };
-  auto tile = [&](const uint4 (&aw)[RB][U], int u, int kt) {
-    const int cur = kt & 1;
-    loadB(min(kt + 1, KT - 1));
-    const uint4* bp = bs + cur * (CBW * 128) + lane;
+  for (int j = 0; j < AL; ++j) ar[j] = wsrc[j][0];
 #pragma unroll
-    for (int c = 0; c < CBW; ++c) {
-      if (c < ncb) {
-        const bf16x8 bh = __builtin_bit_cast(bf16x8, bp[c * 128]);
-        const bf16x8 bl = __builtin_bit_cast(bf16x8, bp[c * 128 + 64]);
+  for (int c = 0; c < CPW; ++c) { bh[c] = xsrc[c][0]; bl[c] = xsrc[c][64]; }
 #pragma unroll
-        for (int r = 0; r < RB; ++r) {
-          const bf16x8 av = __builtin_bit_cast(bf16x8, aw[r][u]);
-          acc[r][c] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(av, bh, acc[r][c], 0, 0, 0);
-          acc[r][c] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(av, bl, acc[r][c], 0, 0, 0);
-        }
+  for (int j = 0; j < AL; ++j) as[tid + 512 * j] = ar[j];
+  __syncthreads();
+  for (int kt = 0; kt < KT; ++kt) {
+    const int cur = kt & 1, nx = min(kt + 1, KT - 1);
+#pragma unroll
+    for (int j = 0; j < AL; ++j) ar[j] = wsrc[j][(size_t)nx * 64];
+#pragma unroll
+    for (int c = 0; c < CPW; ++c) { bhn[c] = xsrc[c][(size_t)nx * 128]; bln[c] = xsrc[c][(size_t)nx * 128 + 64]; }
+    const uint4* ap = as + cur * (RBW * 64) + lane;
+#pragma unroll
+    for (int r = 0; r < RBW; ++r) {
+      const bf16x8 av = __builtin_bit_cast(bf16x8, ap[r * 64]);
+#pragma unroll
+      for (int c = 0; c < CPW; ++c) {
+        acc[r][c] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(av, __builtin_bit_cast(bf16x8, bh[c]), acc[r][c], 0, 0, 0);
+        acc[r][c] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(av, __builtin_bit_cast(bf16x8, bl[c]), acc[r][c], 0, 0, 0);
       }
     }
-    storeB(cur ^ 1);
+#pragma unroll
+    for (int j = 0; j < AL; ++j) as[(cur ^ 1) * (RBW * 64) + tid + 512 * j] = ar[j];
+#pragma unroll
+    for (int c = 0; c < CPW; ++c) { bh[c] = bhn[c]; bl[c] = bln[c]; }
     __syncthreads();
-  };
-  const int ngroups = KT / U;
-  loadB(0);
-  if (ngroups > 0) {
-#pragma unroll
-    for (int r = 0; r < RB; ++r)
-#pragma unroll
-      for (int u = 0; u < U; ++u) a[r][u] = ld_stream(wp[r] + u * 64);
   }
-  storeB(0);
-  __syncthreads();
-  for (int gi = 0; gi + 1 < ngroups; ++gi) {
-#pragma unroll
-    for (int r = 0; r < RB; ++r)
-#pragma unroll
-      for (int u = 0; u < U; ++u) an[r][u] = ld_stream(wp[r] + (size_t)(gi + 1) * U * 64 + u * 64);
-#pragma unroll
-    for (int u = 0; u < U; ++u) tile(a, u, gi * U + u);
-#pragma unroll
-    for (int r = 0; r < RB; ++r)
-#pragma unroll
-      for (int u = 0; u < U; ++u) a[r][u] = an[r][u];
-  }
-  if (ngroups > 0) {
-#pragma unroll
-    for (int u = 0; u < U; ++u) tile(a, u, (ngroups - 1) * U + u);
-  }
-  for (int kt = ngroups * U; kt < KT; ++kt) {
-#pragma unroll
-    for (int r = 0; r < RB; ++r) a[r][0] = ld_stream(wp[r] + (size_t)kt * 64);
-    tile(a, 0, kt);
-  }
-  // epilogue: lane holds rows 4g+j of its row block for token lane%16 of every block of token rows;
-  // each wave works on an LDS patch of its own, so no barrier is needed below
-  float (*fin)[16] = reinterpret_cast<float (*)[16]>(reinterpret_cast<float*>(bs) + wave * 256);
+  // epilogue: lane holds rows 4g+j of a row block for token lane%16 of a block of token rows; each
+  // wave works on an LDS patch of its own, so no barrier is needed below
+  float (*fin)[16] = reinterpret_cast<float (*)[16]>(reinterpret_cast<float*>(as) + wave * 256);
   const int g = lane >> 4, token = lane & 15;
 #pragma unroll
-  for (int r = 0; r < RB; ++r) {
-    const int nb = nb0 + r;
-    if (nb >= NB) break;
+  for (int c = 0; c < CPW; ++c) {
+    if (cb0 + c >= CB) break;
+    const int rowbase = (cb0 + c) * 16;
+    const int mvalid = min(16, p.M - rowbase);
+    const float sc = (p.rowscale && token < mvalid) ? p.rowscale[rowbase + token] : 1.0f;
+    uint16_t* xs_out = p.XsOut ? p.XsOut + (size_t)(cb0 + c) * p.xs_out_cb_stride : nullptr;
+    float* ssq_out = p.ssq_out ? p.ssq_out + (size_t)rowbase * p.NB : nullptr;
 #pragma unroll
-    for (int c = 0; c < CBW; ++c) {
-      if (c < ncb) {
-        const int rowbase = (cb0 + c) * 16;
-        const int mvalid = min(16, p.M - rowbase);
-        const float sc = (p.rowscale && token < mvalid) ? p.rowscale[rowbase + token] : 1.0f;
+    for (int r = 0; r < RBW; ++r) {
+      const int nb = nb0 + r;
+      if (nb < NB) {
 #pragma unroll
         for (int j = 0; j < 4; ++j) fin[token][4 * g + j] = acc[r][c][j] * sc;
         __builtin_amdgcn_wave_barrier();
-        epilogue<EPI, true, true>(p, nb, fin, mvalid, rowbase,
-                                  p.XsOut ? p.XsOut + (size_t)(cb0 + c) * p.xs_out_cb_stride : nullptr,
-                                  p.ssq_out ? p.ssq_out + (size_t)rowbase * p.NB : nullptr);
+        epilogue<EPI, true, true>(p, nb, fin, mvalid, rowbase, xs_out, ssq_out);
         __builtin_amdgcn_wave_barrier();
       }
     }
@@ -1505,35 +1480,37 @@ hipError_t launch_gemm_mfma(const GemmP& p, int epi, int waves, int col_blocks, 
 }
 
 namespace {
-template <int EPI, int RB, int CBW>
+template <int EPI, int RBW, int CPW>
 hipError_t launch_wide_inst(const GemmP& p, hipStream_t s) {
-  const int CB = (p.M + 15) / 16, NS = (p.NB + HG_W * RB - 1) / (HG_W * RB);
-  const size_t lds = (size_t)2 * CBW * 128 * sizeof(uint4);
+  const int CB = (p.M + 15) / 16, NS = (p.NB + RBW - 1) / RBW, NCG = (CB + 8 * CPW - 1) / (8 * CPW);
+  const size_t lds = (size_t)2 * RBW * 64 * sizeof(uint4);
   static bool raised = false;
   if (!raised) {
-    hipError_t e = hipFuncSetAttribute((const void*)gemm_wide_k<EPI, RB, CBW>,
+    hipError_t e = hipFuncSetAttribute((const void*)gemm_wide_k<EPI, RBW, CPW>,
                                        hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
     if (e != hipSuccess) return e;
     raised = true;
   }
-  dim3 grid(NS, (CB + CBW - 1) / CBW), block(512);
+  dim3 grid((NS + 7) / 8 * 8 * NCG), block(512);
   if (p.ev_start && p.ev_stop)
-    hipExtLaunchKernelGGL((gemm_wide_k<EPI, RB, CBW>), grid, block, (uint32_t)lds, s, p.ev_start, p.ev_stop, 0, p);
+    hipExtLaunchKernelGGL((gemm_wide_k<EPI, RBW, CPW>), grid, block, (uint32_t)lds, s, p.ev_start, p.ev_stop, 0, p, NS,
+                          NCG);
   else
-    hipLaunchKernelGGL((gemm_wide_k<EPI, RB, CBW>), grid, block, lds, s, p);
+    hipLaunchKernelGGL((gemm_wide_k<EPI, RBW, CPW>), grid, block, lds, s, p, NS, NCG);
   return hipGetLastError();
 }
 }  // namespace
 
 hipError_t launch_gemm_wide(const GemmP& p, int epi, hipStream_t s) {
   if (p.NB <= 0 || p.KT <= 0 || p.M < 1 || p.wdtype != 1 || !p.Xs) return hipErrorInvalidValue;
-  // matrices with many row blocks: two per wave, 256 token rows per work-group; the square ones
-  // (output and down projection): one per wave and 128 token rows, which doubles their work-groups
-  const bool tall = p.NB >= 512;
+  // a work-group's tile: 8 row blocks x 256 token rows; x 128 for the matrices with few rows (output and
+  // down projection), which doubles their work-groups.  (16 row blocks x 256 rows halves the activation
+  // traffic but leaves one work-group per CU and measured slower.)
+  const bool small = p.NB < 512;
   switch (epi) {
-    case EPI_RESID: return tall ? launch_wide_inst<EPI_RESID, 2, 16>(p, s) : launch_wide_inst<EPI_RESID, 1, 8>(p, s);
-    case EPI_QKV: return tall ? launch_wide_inst<EPI_QKV, 2, 16>(p, s) : launch_wide_inst<EPI_QKV, 1, 8>(p, s);
-    case EPI_SWIGLU: return tall ? launch_wide_inst<EPI_SWIGLU, 2, 16>(p, s) : launch_wide_inst<EPI_SWIGLU, 1, 8>(p, s);
+    case EPI_RESID: return small ? launch_wide_inst<EPI_RESID, 8, 1>(p, s) : launch_wide_inst<EPI_RESID, 8, 2>(p, s);
+    case EPI_QKV: return small ? launch_wide_inst<EPI_QKV, 8, 1>(p, s) : launch_wide_inst<EPI_QKV, 8, 2>(p, s);
+    case EPI_SWIGLU: return small ? launch_wide_inst<EPI_SWIGLU, 8, 1>(p, s) : launch_wide_inst<EPI_SWIGLU, 8, 2>(p, s);
     default: return hipErrorInvalidValue;
   }
 }
