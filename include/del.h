@@ -208,12 +208,21 @@ del_status del_profile_read(const del_ctx* ctx, del_prof_entry* out, int32_t cap
  *   the accepted drafts and the last token, *n_out their number.  Shadow tokens stay greedy at every
  *   layer and the statistics count them over rows 0..u with u the number of accepted drafts.
  *   temperature > 0, 0 < top_p <= 1, else DEL_E_ARG; otherwise the errors of del_round.
+ * del_round_sample_dynamic: del_round_sample with dynamic draft-exiting on top (Section 4.4): d_cap caps
+ *   the draft length and drafting stops, before a token is drawn, at the first step whose confidence
+ *   (temperature-1 soft-max probability of the exit layer's greedy token) is below tau >= 0.  uniforms has
+ *   2*d_cap+1 numbers and every draw keeps its place: draft i uses uniforms[i], acceptance i
+ *   uniforms[d_cap+i], the last token uniforms[2*d_cap].  *gamma_used / *stopped_early as in
+ *   del_round_dynamic.
  * del_debug_spec_sample: the same sampling arithmetic on logits the caller supplies (host,
  *   q_logits [gamma][vocab], p_logits [gamma+1][vocab], row-major); no model, no state change.
  *   drafts_out (host, gamma ints; may be NULL when gamma == 0), *u, *last_token. */
 del_status del_sample_first(del_ctx* ctx, double temperature, double top_p, float r, int32_t* token);
 del_status del_round_sample(del_ctx* ctx, int32_t E, int32_t gamma, double temperature, double top_p,
                             const float* uniforms, int32_t* out_tokens, int32_t* n_out);
+del_status del_round_sample_dynamic(del_ctx* ctx, int32_t E, double tau, int32_t d_cap, double temperature,
+                                    double top_p, const float* uniforms, int32_t* out_tokens, int32_t* n_out,
+                                    int32_t* gamma_used, int32_t* stopped_early);
 del_status del_debug_spec_sample(del_ctx* ctx, const float* q_logits, const float* p_logits, int32_t gamma,
                                  double temperature, double top_p, const float* uniforms, int32_t* drafts_out,
                                  int32_t* u, int32_t* last_token);

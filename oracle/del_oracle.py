@@ -66,6 +66,10 @@ the pins in tests/ cover the mathematics around them):
       last position.  The uniform numbers are inputs (gamma for the drafts,
       gamma for the acceptances, one for the last token).  All of this runs in
       fp64 on the fp32-rounded logits.
+  R21 dynamic draft-exiting under sampling: the confidence of a draft step is, as
+      in R18, the temperature-1 soft-max probability of the exit layer's greedy
+      token (the quantity tau_l is built from); a step below tau_E stops the
+      drafting before its token is drawn.
   R20 statistics under sampling: shadow tokens are greedy at every layer,
       layer L included (Section 4.2 obtains them by greedy decoding), u_r is
       the number of drafted tokens the sampling rule accepted, and c^l, tcs^l,
@@ -570,9 +574,13 @@ class Oracle:
         return tok, dist
 
     def round_sample(self, E: int, gamma: int, temperature: float, top_p: float,
-                     uniforms: Sequence[float], keep_hidden: bool = False) -> RoundRecord:
+                     uniforms: Sequence[float], keep_hidden: bool = False,
+                     tau: Optional[float] = None) -> RoundRecord:
         """One self-speculative round with sampled drafts and the sampling acceptance rule.
-        uniforms: gamma numbers for the drafts, gamma for the acceptances, one for the last token."""
+        uniforms: gamma numbers for the drafts, gamma for the acceptances, one for the last token.
+        tau: dynamic draft-exiting on top (reading R21): `gamma` is then the cap on the draft length,
+        and drafting stops, before a token is drawn, at the first step whose confidence is below tau;
+        the uniform numbers keep their places (draft i uses uniforms[i], acceptance i uniforms[gamma+i])."""
         L, d = self.L, self.cfg.d_model
         assert 1 <= E <= L and 0 <= gamma and len(uniforms) >= 2 * gamma + 1
         assert self.pending is not None, "prefill first"
@@ -584,6 +592,8 @@ class Oracle:
         hid = torch.zeros((L + 1, gamma + 1, d), dtype=self.dtype)
         drafts: List[int] = []
         q_dists: List[torch.Tensor] = []
+        draft_conf: List[float] = []
+        stopped = False
         tok = self.pending
         for i in range(gamma + 1):
             h = self.embed(tok)[None, :]
@@ -592,10 +602,19 @@ class Oracle:
                 h = self.layer(l, h, T + i)
                 hid[l, i] = h[0]
             if i < gamma:
+                if tau is not None:
+                    _, _, cf = self.head_conf(hid[E, i][None, :])
+                    draft_conf.append(cf[0])
+                    if cf[0] < tau:
+                        stopped = True          # nothing drawn; row i is the round's last row
+                        break
                 qd = tempered_nucleus(self.logits(hid[E, i][None, :])[0], temperature, top_p)
                 tok = inverse_cdf(qd, r_draft[i])
                 q_dists.append(qd)
                 drafts.append(tok)
+        if stopped:
+            gamma = len(drafts)
+            hid = hid[:, :gamma + 1].clone()
         rows = hid[E].clone()
         for l in range(E + 1, L + 1):
             rows = self.layer(l, rows, T)
@@ -624,10 +643,10 @@ class Oracle:
         return RoundRecord(E, gamma, T, drafts, target, u, n, out, shadow, gaps, c, alpha,
                            [0.0] + [self.stats.S_c(l) for l in range(1, L + 1)],
                            self.stats.S_n(), nE, ng, hid if keep_hidden else None,
-                           conf, None, False, tcs, fcs, self.stats.tau(),
+                           conf, draft_conf if tau is not None else None, stopped, tcs, fcs, self.stats.tau(),
                            [0.0] + [self.stats.S_tcs(l) for l in range(1, L + 1)],
                            [0.0] + [self.stats.S_fcs(l) for l in range(1, L + 1)],
-                           q_dists, p_dists, last_dist, list(map(float, uniforms[:2 * gamma + 1])))
+                           q_dists, p_dists, last_dist, [float(x) for x in uniforms])
 
     # ---- reference definitions used by the pins ----
     def vanilla_step(self) -> int:
@@ -714,11 +733,12 @@ def generate_del_full(oracle: Oracle, prompt: Sequence[int], n_tokens: int, keep
 
 
 def generate_sample(oracle: Oracle, prompt: Sequence[int], n_tokens: int, temperature: float, top_p: float,
-                    uniforms_for, keep_hidden: bool = False, schedule=None,
+                    uniforms_for, keep_hidden: bool = False, schedule=None, dynamic: bool = False,
                     ) -> Tuple[List[int], PrefillRecord, List[RoundRecord]]:
     """Speculative sampling with DEL choosing (E, gamma) every round (or schedule(round) if given).
     uniforms_for(k, count) returns the uniform numbers of draw k: k = 0 is the first token (one
-    number), k = r + 1 is round r (2 * gamma + 1 numbers)."""
+    number), k = r + 1 is round r (2 * gamma + 1 numbers).  dynamic: draft-exiting on top
+    (Algorithm 1 in full): gamma is d_max and the draft loop stops on tau_E."""
     pre = oracle.prefill(prompt, keep_hidden)
     first, _ = oracle.sample_first(temperature, top_p, float(uniforms_for(0, 1)[0]))
     toks = [first]
@@ -727,8 +747,10 @@ def generate_sample(oracle: Oracle, prompt: Sequence[int], n_tokens: int, temper
     while len(toks) < n_tokens:
         if schedule is not None:
             E, gamma = schedule(len(recs))
-        g = min(gamma, n_tokens - len(toks) - 1)
-        r = oracle.round_sample(E, g, temperature, top_p, uniforms_for(len(recs) + 1, 2 * g + 1), keep_hidden)
+        g = min(oracle.cfg.d_max if dynamic else gamma, n_tokens - len(toks) - 1)
+        tau = (recs[-1].tau[E] if recs else pre.tau[E]) if dynamic else None
+        r = oracle.round_sample(E, g, temperature, top_p, uniforms_for(len(recs) + 1, 2 * g + 1), keep_hidden,
+                                tau=tau)
         recs.append(r)
         toks.extend(r.out_tokens)
         E, gamma = r.next_E, r.next_gamma

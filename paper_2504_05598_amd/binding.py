@@ -15,7 +15,7 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 
 EXPORTS = ["del_create", "del_destroy", "del_load_weights", "del_prefill", "del_round", "del_round_dynamic",
            "del_layer_stats", "del_set_layer_stats", "del_last_timings", "del_debug_hidden",
-           "del_debug_logits", "del_debug_state", "del_debug_set_pending", "del_debug_last_rows", "del_profile_enable", "del_profile_read", "del_policy_step", "del_sample_first", "del_round_sample", "del_debug_spec_sample", "del_bench_stream_read", "del_bench_stream_copy", "del_strerror",
+           "del_debug_logits", "del_debug_state", "del_debug_set_pending", "del_debug_last_rows", "del_profile_enable", "del_profile_read", "del_policy_step", "del_sample_first", "del_round_sample", "del_round_sample_dynamic", "del_debug_spec_sample", "del_bench_stream_read", "del_bench_stream_copy", "del_strerror",
            "del_last_error_text"]
 
 DEL_DTYPE_FP32, DEL_DTYPE_BF16 = 0, 1
@@ -107,6 +107,8 @@ def load_library():
     lib.del_sample_first.argtypes = [C.c_void_p, C.c_double, C.c_double, C.c_float, P(C.c_int32)]
     lib.del_round_sample.argtypes = [C.c_void_p, C.c_int32, C.c_int32, C.c_double, C.c_double, P(C.c_float),
                                      P(C.c_int32), P(C.c_int32)]
+    lib.del_round_sample_dynamic.argtypes = [C.c_void_p, C.c_int32, C.c_double, C.c_int32, C.c_double, C.c_double,
+                                             P(C.c_float), P(C.c_int32), P(C.c_int32), P(C.c_int32), P(C.c_int32)]
     lib.del_debug_spec_sample.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int32, C.c_double, C.c_double,
                                           P(C.c_float), P(C.c_int32), P(C.c_int32), P(C.c_int32)]
     lib.del_strerror.argtypes = [C.c_int]
@@ -189,6 +191,19 @@ def del_round_sample(ctx, E: int, gamma: int, temperature: float, top_p: float,
     n = C.c_int32()
     _check(load_library().del_round_sample(ctx, E, gamma, temperature, top_p, un, out, C.byref(n)), ctx)
     return list(out[:n.value])
+
+
+def del_round_sample_dynamic(ctx, E: int, tau: float, d_cap: int, temperature: float, top_p: float,
+                             uniforms: Sequence[float]) -> Tuple[List[int], int, bool]:
+    """uniforms: 2 * d_cap + 1 numbers.  Returns (tokens, tokens drafted, stopped early)."""
+    if len(uniforms) < 2 * d_cap + 1:
+        raise ValueError("need 2 * d_cap + 1 uniform numbers")
+    un = (C.c_float * (2 * d_cap + 1))(*[float(x) for x in uniforms[:2 * d_cap + 1]])
+    out = (C.c_int32 * (d_cap + 1))()
+    n, g, stop = C.c_int32(), C.c_int32(), C.c_int32()
+    _check(load_library().del_round_sample_dynamic(ctx, E, tau, d_cap, temperature, top_p, un, out, C.byref(n),
+                                                   C.byref(g), C.byref(stop)), ctx)
+    return list(out[:n.value]), g.value, bool(stop.value)
 
 
 def del_debug_spec_sample(ctx, q_logits, p_logits, gamma: int, temperature: float, top_p: float,
@@ -335,6 +350,9 @@ class DelContext:
 
     def round_sample(self, E: int, gamma: int, temperature: float, top_p: float, uniforms) -> List[int]:
         return del_round_sample(self.ctx, E, gamma, temperature, top_p, uniforms)
+
+    def round_sample_dynamic(self, E: int, tau: float, d_cap: int, temperature: float, top_p: float, uniforms):
+        return del_round_sample_dynamic(self.ctx, E, tau, d_cap, temperature, top_p, uniforms)
 
     def spec_sample(self, q_logits, p_logits, gamma: int, temperature: float, top_p: float, uniforms):
         return del_debug_spec_sample(self.ctx, q_logits, p_logits, gamma, temperature, top_p, uniforms)

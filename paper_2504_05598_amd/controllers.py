@@ -35,8 +35,6 @@ def generate(ctx, prompt: Sequence[int], n_tokens: int, controller: str = "del",
     elif controller not in ("ls", "fs"):
         raise ValueError(controller)
     if sampling is not None:
-        if controller == "del_full":
-            raise ValueError("draft-exiting is offered for greedy decoding only")
         temperature, top_p, uniforms = sampling
         first = ctx.sample_first(temperature, top_p, float(uniforms(0, 1)[0]))
     toks = [first]
@@ -46,7 +44,12 @@ def generate(ctx, prompt: Sequence[int], n_tokens: int, controller: str = "del",
         if controller == "del_full":
             st = ctx.stats()
             E = st["next_E"]
-            out, g, _ = ctx.round_dynamic(E, st["tau"][E], min(cfg.d_max, room))
+            cap = min(cfg.d_max, room)
+            if sampling is not None:
+                out, g, _ = ctx.round_sample_dynamic(E, st["tau"][E], cap, temperature, top_p,
+                                                     [float(x) for x in uniforms(len(log) + 1, 2 * cap + 1)])
+            else:
+                out, g, _ = ctx.round_dynamic(E, st["tau"][E], cap)
         else:
             g = min(gamma, room)
             if sampling is not None:

@@ -1131,7 +1131,7 @@ del_status del_sample_first(del_ctx* ctx, double temperature, double top_p, floa
   HIPCHK(hipMemcpyAsync(ctx->unif_dev, &r, 4, hipMemcpyHostToDevice, s));
   HIPCHK(launch_samp_rowstats(ctx->slog + (size_t)VB * ctx->sld, ctx->sld, ctx->V, 1, temperature, top_p,
                               ctx->swf + (size_t)VB * ctx->sld, ctx->sld, ctx->srows + VB, ctx->unif_dev,
-                              ctx->draft_ids, ctx->state + 1, s));
+                              ctx->draft_ids, ctx->state + 1, nullptr, s));
   HIPCHK(hipMemcpyAsync(ctx->step_host, ctx->draft_ids, 4, hipMemcpyDeviceToHost, s));
   HIPCHK(hipStreamSynchronize(s));
   ctx->pending = ctx->step_host[0];
@@ -1139,8 +1139,12 @@ del_status del_sample_first(del_ctx* ctx, double temperature, double top_p, floa
   return DEL_OK;
 }
 
-del_status del_round_sample(del_ctx* ctx, int32_t E, int32_t gamma, double temperature, double top_p,
-                            const float* uniforms, int32_t* out_tokens, int32_t* n_out) {
+// One sampled round.  tau < 0: draft exactly `gamma` tokens; otherwise `gamma` caps the draft and the
+// loop stops, before a token is drawn, at the first step whose confidence is below tau.  uniforms:
+// [0, gamma) drafts, [gamma, 2*gamma) acceptances, [2*gamma] the last token.
+static del_status round_sample_impl(del_ctx* ctx, int E, int gamma, double tau, double temperature, double top_p,
+                                    const float* uniforms, int32_t* out_tokens, int32_t* n_out, int32_t* gamma_used,
+                                    int32_t* stopped_early) {
   if (!ctx || !out_tokens || !n_out || !uniforms || !sampling_args_ok(temperature, top_p)) return DEL_E_ARG;
   if (ctx->phase != 1) return DEL_E_STATE;
   const int L = ctx->L;
@@ -1149,11 +1153,15 @@ del_status del_round_sample(del_ctx* ctx, int32_t E, int32_t gamma, double tempe
     if (!(uniforms[i] >= 0.f && uniforms[i] < 1.f)) return DEL_E_ARG;
   if (ctx->T + gamma + 1 > ctx->Tcap) return DEL_E_CAPACITY;
   hipStream_t s = ctx->stream;
-  const int m = gamma + 1, VB = ctx->cfg.d_max + 1, V = ctx->V;
+  const int cap = gamma, VB = ctx->cfg.d_max + 1, V = ctx->V;
   const int64_t ld = ctx->sld;
-  HIPCHK(hipMemcpyAsync(ctx->unif_dev, uniforms, (size_t)(2 * gamma + 1) * 4, hipMemcpyHostToDevice, s));
+  const bool dynamic = tau >= 0.0;
+  const int Rmax = L * ctx->maxrows;
+  float* dconf = ctx->conf_dev + Rmax;   // draft confidences
+  HIPCHK(hipMemcpyAsync(ctx->unif_dev, uniforms, (size_t)(2 * cap + 1) * 4, hipMemcpyHostToDevice, s));
   HIPCHK(hipEventRecord(ctx->ev[0], s));
   // ---- draft: layers 1..E, the exit layer's logits, a draw from their nucleus
+  bool stopped = false;
   for (int i = 0; i <= gamma; ++i) {
     const int* tok = i == 0 ? ctx->state + 1 : ctx->draft_ids + (i - 1);
     HIPCHK(launch_embed(ctx->embed_t, ctx->wd, ctx->KTd, V, tok, 1, ctx->hid_row(0, i), ctx->dpad, ctx->d, s));
@@ -1165,9 +1173,22 @@ del_status del_round_sample(del_ctx* ctx, int32_t E, int32_t gamma, double tempe
       del_status st = sample_logits(ctx, E, i, 1, i);
       if (st != DEL_OK) return st;
       HIPCHK(launch_samp_rowstats(ctx->slog + (size_t)i * ld, ld, V, 1, temperature, top_p, ctx->swf + (size_t)i * ld,
-                                  ld, ctx->srows + i, ctx->unif_dev + i, ctx->draft_ids + i, nullptr, s));
+                                  ld, ctx->srows + i, ctx->unif_dev + i, ctx->draft_ids + i, nullptr,
+                                  dynamic ? dconf + i : nullptr, s));
+      if (dynamic) {   // the host decides whether to go on: one small copy and a sync per step
+        HIPCHK(hipMemcpyAsync(ctx->step_host, dconf + i, 4, hipMemcpyDeviceToHost, s));
+        HIPCHK(hipStreamSynchronize(s));
+        float cf;
+        memcpy(&cf, ctx->step_host, 4);
+        if ((double)cf < tau) {   // the token drawn at this step is dropped; row i is the round's last row
+          gamma = i;
+          stopped = true;
+          break;
+        }
+      }
     }
   }
+  const int m = gamma + 1;
   HIPCHK(hipEventRecord(ctx->ev[1], s));
   // ---- verify: the gamma+1 exit states through layers E+1..L
   for (int l = E + 1; l <= L; ++l) {
@@ -1182,16 +1203,39 @@ del_status del_round_sample(del_ctx* ctx, int32_t E, int32_t gamma, double tempe
     st = sample_logits(ctx, L, 0, m, VB);
     if (st != DEL_OK) return st;
     HIPCHK(launch_samp_rowstats(ctx->slog + (size_t)VB * ld, ld, V, m, temperature, top_p, ctx->swf + (size_t)VB * ld, ld,
-                                ctx->srows + VB, nullptr, nullptr, nullptr, s));
+                                ctx->srows + VB, nullptr, nullptr, nullptr, nullptr, s));
     HIPCHK(launch_samp_accept(ctx->slog, ctx->swf, ctx->srows, ctx->slog + (size_t)VB * ld, ctx->swf + (size_t)VB * ld,
-                              ctx->srows + VB, ld, ld, V, gamma, ctx->draft_ids, ctx->unif_dev + gamma, ctx->state,
-                              ctx->shadow_ids, L * m, ctx->result, s));
+                              ctx->srows + VB, ld, ld, V, gamma, ctx->draft_ids, ctx->unif_dev + cap,
+                              ctx->unif_dev + 2 * cap, ctx->state, ctx->shadow_ids, L * m, ctx->result, s));
     const size_t nres = (size_t)3 + gamma + (size_t)L * m;
     HIPCHK(hipMemcpyAsync(ctx->result_host, ctx->result, nres * 4, hipMemcpyDeviceToHost, s));
     HIPCHK(hipMemcpyAsync(ctx->conf_host, ctx->conf_dev, (size_t)L * m * 4, hipMemcpyDeviceToHost, s));
+    if (dynamic)
+      HIPCHK(hipMemcpyAsync(ctx->conf_host + Rmax, dconf, (size_t)(gamma + 1) * 4, hipMemcpyDeviceToHost, s));
   }
   HIPCHK(hipEventRecord(ctx->ev[3], s));
-  return finish_round(ctx, E, gamma, false, true, out_tokens, n_out);
+  del_status fst = finish_round(ctx, E, gamma, stopped, true, out_tokens, n_out);
+  if (fst != DEL_OK) return fst;
+  if (dynamic) {
+    const float* dcf = ctx->conf_host + Rmax;
+    for (int i = 0; i < gamma + (stopped ? 1 : 0); ++i) ctx->last_draft_conf[i] = dcf[i];
+  }
+  if (gamma_used) *gamma_used = gamma;
+  if (stopped_early) *stopped_early = stopped ? 1 : 0;
+  return DEL_OK;
+}
+
+del_status del_round_sample(del_ctx* ctx, int32_t E, int32_t gamma, double temperature, double top_p,
+                            const float* uniforms, int32_t* out_tokens, int32_t* n_out) {
+  return round_sample_impl(ctx, E, gamma, -1.0, temperature, top_p, uniforms, out_tokens, n_out, nullptr, nullptr);
+}
+
+del_status del_round_sample_dynamic(del_ctx* ctx, int32_t E, double tau, int32_t d_cap, double temperature,
+                                    double top_p, const float* uniforms, int32_t* out_tokens, int32_t* n_out,
+                                    int32_t* gamma_used, int32_t* stopped_early) {
+  if (!(tau >= 0.0)) return DEL_E_ARG;
+  return round_sample_impl(ctx, E, d_cap, tau, temperature, top_p, uniforms, out_tokens, n_out, gamma_used,
+                           stopped_early);
 }
 
 del_status del_debug_spec_sample(del_ctx* ctx, const float* q_logits, const float* p_logits, int32_t gamma,
@@ -1220,11 +1264,12 @@ del_status del_debug_spec_sample(del_ctx* ctx, const float* q_logits, const floa
   HIPCHK(hipMemsetAsync(scratch, 0, n_scr * 4, s));
   if (gamma > 0)
     HIPCHK(launch_samp_rowstats(ctx->slog, ld, V, gamma, temperature, top_p, ctx->swf, ld, ctx->srows, ctx->unif_dev,
-                                dr_s, nullptr, s));
+                                dr_s, nullptr, nullptr, s));
   HIPCHK(launch_samp_rowstats(ctx->slog + (size_t)VB * ld, ld, V, gamma + 1, temperature, top_p,
-                              ctx->swf + (size_t)VB * ld, ld, ctx->srows + VB, nullptr, nullptr, nullptr, s));
+                              ctx->swf + (size_t)VB * ld, ld, ctx->srows + VB, nullptr, nullptr, nullptr, nullptr, s));
   HIPCHK(launch_samp_accept(ctx->slog, ctx->swf, ctx->srows, ctx->slog + (size_t)VB * ld, ctx->swf + (size_t)VB * ld,
-                            ctx->srows + VB, ld, ld, V, gamma, dr_s, ctx->unif_dev + gamma, st_s, nullptr, 0, rs_s, s));
+                            ctx->srows + VB, ld, ld, V, gamma, dr_s, ctx->unif_dev + gamma, ctx->unif_dev + 2 * gamma, st_s,
+                            nullptr, 0, rs_s, s));
   HIPCHK(hipStreamSynchronize(s));
   std::vector<int> host(n_scr);
   HIPCHK(hipMemcpy(host.data(), scratch, n_scr * 4, hipMemcpyDeviceToHost));

@@ -141,16 +141,19 @@ struct SampRow {
   int argmax;                    // greedy token (lowest id at the maximum)
   unsigned long long Wkept;      // mass of the nucleus
   unsigned long long Wtot;       // mass of all tokens
+  float conf;                    // soft-max probability of the greedy token at temperature 1 (if asked for)
+  int pad;
 };
 // draw_r (optional): also draw one token per row with the uniform number draw_r[row] into draw_tok[row]
 // (and into *pending, if given; one row only).
+// conf_out (optional): the greedy token's temperature-1 soft-max probability per row.
 hipError_t launch_samp_rowstats(const float* Z, int64_t ldz, int V, int rows, double temperature, double top_p,
                                 unsigned long long* WF, int64_t ldw, SampRow* out, const float* draw_r, int* draw_tok,
-                                int* pending, hipStream_t s);
+                                int* pending, float* conf_out, hipStream_t s);
 hipError_t launch_samp_accept(const float* Zq, const unsigned long long* WFq, const SampRow* rq, const float* Zp,
                               const unsigned long long* WFp, const SampRow* rp, int64_t ldz, int64_t ldw, int V,
-                              int gamma, const int* drafts, const float* unif, int* state, const int* shadow_ids,
-                              int n_shadow, int* result, hipStream_t s);
+                              int gamma, const int* drafts, const float* unif_accept, const float* unif_last, int* state,
+                              const int* shadow_ids, int n_shadow, int* result, hipStream_t s);
 
 
 }  // namespace del

@@ -216,7 +216,8 @@ __device__ __forceinline__ void select_bin(const u64* hist, u64 above, u64 targe
 // draw_tok[row] (and into *pending, if given).
 __global__ void __launch_bounds__(SB) samp_rowstats_k(const float* Z, long long ldz, int V, double inv_temp,
                                                       double top_p, u64* WF, long long ldw, SampRow* rows,
-                                                      const float* draw_r, int* draw_tok, int* pending) {
+                                                      const float* draw_r, int* draw_tok, int* pending,
+                                                      float* conf_out) {
   __shared__ PickLds pl;
   __shared__ double dbuf[SB];
   __shared__ u64 hist[256];
@@ -263,9 +264,11 @@ __global__ void __launch_bounds__(SB) samp_rowstats_k(const float* Z, long long 
   if (t < 256) { hist[t] = 0; bmin[t] = 0xffffffffu; bmax[t] = 0u; }
   __syncthreads();
   u64 wsum = 0;
+  double s1 = 0.0;   // temperature-1 partition sum, only when the confidence is asked for
   sweep(z, V, [&](int j, float zj) {
     const float zc = zj + 0.0f;
     const double dz = (double)zc - (double)zmax;
+    if (conf_out) s1 += exp(dz);
     const u64 w = (u64)rint(exp(dz * inv_temp) * FIX);
     wf[j] = w;
     wsum += w;
@@ -286,6 +289,17 @@ __global__ void __launch_bounds__(SB) samp_rowstats_k(const float* Z, long long 
   }
   const u64 Wtot = sbuf[0];
   __syncthreads();
+  float conf = 0.f;
+  if (conf_out) {
+    dbuf[t] = s1;
+    __syncthreads();
+    for (int off = SB / 2; off > 0; off >>= 1) {
+      if (t < off) dbuf[t] += dbuf[t + off];
+      __syncthreads();
+    }
+    conf = (float)(1.0 / dbuf[0]);
+    __syncthreads();
+  }
   unsigned kstar = 0;
   int tie_id = V;
   u64 Wkept = Wtot;
@@ -374,8 +388,11 @@ __global__ void __launch_bounds__(SB) samp_rowstats_k(const float* Z, long long 
   }
   SampRow R;
   R.zmax = zmax; R.kstar = kstar; R.tie_id = tie_id; R.argmax = s_arg;
-  R.Wkept = Wkept; R.Wtot = Wtot;
-  if (t == 0) rows[row] = R;
+  R.Wkept = Wkept; R.Wtot = Wtot; R.conf = conf; R.pad = 0;
+  if (t == 0) {
+    rows[row] = R;
+    if (conf_out) conf_out[row] = conf;
+  }
   if (draw_r) {
     u64 total;
     const int tok = pick_by_fraction(KeptMass{z, wf, R, V}, V, (double)draw_r[row], &pl, &total);
@@ -389,13 +406,14 @@ __global__ void __launch_bounds__(SB) samp_rowstats_k(const float* Z, long long 
 
 // Acceptance of gamma drafted tokens and the round's last token; commits the KV length and the
 // pending token.  Rows 0..gamma-1 of (Zq, WFq, rq) are the draft steps, rows 0..gamma of
-// (Zp, WFp, rp) the target's.  unif[0..gamma) decide the acceptances, unif[gamma] draws the last token.
+// (Zp, WFp, rp) the target's.  unif_accept[0..gamma) decide the acceptances, *unif_last draws the last token.
 // result: [0]=u, [1]=new KV length, [2]=last token, [3..3+gamma)=drafts, then the L*m shadow tokens.
 __global__ void __launch_bounds__(SB) samp_accept_k(const float* Zq, const u64* WFq, const SampRow* rq,
                                                     const float* Zp, const u64* WFp, const SampRow* rp,
                                                     long long ldz, long long ldw, int V, int gamma,
-                                                    const int* drafts, const float* unif, int* state,
-                                                    const int* shadow_ids, int n_shadow, int* result) {
+                                                    const int* drafts, const float* unif_accept,
+                                                    const float* unif_last, int* state, const int* shadow_ids,
+                                                    int n_shadow, int* result) {
   __shared__ PickLds pl;
   __shared__ int s_rej[64];
   __shared__ int s_u;
@@ -409,7 +427,7 @@ __global__ void __launch_bounds__(SB) samp_accept_k(const float* Zq, const u64* 
       const double qx = (double)WFq[(long long)t * ldw + x] / (double)q.Wkept;
       const double px = kept(p, Zp[(long long)t * ldz + x], x)
                             ? (double)WFp[(long long)t * ldw + x] / (double)p.Wkept : 0.0;
-      rej = !((double)unif[t] * qx < px);
+      rej = !((double)unif_accept[t] * qx < px);
     }
     s_rej[t] = rej;
   }
@@ -422,7 +440,7 @@ __global__ void __launch_bounds__(SB) samp_accept_k(const float* Zq, const u64* 
   }
   __syncthreads();
   const int u = s_u;
-  const double r = (double)unif[gamma];
+  const double r = (double)*unif_last;
   const float* zp = Zp + (long long)u * ldz;
   const u64* wp = WFp + (long long)u * ldw;
   const SampRow P = rp[u];
@@ -463,21 +481,21 @@ __global__ void __launch_bounds__(SB) samp_accept_k(const float* Zq, const u64* 
 
 hipError_t launch_samp_rowstats(const float* Z, int64_t ldz, int V, int rows, double temperature, double top_p,
                                 unsigned long long* WF, int64_t ldw, SampRow* out, const float* draw_r, int* draw_tok,
-                                int* pending, hipStream_t s) {
+                                int* pending, float* conf_out, hipStream_t s) {
   if (rows <= 0 || V <= 0 || !(temperature > 0.0) || !(top_p > 0.0) || (draw_r && !draw_tok))
     return hipErrorInvalidValue;
   hipLaunchKernelGGL(samp_rowstats_k, dim3(rows), dim3(SB), 0, s, Z, (long long)ldz, V, 1.0 / temperature, top_p, WF,
-                     (long long)ldw, out, draw_r, draw_tok, pending);
+                     (long long)ldw, out, draw_r, draw_tok, pending, conf_out);
   return hipGetLastError();
 }
 
 hipError_t launch_samp_accept(const float* Zq, const unsigned long long* WFq, const SampRow* rq, const float* Zp,
                               const unsigned long long* WFp, const SampRow* rp, int64_t ldz, int64_t ldw, int V,
-                              int gamma, const int* drafts, const float* unif, int* state, const int* shadow_ids,
-                              int n_shadow, int* result, hipStream_t s) {
+                              int gamma, const int* drafts, const float* unif_accept, const float* unif_last, int* state,
+                              const int* shadow_ids, int n_shadow, int* result, hipStream_t s) {
   if (gamma < 0 || gamma > 64 || V <= 0) return hipErrorInvalidValue;
   hipLaunchKernelGGL(samp_accept_k, dim3(1), dim3(SB), 0, s, Zq, WFq, rq, Zp, WFp, rp, (long long)ldz, (long long)ldw,
-                     V, gamma, drafts, unif, state, shadow_ids, n_shadow, result);
+                     V, gamma, drafts, unif_accept, unif_last, state, shadow_ids, n_shadow, result);
   return hipGetLastError();
 }
 

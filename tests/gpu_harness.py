@@ -248,11 +248,13 @@ def _cut_slack(oracle: Oracle, h_row: torch.Tensor, dist: torch.Tensor, temperat
 
 
 def lockstep_sample(cfg, oracle: Oracle, ctx: DelContext, prompt, n_tokens, temperature, top_p,
-                    sample_tol, ratio_tol, schedule=None, stream0=0) -> ParityReport:
+                    sample_tol, ratio_tol, schedule=None, stream0=0, dynamic=False) -> ParityReport:
     """Speculative sampling in lock-step: the same uniform numbers on both sides; drafts, acceptance
     count, emitted tokens, greedy shadow tokens, statistics and the next (E, gamma) are compared.
     A differing sampled decision must be a near-boundary one (see above) and is followed by a
-    re-prefill of the GPU context on the oracle's tokens."""
+    re-prefill of the GPU context on the oracle's tokens.
+    dynamic: draft-exiting on top: the cap is d_max, the loop stops on the oracle's tau_E; the stop
+    decision may differ only where the oracle's confidence is within CONF_RTOL of the threshold."""
     from synthdata import gen_uniforms
     rep = ParityReport()
     L = cfg.n_layers
@@ -273,18 +275,35 @@ def lockstep_sample(cfg, oracle: Oracle, ctx: DelContext, prompt, n_tokens, temp
     if (gE, gg) != (pre.next_E, pre.next_gamma):
         _resync(ctx, oracle, prompt, emitted, rep)
     E, gamma = (pre.next_E, pre.next_gamma) if schedule is None else schedule
+    tau = pre.tau[E]
     while len(emitted) < n_tokens:
-        g = min(gamma, n_tokens - len(emitted) - 1)
+        # g: the draft length asked for (the cap, if dynamic); the uniform numbers are laid out by it
+        g = min(cfg.d_max if dynamic else gamma, n_tokens - len(emitted) - 1)
         un = gen_uniforms(cfg, stream0 + 1 + rep.rounds, 2 * g + 1).tolist()
-        r = oracle.round_sample(E, g, temperature, top_p, un, keep_hidden=True)
-        out = ctx.round_sample(E, g, temperature, top_p, un)
-        st = ctx.stats()
-        rep.rounds += 1
-        decisions += 2 * g + 1
         diverged = None
+        if dynamic:
+            r = oracle.round_sample(E, g, temperature, top_p, un, keep_hidden=True, tau=tau)
+            out, g_gpu, stopped = ctx.round_sample_dynamic(E, tau, g, temperature, top_p, un)
+            st = ctx.stats()
+            n_draft = min(g_gpu, r.gamma)
+            for i, cf in enumerate(st["last_draft_conf"][:n_draft]):
+                if st["last_draft"][:i] == r.draft_ids[:i]:
+                    assert _close(cf, r.draft_conf[i], CONF_RTOL), ("draft confidence", i, cf, r.draft_conf[i])
+            if (g_gpu, stopped) != (r.gamma, r.stopped_early) and st["last_draft"][:n_draft] == r.draft_ids[:n_draft]:
+                assert n_draft < len(r.draft_conf) and _close(r.draft_conf[n_draft], tau, CONF_RTOL), (
+                    f"round {rep.rounds + 1}: gpu drafted {g_gpu} (stopped {stopped}), oracle {r.gamma} "
+                    f"(stopped {r.stopped_early}), confidences {r.draft_conf}, tau {tau}")
+                diverged = ("stop", n_draft)
+        else:
+            r = oracle.round_sample(E, g, temperature, top_p, un, keep_hidden=True)
+            out = ctx.round_sample(E, g, temperature, top_p, un)
+            st = ctx.stats()
+            n_draft = g
+        rep.rounds += 1
+        decisions += 2 * n_draft + 1
         # the drafts, in order; after a differing draft the two sides see different inputs
-        same_rows = g + 1
-        for i in range(g):
+        same_rows = n_draft + 1
+        for i in range(n_draft):
             if st["last_draft"][i] != r.draft_ids[i]:
                 d = _interval_distance(r.q_dists[i], st["last_draft"][i], un[i])
                 slack = _cut_slack(oracle, r.hidden[E, i], r.q_dists[i], temperature, top_p)
@@ -310,6 +329,7 @@ def lockstep_sample(cfg, oracle: Oracle, ctx: DelContext, prompt, n_tokens, temp
             assert err <= HID_TOL, ("hidden", rep.rounds, l, err)
         if diverged is None:
             u_g = len(out) - 1
+            gg = r.gamma      # drafts actually taken (equal on both sides here)
             if u_g != r.u:
                 # the acceptance at the first position where the two sides differ
                 k = min(u_g, r.u)
@@ -326,7 +346,7 @@ def lockstep_sample(cfg, oracle: Oracle, ctx: DelContext, prompt, n_tokens, temp
             elif out[-1] != r.out_tokens[-1]:
                 d = _interval_distance(r.last_dist, out[-1], un[2 * g])
                 slack = _cut_slack(oracle, r.hidden[L, r.u], r.p_dists[r.u], temperature, top_p)
-                if r.u < g:
+                if r.u < gg:
                     slack += _cut_slack(oracle, r.hidden[E, r.u], r.q_dists[r.u], temperature, top_p)
                     # the residual is renormalised by its own total: boundary shifts scale with 1 / total
                     total = float(torch.clamp(r.p_dists[r.u] - r.q_dists[r.u], min=0).sum())
@@ -354,6 +374,7 @@ def lockstep_sample(cfg, oracle: Oracle, ctx: DelContext, prompt, n_tokens, temp
             _resync(ctx, oracle, prompt, emitted, rep)
         if schedule is None:
             E, gamma = r.next_E, r.next_gamma
+        tau = r.tau[E]
     rep.tokens = emitted
     rep.decisions = decisions
     return rep

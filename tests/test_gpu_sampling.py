@@ -181,3 +181,37 @@ def test_sampled_generation_is_reproducible():
         runs.append(toks)
     assert runs[0] == runs[1]
     assert len(set(runs[0])) > 8
+
+
+@pytest.mark.parametrize("name,T,top_p,stol,rtol", [CASES[0], CASES[2], CASES[4], CASES[5]])
+def test_sampled_rounds_with_draft_exiting_in_lockstep(name, T, top_p, stol, rtol):
+    """Algorithm 1 in full under sampling: E from the statistics, the draft loop stops on tau_E."""
+    from gpu_harness import lockstep_sample, log
+    cfg, oracle, ctx, prompt = _setup(name)
+    rep = lockstep_sample(cfg, oracle, ctx, prompt, cfg.gen_len, T, top_p, stol, rtol, dynamic=True, stream0=7000)
+    log(f"{name} draft-exiting: {rep.rounds} rounds, {rep.decisions} sampled decisions, {rep.flips} near-boundary, "
+        f"{rep.resyncs} resyncs")
+    assert len(rep.tokens) >= cfg.gen_len
+    assert rep.flips <= max(2, rep.decisions // 5)
+
+
+def test_draft_exiting_threshold_extremes_under_sampling():
+    from gpu_harness import gpu_context
+    cfg = get_config("mini_mha")
+    prompt = gen_prompt(cfg).tolist()
+    a, _ = gpu_context(cfg)
+    b, _ = gpu_context(cfg)
+    for ctx in (a, b):
+        ctx.prefill(prompt)
+        ctx.sample_first(0.8, 0.9, 0.4)
+    for k in range(6):
+        E, cap = 1 + k % 4, 1 + k % cfg.d_max
+        un = gen_uniforms(cfg, 8000 + k, 2 * cap + 1).tolist()
+        # tau = 0 never stops: the plain sampled round with the same uniform numbers
+        out_b, g, stopped = b.round_sample_dynamic(E, 0.0, cap, 0.8, 0.9, un)
+        assert out_b == a.round_sample(E, cap, 0.8, 0.9, un) and g == cap and not stopped
+        assert a.state() == b.state()
+    # tau above 1 stops before the first draft: one token a round, drawn with the last uniform number
+    T0 = b.state()[0]
+    out, g, stopped = b.round_sample_dynamic(2, 1.5, 4, 0.8, 0.9, gen_uniforms(cfg, 8100, 9).tolist())
+    assert len(out) == 1 and g == 0 and stopped and b.state() == (T0 + 1, out[0])

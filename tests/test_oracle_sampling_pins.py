@@ -201,3 +201,35 @@ def test_sampled_round_bookkeeping(tiny_model):
             x = r.draft_ids[r.u]
             assert float(r.last_dist[x]) == 0.0 or float(r.p_dists[r.u][x]) > float(r.q_dists[r.u][x])
     assert rejected > 0
+
+
+def test_draft_exiting_under_sampling_limits(tiny_model):
+    """tau = 0 never stops (the plain sampled round); tau > 1 stops at once (a round of one token drawn
+    from the target with the last uniform number); at low temperature it is the greedy round with
+    draft-exiting."""
+    cfg, weights, prompt = tiny_model
+    gen = torch.Generator().manual_seed(11)
+    a, b, c, d, e = (Oracle(cfg, weights) for _ in range(5))
+    for o in (a, b, c, d, e):
+        o.prefill(prompt)
+    for o in (a, b, c):
+        o.sample_first(0.8, 0.9, 0.3)
+    for (E, cap) in [(2, 4), (1, 3), (3, 4), (2, 1)]:
+        un = torch.rand(2 * cap + 1, generator=gen).tolist()
+        ra = a.round_sample(E, cap, 0.8, 0.9, un)
+        rb = b.round_sample(E, cap, 0.8, 0.9, un, tau=0.0)
+        assert rb.out_tokens == ra.out_tokens and rb.u == ra.u and not rb.stopped_early
+        assert len(rb.draft_conf) == cap and rb.gamma == cap
+        rc = c.round_sample(E, cap, 0.8, 0.9, un, tau=1.5)
+        assert rc.stopped_early and rc.gamma == 0 and rc.u == 0 and len(rc.out_tokens) == 1
+        assert rc.out_tokens[0] == int(inverse_cdf(rc.p_dists[0], un[2 * cap])) and len(rc.draft_conf) == 1
+        tau = 0.5 * (max(rb.draft_conf) + min(rb.draft_conf))
+        rd = d.round(E, cap, tau=tau)
+        re_ = e.round_sample(E, cap, 1e-5, 1.0, un, tau=tau)
+        assert re_.out_tokens == rd.out_tokens and re_.stopped_early == rd.stopped_early and re_.gamma == rd.gamma
+        assert re_.draft_conf == rd.draft_conf and re_.c == rd.c
+        # keep the three sampled contexts on the same tokens
+        for o in (b, c):
+            o.T, o.pending = a.T, a.pending
+            for l in range(1, cfg.n_layers + 1):
+                o.K[l], o.V[l] = a.K[l].clone(), a.V[l].clone()
