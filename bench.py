@@ -220,7 +220,7 @@ def main():
     if pprof:
         # multiply-adds of a launch = weight elements x token rows; the activations enter as a bf16
         # high and low part, so the matrix cores execute twice that
-        pw = max(pprof, key=lambda e: e["total_ms"])
+        pw = max(pprof, key=lambda e: e["total_ms"])     # one class per (epilogue, matrix size)
         macs = sum(e["weight_bytes"] / 2 * e["rows"] * e["launches"] for e in pprof)
         ms = sum(e["total_ms"] for e in pprof)
         pw_tf = 2 * 2 * (pw["weight_bytes"] / 2) * pw["rows"] * pw["launches"] / (pw["total_ms"] * 1e-3) / 1e12

@@ -183,11 +183,11 @@ del_status del_bench_stream_copy(del_ctx* ctx, int64_t bytes, int32_t iters, flo
  * (hipExtLaunchKernel); per kernel class the launch count and the summed duration are
  * accumulated (throughput is still measured with profiling off).  A class is one kernel instantiation:
  * flavour (0 vector-ALU GEMV/GEMM, 1 matrix-core skinny GEMM, 2 shadow-head GEMM, 3 wide prefill GEMM), epilogue (0 store, 1 residual, 2 qkv+rotary,
- * 3 swiglu, 4 argmax), rows m.  weight_bytes is what one launch of the class streams. */
+ * 3 swiglu, 4 argmax), rows m, matrix size.  weight_bytes is what one launch of the class streams. */
 typedef struct {
   int32_t flavour, epilogue, rows, launches;
   double total_ms;
-  int64_t weight_bytes;    /* tile bytes streamed per launch (of the last launch seen) */
+  int64_t weight_bytes;    /* tile bytes streamed per launch (part of what makes a class) */
 } del_prof_entry;
 del_status del_profile_enable(del_ctx* ctx, int32_t on);   /* also clears the counters */
 del_status del_profile_read(const del_ctx* ctx, del_prof_entry* out, int32_t cap, int32_t* n);

@@ -194,7 +194,9 @@ int prof_begin(del_ctx* ctx, int flavour, int epi, int rows, int64_t bytes) {
   if (!ctx->prof_on) return -1;
   int cls = -1;
   for (size_t i = 0; i < ctx->prof.size(); ++i)
-    if (ctx->prof[i].flavour == flavour && ctx->prof[i].epilogue == epi && ctx->prof[i].rows == rows) cls = (int)i;
+    if (ctx->prof[i].flavour == flavour && ctx->prof[i].epilogue == epi && ctx->prof[i].rows == rows &&
+        ctx->prof[i].weight_bytes == bytes)
+      cls = (int)i;
   if (cls < 0) {
     del_prof_entry e{flavour, epi, rows, 0, 0.0, bytes};
     ctx->prof.push_back(e);
