@@ -226,20 +226,25 @@ def test_graph_replays_match_eager_launches():
     eager.close(); graphed.close()
 
 
-@pytest.mark.parametrize("name,plen,rows", [("mini_gqa", 150, 64), ("mini_mha", 97, 32), ("mini_g8", 200, 1024)])
-def test_wide_prefill_passes_match_the_oracle_and_the_short_passes(name, plen, rows, monkeypatch):
+@pytest.mark.parametrize("name,plen,rows,flash", [("mini_gqa", 150, 64, 1), ("mini_mha", 97, 32, 1),
+                                                  ("mini_g8", 200, 1024, 1), ("mini_gqa", 150, 64, 0),
+                                                  ("mini_mha", 120, 48, 0)])
+def test_wide_prefill_passes_match_the_oracle_and_the_short_passes(name, plen, rows, flash, monkeypatch):
     """Prefill in several wide passes (a ragged first one, then full ones that start on a filled cache)
-    against the oracle, and against the same library's 16-row passes."""
+    against the oracle, and against the same library's 16-row passes; with the matrix-core attention
+    and with the vector-ALU one."""
     from gpu_harness import gpu_context, lockstep, HID_TOL
     from oracle.del_oracle import Oracle, load_weights
     cfg = get_config(name)
     prompt = gen_prompt(cfg, length=plen).tolist()
     ctxlen = plen + cfg.gen_len + cfg.d_max + 1
     monkeypatch.setenv("DEL_PREFILL_ROWS", str(rows))
+    monkeypatch.setenv("DEL_PREFILL_FLASH", str(flash))     # 0: the vector-ALU attention with row groups
     wide, _ = gpu_context(cfg, max_context=ctxlen)
     monkeypatch.setenv("DEL_PREFILL_ROWS", "0")
     short, _ = gpu_context(cfg, max_context=ctxlen)
     monkeypatch.delenv("DEL_PREFILL_ROWS")
+    monkeypatch.delenv("DEL_PREFILL_FLASH")
     fw = wide.prefill(prompt)
     fs = short.prefill(prompt)
     ch = min(rows, (ctxlen + 15) // 16 * 16) // 16 * 16      # rows of a full wide pass; a ragged pass comes first
@@ -255,7 +260,7 @@ def test_wide_prefill_passes_match_the_oracle_and_the_short_passes(name, plen, r
         assert sw["alpha"] == ss["alpha"]
     oracle = Oracle(cfg, load_weights(cfg), max_context=ctxlen)
     rep = lockstep(cfg, oracle, wide, prompt, 12)
-    _check_report(rep, f"{name} P={plen} wide rows={rows}")
+    _check_report(rep, f"{name} P={plen} wide rows={rows} flash={flash}")
     wide.close()
     short.close()
 
