@@ -207,9 +207,17 @@ def del_round_sample_dynamic(ctx, E: int, tau: float, d_cap: int, temperature: f
 
 
 def del_debug_spec_sample(ctx, q_logits, p_logits, gamma: int, temperature: float, top_p: float,
-                          uniforms: Sequence[float]) -> Tuple[List[int], int, int]:
+                          uniforms: Sequence[float], vocab: int) -> Tuple[List[int], int, int]:
     """q_logits [gamma, vocab] and p_logits [gamma + 1, vocab]: contiguous float32 numpy arrays (host).
     Returns (drafts, u, last token)."""
+    if len(uniforms) < 2 * gamma + 1:
+        raise ValueError("need 2 * gamma + 1 uniform numbers")
+    for name, arr, rows in (("q_logits", q_logits, gamma), ("p_logits", p_logits, gamma + 1)):
+        if rows == 0:
+            continue
+        if (str(arr.dtype) != "float32" or not arr.flags["C_CONTIGUOUS"] or arr.ndim != 2 or arr.shape[0] < rows
+                or arr.shape[1] != vocab):
+            raise ValueError(f"{name}: need a C-contiguous float32 array of shape [>= {rows}, {vocab}]")
     un = (C.c_float * (2 * gamma + 1))(*[float(x) for x in uniforms[:2 * gamma + 1]])
     drafts = (C.c_int32 * max(1, gamma))()
     u, last = C.c_int32(), C.c_int32()
@@ -355,7 +363,8 @@ class DelContext:
         return del_round_sample_dynamic(self.ctx, E, tau, d_cap, temperature, top_p, uniforms)
 
     def spec_sample(self, q_logits, p_logits, gamma: int, temperature: float, top_p: float, uniforms):
-        return del_debug_spec_sample(self.ctx, q_logits, p_logits, gamma, temperature, top_p, uniforms)
+        return del_debug_spec_sample(self.ctx, q_logits, p_logits, gamma, temperature, top_p, uniforms,
+                                     self.cfg.vocab)
 
     def last_rows(self) -> int:
         """Rows the last pass filled; after a prefill the last prompt position is row last_rows() - 1."""

@@ -36,3 +36,16 @@ def test_error_strings_without_a_context():
     assert lib.del_strerror(0) == b"ok"
     assert b"order" in lib.del_strerror(2)
     assert lib.del_create(None, None, None) == 1       # DEL_E_ARG, no device touched
+
+
+def test_binding_rejects_misshapen_logits_before_any_device_call():
+    import numpy as np
+    import pytest
+    from paper_2504_05598_amd import binding
+    good = np.zeros((2, 10), dtype=np.float32)
+    for bad in (np.zeros((2, 10), dtype=np.float64), np.zeros((2, 9), dtype=np.float32),
+                np.zeros((10, 2), dtype=np.float32).T, np.zeros((1, 10), dtype=np.float32)):
+        with pytest.raises(ValueError):
+            binding.del_debug_spec_sample(None, good[:1].copy(), bad, 1, 1.0, 0.9, [0.1, 0.1, 0.1], 10)
+    with pytest.raises(ValueError):
+        binding.del_debug_spec_sample(None, good[:1].copy(), good, 1, 1.0, 0.9, [0.1], 10)
