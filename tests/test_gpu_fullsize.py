@@ -77,6 +77,31 @@ def test_speculative_equals_autoregressive_on_gpu(name, n):
         f"(draft-exiting) for {k3}/{n}; {len(rounds)} rounds, mean tokens/round {n / len(rounds):.2f} "
         f"({len(rounds_full)} rounds with draft-exiting)")
     assert all(1 <= e < cfg.n_layers and 0 <= g <= cfg.d_max for e, g, _ in rounds)
+    # sampled rounds at this shape: a one-token nucleus reproduces the greedy stream; with the paper's
+    # temperature and top_p the bookkeeping holds and a repeat gives the same tokens
+    from synthdata import gen_uniforms
+    _, E, g = ctx.prefill(prompt)
+    one = [ctx.sample_first(0.6, 1e-9, 0.5)]
+    for k in range(3):
+        gg = min(g, 4)
+        one += ctx.round_sample(E, gg, 0.6, 1e-9, gen_uniforms(cfg, 40 + k, 2 * gg + 1).tolist())
+        st = ctx.stats()
+        E, g = st["next_E"], st["next_gamma"]
+    _first_divergence_is_near_tie(ctx, cfg, prompt, vanilla, one)
+    runs = []
+    for _ in range(2):
+        _, E, g = ctx.prefill(prompt)
+        toks = [ctx.sample_first(0.6, 0.95, 0.77)]
+        T0 = ctx.state()[0]
+        for k in range(4):
+            out, gu, _ = ctx.round_sample_dynamic(E, ctx.stats()["tau"][E], cfg.d_max, 0.6, 0.95,
+                                                  gen_uniforms(cfg, 60 + k, 2 * cfg.d_max + 1).tolist())
+            assert 1 <= len(out) <= gu + 1 <= cfg.d_max + 1
+            toks += out
+            assert ctx.state() == (T0 + len(toks) - 1, toks[-1])
+            E = ctx.stats()["next_E"]
+        runs.append(toks)
+    assert runs[0] == runs[1]
     ctx.close()
 
 
