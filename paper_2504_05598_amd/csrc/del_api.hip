@@ -485,12 +485,14 @@ GemmP head_gemm(const del_ctx* ctx) {
 
 // Final norm + LM head + arg-max on one row of the hidden buffer (the draft's head).
 // Also the token's confidence (its soft-max probability, Section 4.4) into out_conf.
-del_status head_one(del_ctx* ctx, int layer, int row, int* out_id, float* out_conf) {
+// emb_next (optional): the token's embedding row goes there too (the next draft step's layer-0 input).
+del_status head_one(del_ctx* ctx, int layer, int row, int* out_id, float* out_conf, float* emb_next = nullptr) {
   GemmP p = head_gemm(ctx);
   p.X = ctx->hid_row(layer, row);
   del_status st = gemm(ctx, p, EPI_ARGMAX, 1, false);
   if (st != DEL_OK) return st;
-  HIPCHK(launch_argmax_finish(ctx->pval, ctx->pidx, ctx->psum, 1, ctx->NBv, out_id, out_conf, ctx->stream));
+  HIPCHK(launch_argmax_finish(ctx->pval, ctx->pidx, ctx->psum, 1, ctx->NBv, out_id, out_conf, ctx->stream,
+                              ctx->embed_t, ctx->wd, ctx->KTd, ctx->V, emb_next, ctx->d));
   return DEL_OK;
 }
 
@@ -1017,14 +1019,16 @@ static del_status round_impl(del_ctx* ctx, int E, int gamma, double tau, int32_t
   HIPCHK(hipEventRecord(ctx->ev[0], s));
   // one draft step: embed the pending token, layers 1..E on row i, optionally the head
   auto draft_step = [&](int i, bool with_head, bool copy_conf) -> del_status {
-    const int* tok = i == 0 ? ctx->state + 1 : ctx->draft_ids + (i - 1);
-    HIPCHK(launch_embed(ctx->embed_t, ctx->wd, ctx->KTd, ctx->V, tok, 1, ctx->hid_row(0, i), ctx->dpad, ctx->d, s));
+    // step 0 embeds the pending token; the head of step i - 1 has already left step i's embedding row
+    if (i == 0)
+      HIPCHK(launch_embed(ctx->embed_t, ctx->wd, ctx->KTd, ctx->V, ctx->state + 1, 1, ctx->hid_row(0, 0), ctx->dpad,
+                          ctx->d, s));
     for (int l = 1; l <= E; ++l) {
       del_status st = run_layer(ctx, l, i, 1, l > 1);
       if (st != DEL_OK) return st;
     }
     if (with_head) {
-      del_status st = head_one(ctx, E, i, ctx->draft_ids + i, dconf + i);
+      del_status st = head_one(ctx, E, i, ctx->draft_ids + i, dconf + i, ctx->hid_row(0, i + 1));
       if (st != DEL_OK) return st;
       if (copy_conf) HIPCHK(hipMemcpyAsync(ctx->step_host, dconf + i, 4, hipMemcpyDeviceToHost, s));
     }

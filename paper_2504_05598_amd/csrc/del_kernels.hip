@@ -1252,8 +1252,11 @@ __global__ void __launch_bounds__(256) embed_k(const void* Et, int KT, int vocab
 // Merge the per-row-block (max, index) partials of one logits row; lowest index wins ties.
 // With psum (per-block sums of exp(logit - block max)) also the confidence of the arg-max token:
 // its soft-max probability 1 / sum_b psum[b] * exp(max_b - max) (Section 4.4).
+// emb_out (optional, one row): the winner's embedding row goes there as fp32 (the next draft step's input),
+// read from the tiled embedding Et (kpl = 8 bf16 or 4 fp32 elements per lane and tile).
 __global__ void __launch_bounds__(256) argmax_finish_k(const float* pval, const int* pidx, const float* psum, int NB,
-                                                       int* out_ids, float* out_conf) {
+                                                       int* out_ids, float* out_conf, const void* Et, int kpl,
+                                                       int KT_e, int vocab, float* emb_out, int d_model) {
   __shared__ float sv[256];
   __shared__ int si[256];
   const int row = blockIdx.x, tid = threadIdx.x;
@@ -1275,7 +1278,17 @@ __global__ void __launch_bounds__(256) argmax_finish_k(const float* pval, const 
     __syncthreads();
   }
   const float M = sv[0];
-  if (tid == 0) out_ids[row] = si[0];
+  const int winner = si[0];
+  if (tid == 0) out_ids[row] = winner;
+  if (emb_out && row == 0) {
+    const int id = winner < 0 ? 0 : (winner >= vocab ? vocab - 1 : winner);
+    const int nb = id >> 4, r = id & 15, tk = 4 * kpl;
+    for (int k = tid; k < d_model; k += 256) {
+      const int kt = k / tk, g = (k % tk) / kpl, e = k % kpl;
+      const size_t off = (((size_t)nb * KT_e + kt) * 64 + g * 16 + r) * kpl + e;
+      emb_out[k] = kpl == 8 ? bf16_bits_to_f32(((const uint16_t*)Et)[off]) : ((const float*)Et)[off];
+    }
+  }
   if (psum && out_conf) {
     __syncthreads();
     float se = 0.f;
@@ -1301,22 +1314,30 @@ __global__ void __launch_bounds__(256) argmax_finish_k(const float* pval, const 
 // result: [0]=u, [1]=new T, [2]=pending, [3..3+gamma) drafts, then shadow [L][m]
 __global__ void accept_k(int* state, const int* draft_ids, int* shadow_ids, int L, int m, int E, int gamma,
                          int* result) {
-  if (threadIdx.x != 0 || blockIdx.x != 0) return;
+  // one wave: the drafts stand in for layer E's shadow tokens, then the first mismatch, then the copies
+  const int t = threadIdx.x;
+  if (blockIdx.x != 0 || t >= 64) return;
   int* srow = shadow_ids + (size_t)(E - 1) * m;
-  for (int i = 0; i < gamma; ++i) srow[i] = draft_ids[i];
+  for (int i = t; i < gamma; i += 64) srow[i] = draft_ids[i];
   const int* target = shadow_ids + (size_t)(L - 1) * m;
-  int u = gamma;
-  for (int i = 0; i < gamma; ++i) {
-    if (draft_ids[i] != target[i]) { u = i; break; }
-  }
+  // lane i < gamma looks at draft i (gamma <= 64 is checked by the launcher)
+  const bool miss = t < gamma && draft_ids[t] != target[t];
+  const unsigned long long mm = __ballot(miss);
+  const int u = mm ? __ffsll((long long)mm) - 1 : gamma;
   const int T = state[0] + u + 1;
-  state[0] = T;
-  state[1] = target[u];
-  result[0] = u;
-  result[1] = T;
-  result[2] = target[u];
-  for (int i = 0; i < gamma; ++i) result[3 + i] = draft_ids[i];
-  for (int i = 0; i < L * m; ++i) result[3 + gamma + i] = shadow_ids[i];
+  const int next = target[u];
+  __builtin_amdgcn_wave_barrier();
+  if (t == 0) {
+    state[0] = T;
+    state[1] = next;
+    result[0] = u;
+    result[1] = T;
+    result[2] = next;
+  }
+  for (int i = t; i < gamma; i += 64) result[3 + i] = draft_ids[i];
+  // layer E's row was rewritten above by this same wave; its stores precede these loads in program order
+  __threadfence_block();
+  for (int i = t; i < L * m; i += 64) result[3 + gamma + i] = shadow_ids[i];
 }
 
 __global__ void set_state_k(int* state, int add_T, int set_T, const int* pending_src, int pending_val) {
@@ -1627,13 +1648,17 @@ hipError_t launch_embed(const void* Et, int wdtype, int KT, int vocab, const int
 }
 
 hipError_t launch_argmax_finish(const float* pval, const int* pidx, const float* psum, int rows, int NB, int* out_ids,
-                                float* out_conf, hipStream_t s) {
-  hipLaunchKernelGGL(argmax_finish_k, dim3(rows), dim3(256), 0, s, pval, pidx, psum, NB, out_ids, out_conf);
+                                float* out_conf, hipStream_t s, const void* Et, int wdtype, int KT_e, int vocab,
+                                float* emb_out, int d_model) {
+  if (emb_out && (rows != 1 || !Et)) return hipErrorInvalidValue;
+  hipLaunchKernelGGL(argmax_finish_k, dim3(rows), dim3(256), 0, s, pval, pidx, psum, NB, out_ids, out_conf, Et,
+                     wdtype == 1 ? 8 : 4, KT_e, vocab, emb_out, d_model);
   return hipGetLastError();
 }
 
 hipError_t launch_accept(int* state, const int* draft_ids, int* shadow_ids, int L, int m, int E, int gamma,
                          int* result, hipStream_t s) {
+  if (gamma > 64) return hipErrorInvalidValue;
   hipLaunchKernelGGL(accept_k, dim3(1), dim3(64), 0, s, state, draft_ids, shadow_ids, L, m, E, gamma, result);
   return hipGetLastError();
 }
