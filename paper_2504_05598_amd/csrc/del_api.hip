@@ -3,6 +3,7 @@
 #include <hip/hip_runtime.h>
 
 #include <algorithm>
+#include <chrono>
 #include <cmath>
 #include <cstdio>
 #include <cstdlib>
@@ -116,7 +117,9 @@ struct del_ctx {
   float* pval = nullptr; int* pidx = nullptr; float* psum = nullptr;
   float* conf_dev = nullptr;   // [Rmax] shadow confidences, then [d_max+1] draft confidences
   float* conf_host = nullptr;  // pinned mirror
-  int* step_host = nullptr;    // pinned: (token id, confidence bits) of the last draft step
+  int* step_host = nullptr;    // pinned: (token id, confidence bits) of the last draft step; bytes 8..15: the
+                               // (sequence number, confidence) word a draft step's head writes for the polling host
+  unsigned note_seq = 0;
   int* state = nullptr; int* draft_ids = nullptr; int* shadow_ids = nullptr; int* result = nullptr;
   int* ids_dev = nullptr; int* result_host = nullptr;
   float* logits_dbg = nullptr; float* sink = nullptr;
@@ -486,13 +489,14 @@ GemmP head_gemm(const del_ctx* ctx) {
 // Final norm + LM head + arg-max on one row of the hidden buffer (the draft's head).
 // Also the token's confidence (its soft-max probability, Section 4.4) into out_conf.
 // emb_next (optional): the token's embedding row goes there too (the next draft step's layer-0 input).
-del_status head_one(del_ctx* ctx, int layer, int row, int* out_id, float* out_conf, float* emb_next = nullptr) {
+del_status head_one(del_ctx* ctx, int layer, int row, int* out_id, float* out_conf, float* emb_next = nullptr,
+                    unsigned long long* note = nullptr, unsigned seq = 0) {
   GemmP p = head_gemm(ctx);
   p.X = ctx->hid_row(layer, row);
   del_status st = gemm(ctx, p, EPI_ARGMAX, 1, false);
   if (st != DEL_OK) return st;
   HIPCHK(launch_argmax_finish(ctx->pval, ctx->pidx, ctx->psum, 1, ctx->NBv, out_id, out_conf, ctx->stream,
-                              ctx->embed_t, ctx->wd, ctx->KTd, ctx->V, emb_next, ctx->d));
+                              ctx->embed_t, ctx->wd, ctx->KTd, ctx->V, emb_next, ctx->d, note, seq));
   return DEL_OK;
 }
 
@@ -771,6 +775,7 @@ del_status del_create(const del_config* cfg, void* hip_stream, del_ctx** out) {
   CK(dmalloc(&ctx->conf_dev, (size_t)(Rmax + cfg->d_max + 1) * 4));
   CK(hipHostMalloc((void**)&ctx->conf_host, (size_t)(Rmax + cfg->d_max + 1) * 4, hipHostMallocDefault));
   CK(hipHostMalloc((void**)&ctx->step_host, 16, hipHostMallocDefault));
+  memset(ctx->step_host, 0, 16);
   CK(dmalloc(&ctx->state, 16));
   CK(hipMemsetAsync(ctx->state, 0, 16, ctx->stream));
   CK(dmalloc(&ctx->draft_ids, (size_t)(cfg->d_max + 1) * 4));
@@ -1028,9 +1033,14 @@ static del_status round_impl(del_ctx* ctx, int E, int gamma, double tau, int32_t
       if (st != DEL_OK) return st;
     }
     if (with_head) {
-      del_status st = head_one(ctx, E, i, ctx->draft_ids + i, dconf + i, ctx->hid_row(0, i + 1));
+      // a step the host decides on: its head writes (sequence number, confidence) straight into pinned
+      // memory, which the host polls; under graph replay (a baked-in number would be stale) a copy instead
+      const bool poll = copy_conf && !ctx->use_graphs;
+      unsigned long long* note = reinterpret_cast<unsigned long long*>(ctx->step_host) + 1;
+      del_status st = head_one(ctx, E, i, ctx->draft_ids + i, dconf + i, ctx->hid_row(0, i + 1),
+                               poll ? note : nullptr, poll ? ++ctx->note_seq : 0);
       if (st != DEL_OK) return st;
-      if (copy_conf) HIPCHK(hipMemcpyAsync(ctx->step_host, dconf + i, 4, hipMemcpyDeviceToHost, s));
+      if (copy_conf && !poll) HIPCHK(hipMemcpyAsync(ctx->step_host, dconf + i, 4, hipMemcpyDeviceToHost, s));
     }
     return DEL_OK;
   };
@@ -1057,9 +1067,27 @@ static del_status round_impl(del_ctx* ctx, int E, int gamma, double tau, int32_t
       // the host decides whether to go on: one small copy and a sync per step
       del_status st = run_segment(ctx, SEG_STEP, E, i, [&]() { return draft_step(i, true, true); });
       if (st != DEL_OK) return st;
-      HIPCHK(hipStreamSynchronize(s));
       float cf;
-      memcpy(&cf, ctx->step_host, 4);
+      if (!ctx->use_graphs) {
+        // poll the word the head writes; past a few milliseconds fall back to waiting for the stream
+        const volatile unsigned long long* note = reinterpret_cast<unsigned long long*>(ctx->step_host) + 1;
+        const auto t0 = std::chrono::steady_clock::now();
+        unsigned long long w = *note;
+        for (unsigned spins = 0; (unsigned)(w >> 32) != ctx->note_seq; ++spins) {
+          if ((spins & 1023u) == 1023u && std::chrono::steady_clock::now() - t0 > std::chrono::milliseconds(20)) {
+            HIPCHK(hipStreamSynchronize(s));
+            w = *note;
+            if ((unsigned)(w >> 32) != ctx->note_seq) return ctx->fail(hipErrorUnknown, "draft step left no confidence");
+            break;
+          }
+          w = *note;
+        }
+        const unsigned bits = (unsigned)w;
+        memcpy(&cf, &bits, 4);
+      } else {
+        HIPCHK(hipStreamSynchronize(s));
+        memcpy(&cf, ctx->step_host, 4);
+      }
       if ((double)cf < tau) {   // not appended; row i is the last row of the round
         gamma = i;
         stopped = true;

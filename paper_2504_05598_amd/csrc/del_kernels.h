@@ -119,10 +119,11 @@ hipError_t launch_embed(const void* Et, int wdtype, int KT, int vocab, const int
                         float* out, int ld, int d_model, hipStream_t s);
 // psum / out_conf may be null; out_conf[row] = soft-max probability of the arg-max token.
 // emb_out (optional, rows == 1): also writes the winner's embedding row (d_model floats) there.
+// note (optional, host-visible memory): row 0's confidence and `seq` as one 8-byte word (seq << 32 | bits).
 hipError_t launch_argmax_finish(const float* pval, const int* pidx, const float* psum, int rows, int NB,
                                 int* out_ids, float* out_conf, hipStream_t s, const void* Et = nullptr,
                                 int wdtype = 0, int KT_e = 0, int vocab = 0, float* emb_out = nullptr,
-                                int d_model = 0);
+                                int d_model = 0, unsigned long long* note = nullptr, unsigned seq = 0);
 hipError_t launch_accept(int* state, const int* draft_ids, int* shadow_ids, int L, int m, int E,
                          int gamma, int* result, hipStream_t s);
 hipError_t launch_set_state(int* state, int add_T, int set_T, const int* pending_src,

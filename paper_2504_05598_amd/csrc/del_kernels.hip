@@ -1256,7 +1256,8 @@ __global__ void __launch_bounds__(256) embed_k(const void* Et, int KT, int vocab
 // read from the tiled embedding Et (kpl = 8 bf16 or 4 fp32 elements per lane and tile).
 __global__ void __launch_bounds__(256) argmax_finish_k(const float* pval, const int* pidx, const float* psum, int NB,
                                                        int* out_ids, float* out_conf, const void* Et, int kpl,
-                                                       int KT_e, int vocab, float* emb_out, int d_model) {
+                                                       int KT_e, int vocab, float* emb_out, int d_model,
+                                                       unsigned long long* note, unsigned seq) {
   __shared__ float sv[256];
   __shared__ int si[256];
   const int row = blockIdx.x, tid = threadIdx.x;
@@ -1302,7 +1303,15 @@ __global__ void __launch_bounds__(256) argmax_finish_k(const float* pval, const 
       if (tid < s) sv[tid] += sv[tid + s];
       __syncthreads();
     }
-    if (tid == 0) out_conf[row] = 1.0f / sv[0];
+    if (tid == 0) {
+      const float cf = 1.0f / sv[0];
+      out_conf[row] = cf;
+      // for a host that polls pinned memory instead of waiting for the stream: sequence number and
+      // confidence in one 8-byte store
+      if (note && row == 0)
+        __hip_atomic_store(note, ((unsigned long long)seq << 32) | __float_as_uint(cf), __ATOMIC_RELAXED,
+                           __HIP_MEMORY_SCOPE_SYSTEM);
+    }
   }
 }
 
@@ -1649,10 +1658,10 @@ hipError_t launch_embed(const void* Et, int wdtype, int KT, int vocab, const int
 
 hipError_t launch_argmax_finish(const float* pval, const int* pidx, const float* psum, int rows, int NB, int* out_ids,
                                 float* out_conf, hipStream_t s, const void* Et, int wdtype, int KT_e, int vocab,
-                                float* emb_out, int d_model) {
-  if (emb_out && (rows != 1 || !Et)) return hipErrorInvalidValue;
+                                float* emb_out, int d_model, unsigned long long* note, unsigned seq) {
+  if ((emb_out && (rows != 1 || !Et)) || (note && !(psum && out_conf))) return hipErrorInvalidValue;
   hipLaunchKernelGGL(argmax_finish_k, dim3(rows), dim3(256), 0, s, pval, pidx, psum, NB, out_ids, out_conf, Et,
-                     wdtype == 1 ? 8 : 4, KT_e, vocab, emb_out, d_model);
+                     wdtype == 1 ? 8 : 4, KT_e, vocab, emb_out, d_model, note, seq);
   return hipGetLastError();
 }
 
