@@ -38,6 +38,32 @@ template <> struct WDec<4> {  // 4 fp32 in a uint4
   }
 };
 
+// One embedding row out of the tiled table as fp32: a row's k tile is four 16-byte pieces (lanes g*16 + r
+// of the tile), so every thread moves whole pieces.  kpl = 8 (bf16) or 4 (fp32) elements per piece.
+__device__ __forceinline__ void gather_embedding(const void* Et, int kpl, int KT, int id, float* out, int d_model,
+                                                 int tid, int nthr) {
+  const int nb = id >> 4, r = id & 15;
+  const int pieces = (d_model + kpl - 1) / kpl;
+  for (int c = tid; c < pieces; c += nthr) {
+    const int kt = c >> 2, g = c & 3;
+    const uint4 raw = ((const uint4*)Et)[((size_t)nb * KT + kt) * 64 + g * 16 + r];
+    float v[8];
+    if (kpl == 8) {
+      WDec<8>::dec(raw, v);
+    } else {
+      v[0] = __uint_as_float(raw.x); v[1] = __uint_as_float(raw.y);
+      v[2] = __uint_as_float(raw.z); v[3] = __uint_as_float(raw.w);
+    }
+    const int k0 = c * kpl;
+    if (k0 + kpl <= d_model) {
+      *(float4*)(out + k0) = make_float4(v[0], v[1], v[2], v[3]);
+      if (kpl == 8) *(float4*)(out + k0 + 4) = make_float4(v[4], v[5], v[6], v[7]);
+    } else {
+      for (int e = 0; e < kpl && k0 + e < d_model; ++e) out[k0 + e] = v[e];
+    }
+  }
+}
+
 template <bool BF16> __device__ __forceinline__ void kv_store(void* base, size_t idx, float v) {
   if (BF16) ((uint16_t*)base)[idx] = f32_to_bf16_rne(v);
   else ((float*)base)[idx] = v;
@@ -1234,19 +1260,10 @@ __global__ void __launch_bounds__(128) attn_combine_k(AttnP p) {
 template <int KPL>
 __global__ void __launch_bounds__(256) embed_k(const void* Et, int KT, int vocab, const int* ids, float* out, int ld,
                                                int d_model) {
-  constexpr int TK = 4 * KPL;
   const int row = blockIdx.x;
   int id = ids[row];
   id = id < 0 ? 0 : (id >= vocab ? vocab - 1 : id);
-  const int nb = id >> 4, r = id & 15;
-  for (int k = threadIdx.x; k < d_model; k += 256) {
-    const int kt = k / TK, g = (k % TK) / KPL, e = k % KPL;
-    const size_t off = (((size_t)nb * KT + kt) * 64 + g * 16 + r) * KPL + e;
-    float v;
-    if (KPL == 8) v = bf16_bits_to_f32(((const uint16_t*)Et)[off]);
-    else v = ((const float*)Et)[off];
-    out[(size_t)row * ld + k] = v;
-  }
+  gather_embedding(Et, KPL, KT, id, out + (size_t)row * ld, d_model, threadIdx.x, 256);
 }
 
 // Merge the per-row-block (max, index) partials of one logits row; lowest index wins ties.
@@ -1283,12 +1300,7 @@ __global__ void __launch_bounds__(256) argmax_finish_k(const float* pval, const 
   if (tid == 0) out_ids[row] = winner;
   if (emb_out && row == 0) {
     const int id = winner < 0 ? 0 : (winner >= vocab ? vocab - 1 : winner);
-    const int nb = id >> 4, r = id & 15, tk = 4 * kpl;
-    for (int k = tid; k < d_model; k += 256) {
-      const int kt = k / tk, g = (k % tk) / kpl, e = k % kpl;
-      const size_t off = (((size_t)nb * KT_e + kt) * 64 + g * 16 + r) * kpl + e;
-      emb_out[k] = kpl == 8 ? bf16_bits_to_f32(((const uint16_t*)Et)[off]) : ((const float*)Et)[off];
-    }
+    gather_embedding(Et, kpl, KT_e, id, emb_out, d_model, tid, 256);
   }
   if (psum && out_conf) {
     __syncthreads();
