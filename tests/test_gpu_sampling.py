@@ -45,7 +45,7 @@ def _logit_rows(rng, rows, vocab, kind):
     return np.ascontiguousarray(z, dtype=np.float32)
 
 
-@pytest.mark.parametrize("vocab", [3000, 32000, 128256])
+@pytest.mark.parametrize("vocab", [3000, 3001, 32000, 128256])
 def test_sampling_arithmetic_is_exact_on_given_logits(vocab):
     ctx, cfg = _ctx_for_vocab(vocab)
     rng = np.random.default_rng(vocab)
