@@ -113,7 +113,8 @@ struct del_ctx {
   uint16_t* xs_layer = nullptr; uint16_t* xs_shadow = nullptr; float* rowscale = nullptr;
   uint16_t* xs_h = nullptr; uint16_t* xs_attn = nullptr; uint16_t* xs_h1 = nullptr; uint16_t* xs_act = nullptr;
   float* ssq_h = nullptr; float* ssq_h1 = nullptr;
-  float* PM = nullptr; float* PL = nullptr; float* PA = nullptr; int nch_max = 0, attn_ct = 64, attn_S = 0, attn_dec_rows = 16;   // attn_S > 0: register decode kernel with S splits
+  float* PM = nullptr; float* PL = nullptr; float* PA = nullptr; int nch_max = 0, attn_ct = 64, attn_S = 0, attn_dec_rows = 16;
+  int attn_direct_rows = 0;   // passes of at least this many rows (> 1): one context split per row, no merge kernel   // attn_S > 0: register decode kernel with S splits
   float* pval = nullptr; int* pidx = nullptr; float* psum = nullptr;
   float* conf_dev = nullptr;   // [Rmax] shadow confidences, then [d_max+1] draft confidences
   float* conf_host = nullptr;  // pinned mirror
@@ -341,7 +342,10 @@ del_status run_layer(del_ctx* ctx, int l, int row0, int m, bool chained) {
   // partials are merged by the O projection itself, several rows' by the merge kernel
   const bool dec_any = ctx->attn_S > 0 && m <= ctx->attn_dec_rows;
   const bool dec = dec_any && m == 1;
-  if (dec_any) {
+  if (dec_any && m > 1 && ctx->attn_direct_rows > 0 && m >= ctx->attn_direct_rows) {
+    a.nsplit = -1;   // one split per row: the kernel writes the output rows and their tiles itself
+    HIPCHK(launch_attention_decode(a, 1, ctx->stream));
+  } else if (dec_any) {
     HIPCHK(launch_attention_decode(a, ctx->attn_S, ctx->stream));
     if (m > 1) {
       a.nsplit = ctx->attn_S;
@@ -671,6 +675,12 @@ del_status del_create(const del_config* cfg, void* hip_stream, del_ctx** out) {
     if (const char* e = getenv("DEL_ATTN_SPLITS")) {
       const int v = atoi(e);
       if (v >= 0 && v <= std::min(16, ctx->nch_max)) ctx->attn_S = v;   // 0: staged kernels everywhere
+    }
+    // enough rows give enough work-groups (rows x kv heads >= 192) without splitting the context
+    ctx->attn_direct_rows = std::max(2, ceil_div(192, ctx->nkv));
+    if (const char* e = getenv("DEL_ATTN_DIRECT_ROWS")) {
+      const int v = atoi(e);
+      if (v >= 0 && v <= 64) ctx->attn_direct_rows = v;   // 0: always split and merge
     }
     if (const char* e = getenv("DEL_ATTN_DEC_ROWS")) {
       const int v = atoi(e);

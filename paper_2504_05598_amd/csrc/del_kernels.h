@@ -85,7 +85,8 @@ struct AttnP {
   int nch_max;
   int ct;                       // cache rows per work-group (16, 32, 48 or 64)
   int qb;                       // query rows per batch (set by the launcher)
-  int nsplit;                   // > 0: the partials come from the decode kernel, this many per row
+  int nsplit;                   // > 0: the partials come from the decode kernel, this many per row;
+                                // < 0 (decode kernel, one split): write O / XsOut directly, no partials
   float* O; int ldo;            // combined output [m][n_q*hd]
   uint16_t* XsOut;              // optional: the same rows as split tiles (input of the O projection)
   long long xs_cb_stride;       // 16-bit elements between the tiles of consecutive blocks of 16 token rows

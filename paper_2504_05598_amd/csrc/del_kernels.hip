@@ -1074,7 +1074,23 @@ __global__ void __launch_bounds__(512) attn_decode_k(AttnP p) {
       L += c * sl[w][g];
       A += c * sa[w][g][d];
     }
-    const size_t prow = ((size_t)(mi0 + g / G) * p.n_q + kvh * G + g % G) * p.nch_max + split;
+    const int mi = mi0 + g / G, h = kvh * G + g % G;
+    if (S == 1 && p.nsplit < 0) {
+      // a single split and the caller wants the result itself: output row and its split tile, no partials
+      const float o = A / L;
+      p.O[(size_t)mi * p.ldo + h * HD + d] = o;
+      if (p.XsOut) {
+        const int k = h * HD + d;
+        const uint16_t hi = f32_to_bf16_rne(o);
+        const uint16_t lo = f32_to_bf16_rne(o - bf16_bits_to_f32(hi));
+        uint16_t* dst = p.XsOut + (size_t)(mi >> 4) * p.xs_cb_stride + (size_t)(k >> 5) * 1024 +
+                        (((k & 31) >> 3) * 16 + (mi & 15)) * 8 + (k & 7);
+        dst[0] = hi;
+        dst[512] = lo;
+      }
+      continue;
+    }
+    const size_t prow = ((size_t)mi * p.n_q + h) * p.nch_max + split;
     if (d == 0) { p.PM[prow] = M; p.PL[prow] = L; }
     p.PA[prow * HD + d] = A;
   }

@@ -280,3 +280,18 @@ def test_statistics_seeded_from_every_prompt_position():
     assert ctx.stats()["rounds"] > 0
     _check_report(rep, "mini_gqa window=77")
     ctx.close()
+
+
+@pytest.mark.parametrize("name", ["tiny", "mini_gqa", "mini_mha", "mini_g8"])
+def test_unsplit_attention_for_multi_row_passes(name, monkeypatch):
+    """Passes of several rows with one context split per row (the attention kernel writes its output rows
+    and their tiles itself, no merge kernel): forced here for every pass of two or more rows."""
+    from gpu_harness import lockstep
+    monkeypatch.setenv("DEL_ATTN_DIRECT_ROWS", "2")
+    monkeypatch.setenv("DEL_PREFILL_ROWS", "0")        # 16-row prefill passes take this path too
+    cfg, ctx, oracle = _setup(name)
+    monkeypatch.delenv("DEL_ATTN_DIRECT_ROWS")
+    monkeypatch.delenv("DEL_PREFILL_ROWS")
+    rep = lockstep(cfg, oracle, ctx, gen_prompt(cfg).tolist(), cfg.gen_len)
+    _check_report(rep, f"{name} unsplit attention")
+    ctx.close()
