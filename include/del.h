@@ -121,7 +121,9 @@ del_status del_round(del_ctx* ctx, int32_t E, int32_t gamma, int32_t* out_tokens
  * tau of layer E from del_layer_stats.  The hidden state of the stopping step is the round's last
  * row, so no extra pass over the first E layers is needed.  out_tokens has room for d_cap+1 ids.
  * *gamma_used = tokens drafted, *stopped_early = 1 if the loop stopped on low confidence (either
- * may be NULL).  The host reads one confidence per draft step (a 4-byte copy and a stream sync). */
+ * may be NULL).  The host decides after every draft step: the step's head kernel writes one 8-byte word
+ * (sequence number, confidence) into pinned host memory, which the host polls (bounded; past 20 ms it
+ * falls back to waiting for the stream), so a draft step costs one host round trip. */
 del_status del_round_dynamic(del_ctx* ctx, int32_t E, double tau, int32_t d_cap, int32_t* out_tokens,
                              int32_t* n_out, int32_t* gamma_used, int32_t* stopped_early);
 
@@ -150,7 +152,8 @@ typedef struct {
 } del_stats;
 del_status del_layer_stats(const del_ctx* ctx, del_stats* out);
 /* Import S_n and S_c, and S_tcs / S_fcs when both are non-NULL (resume, or re-synchronise a
- * test harness); recomputes alpha, tau and the next (E, gamma).  Nothing else is read. */
+ * test harness); recomputes alpha, tau and the next (E, gamma).  Nothing else is read.
+ * Errors: DEL_E_ARG for S_n <= 0 or a negative sum; the statistics are then unchanged. */
 del_status del_set_layer_stats(del_ctx* ctx, const del_stats* in);
 
 /* Wall time of the segments of the last round, from HIP events on the stream. */

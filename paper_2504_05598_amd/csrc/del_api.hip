@@ -115,6 +115,8 @@ struct del_ctx {
   float* ssq_h = nullptr; float* ssq_h1 = nullptr;
   float* PM = nullptr; float* PL = nullptr; float* PA = nullptr; int nch_max = 0, attn_ct = 64, attn_S = 0, attn_dec_rows = 16;
   int attn_direct_rows = 0;   // passes of at least this many rows (> 1): one context split per row, no merge kernel   // attn_S > 0: register decode kernel with S splits
+  bool verify_flash = true;   // passes of 2..16 rows: attention on the matrix cores, split over the context
+  int verify_flash_waves = 1024;   // waves (splits x query heads) that kernel aims for
   float* pval = nullptr; int* pidx = nullptr; float* psum = nullptr;
   float* conf_dev = nullptr;   // [Rmax] shadow confidences, then [d_max+1] draft confidences
   float* conf_host = nullptr;  // pinned mirror
@@ -244,15 +246,22 @@ del_status gemm(del_ctx* ctx, GemmP p, int epi, int m, bool mfma) {
   const int waves = ctx->pick_waves(p.NB, p.KT);
   const int64_t wbytes = (int64_t)p.NB * p.KT * 1024;
   if (mfma) {
-    HIPCHK(launch_prep_split(p.X, m, m, 0, p.ldx, p.K, p.KT, p.gain, p.rms, p.eps, ctx->xs_layer, ctx->rowscale,
-                             ctx->stream));
-    p.Xs = ctx->xs_layer;
-    p.rowscale = p.rms ? ctx->rowscale : nullptr;
-    p.M = m;
-    const int pr = prof_begin(ctx, 1, epi, m, wbytes);
-    if (pr >= 0) { p.ev_start = ctx->prof_ev[2 * pr]; p.ev_stop = ctx->prof_ev[2 * pr + 1]; }
-    HIPCHK(launch_gemm_mfma(p, epi, waves, 1, ctx->stream));
-    prof_end(ctx, pr);
+    // blocks of up to 16 token rows, each split into tiles and multiplied on its own
+    for (int off = 0; off < m; off += 16) {
+      const int mb = std::min(16, m - off);
+      GemmP q = p;
+      q.X = p.X + (size_t)off * p.ldx;
+      if (q.Y) q.Y = p.Y + (size_t)off * p.ldy;
+      HIPCHK(launch_prep_split(q.X, mb, mb, 0, q.ldx, q.K, q.KT, q.gain, q.rms, q.eps, ctx->xs_layer, ctx->rowscale,
+                               ctx->stream));
+      q.Xs = ctx->xs_layer;
+      q.rowscale = q.rms ? ctx->rowscale : nullptr;
+      q.M = mb;
+      const int pr = prof_begin(ctx, 1, epi, mb, wbytes);
+      if (pr >= 0) { q.ev_start = ctx->prof_ev[2 * pr]; q.ev_stop = ctx->prof_ev[2 * pr + 1]; }
+      HIPCHK(launch_gemm_mfma(q, epi, waves, 1, ctx->stream));
+      prof_end(ctx, pr);
+    }
     return DEL_OK;
   }
   int off = 0;
@@ -301,7 +310,8 @@ del_status gemm_mf(del_ctx* ctx, GemmP p, int epi, int m) {
 // split tiles of this layer's (gained) input in xs_h and their sums of squares in ssq_h.
 del_status run_layer(del_ctx* ctx, int l, int row0, int m, bool chained) {
   const int li = l - 1;
-  const bool mf = ctx->cfg.use_mfma && ctx->wd == DEL_DTYPE_BF16 && m > 1;
+  // more than 16 rows in a round (gamma > 15) take the wide path (see layer_pass) or, failing that, the vector path
+  const bool mf = ctx->cfg.use_mfma && ctx->wd == DEL_DTYPE_BF16 && m > 1 && m <= 16;
   char* base = ctx->arena + (size_t)li * ctx->layer_stride;
   float* hin = ctx->hid_row(l - 1, row0);
   float* hout = ctx->hid_row(l, row0);
@@ -315,6 +325,10 @@ del_status run_layer(del_ctx* ctx, int l, int row0, int m, bool chained) {
   p.n_q = ctx->nq; p.n_kv = ctx->nkv; p.hd = ctx->hd; p.Tcap = ctx->Tcap;
   p.state = ctx->state; p.row_off = row0; p.rope = ctx->rope;
   void* Kc = p.Kc; void* Vc = p.Vc;
+  // the feature-major copy of the values is kept by every pass, so that the matrix-core attention
+  // kernels can be used at any point of a generation
+  void* VcT = ctx->vct ? ctx->vct + (size_t)li * ctx->vct_layer_bytes : nullptr;
+  p.VcT = VcT; p.TcapT = ctx->TcapT;
   if (mf) {
     p.Xs = ctx->xs_h;
     if (chained) {
@@ -342,7 +356,20 @@ del_status run_layer(del_ctx* ctx, int l, int row0, int m, bool chained) {
   // partials are merged by the O projection itself, several rows' by the merge kernel
   const bool dec_any = ctx->attn_S > 0 && m <= ctx->attn_dec_rows;
   const bool dec = dec_any && m == 1;
-  if (dec_any && m > 1 && ctx->attn_direct_rows > 0 && m >= ctx->attn_direct_rows) {
+  if (mf && VcT && ctx->verify_flash && row0 == 0) {
+    // several rows (verify): on the matrix cores, the cache read once for all rows, split over the
+    // context so that splits x query heads waves are in flight; then the merge
+    // the split plan depends on the cache capacity only, never on the current length: a round's launch
+    // sequence (and its rounding) is then a function of (E, gamma) alone; spans past the context are empty
+    int rps = ceil_div((int64_t)ctx->Tcap * ctx->nq, ctx->verify_flash_waves);
+    rps = std::max(32, ceil_div(rps, 32) * 32);
+    while (ceil_div(ctx->Tcap, rps) > ctx->nch_max) rps += 32;
+    const int S = ceil_div(ctx->Tcap, rps);
+    a.VcT = VcT; a.TcapT = ctx->TcapT;
+    HIPCHK(launch_attention_flash_split(a, S, rps, ctx->stream));
+    a.nsplit = S;
+    HIPCHK(launch_attention_merge(a, ctx->stream));
+  } else if (dec_any && m > 1 && ctx->attn_direct_rows > 0 && m >= ctx->attn_direct_rows) {
     a.nsplit = -1;   // one split per row: the kernel writes the output rows and their tiles itself
     HIPCHK(launch_attention_decode(a, 1, ctx->stream));
   } else if (dec_any) {
@@ -480,6 +507,13 @@ del_status run_layer_wide(del_ctx* ctx, int l, int m, bool chained) {
     p.ssq_out = ctx->ssq_h;
   }
   return wide(p, EPI_RESID);
+}
+
+// Transformer_l on rows [0, m) of a round's verify pass: up to 16 rows on the skinny matrix-core GEMMs
+// (or the vector path); more (gamma > 15) as one wide pass where the context has one, else on the vector path.
+del_status layer_pass(del_ctx* ctx, int l, int m, bool chained) {
+  if (m > 16 && ctx->prows >= m && ctx->cfg.use_mfma && ctx->wd == DEL_DTYPE_BF16) return run_layer_wide(ctx, l, m, chained);
+  return run_layer(ctx, l, 0, m, chained);
 }
 
 GemmP head_gemm(const del_ctx* ctx) {
@@ -681,6 +715,11 @@ del_status del_create(const del_config* cfg, void* hip_stream, del_ctx** out) {
     if (const char* e = getenv("DEL_ATTN_DIRECT_ROWS")) {
       const int v = atoi(e);
       if (v >= 0 && v <= 64) ctx->attn_direct_rows = v;   // 0: always split and merge
+    }
+    if (const char* e = getenv("DEL_VERIFY_FLASH")) ctx->verify_flash = atoi(e) != 0;
+    if (const char* e = getenv("DEL_VERIFY_FLASH_WAVES")) {
+      const int v = atoi(e);
+      if (v >= 32 && v <= 16384) ctx->verify_flash_waves = v;
     }
     if (const char* e = getenv("DEL_ATTN_DEC_ROWS")) {
       const int v = atoi(e);
@@ -910,6 +949,7 @@ del_status del_prefill(del_ctx* ctx, const int32_t* prompt, int32_t n_prompt, in
     const int mc = (start == 0 && P % CH != 0) ? P % CH : CH;
     // with the feature-major value copy every pass must keep it filled: all passes take the wide path
     const bool widep = ctx->prows > 0 && (mc > 16 || ctx->vct);
+    ctx->T = start;   // host mirror of the KV length this pass starts from
     HIPCHK(launch_embed(ctx->embed_t, ctx->wd, ctx->KTd, ctx->V, ctx->ids_dev + start, mc, ctx->hid_row(0, 0),
                         ctx->dpad, ctx->d, ctx->stream));
     for (int l = 1; l <= L; ++l) {
@@ -1111,7 +1151,7 @@ static del_status round_impl(del_ctx* ctx, int E, int gamma, double tau, int32_t
   {
     del_status st = run_segment(ctx, SEG_VERIFY, E, m, [&]() -> del_status {
       for (int l = E + 1; l <= L; ++l) {
-        del_status st2 = run_layer(ctx, l, 0, m, l > E + 1);
+        del_status st2 = layer_pass(ctx, l, m, l > E + 1);
         if (st2 != DEL_OK) return st2;
       }
       return DEL_OK;
@@ -1236,7 +1276,7 @@ static del_status round_sample_impl(del_ctx* ctx, int E, int gamma, double tau, 
   HIPCHK(hipEventRecord(ctx->ev[1], s));
   // ---- verify: the gamma+1 exit states through layers E+1..L
   for (int l = E + 1; l <= L; ++l) {
-    del_status st = run_layer(ctx, l, 0, m, l > E + 1);
+    del_status st = layer_pass(ctx, l, m, l > E + 1);
     if (st != DEL_OK) return st;
   }
   HIPCHK(hipEventRecord(ctx->ev[2], s));
@@ -1350,15 +1390,19 @@ del_status del_layer_stats(const del_ctx* ctx, del_stats* out) {
 del_status del_set_layer_stats(del_ctx* ctx, const del_stats* in) {
   if (!ctx || !in || !in->S_c) return DEL_E_ARG;
   if (!(in->S_n > 0.0)) return DEL_E_ARG;
-  for (int l = 1; l <= ctx->L; ++l)
+  // every input is checked before anything is changed: an error leaves the policy as it was
+  const bool conf = in->S_tcs && in->S_fcs;
+  for (int l = 1; l <= ctx->L; ++l) {
     if (!(in->S_c[l] >= 0.0)) return DEL_E_ARG;
-  for (int l = 1; l <= ctx->L; ++l) ctx->pol.Sc[l] = in->S_c[l];
-  if (in->S_tcs && in->S_fcs)
-    for (int l = 1; l <= ctx->L; ++l) {
-      if (!(in->S_tcs[l] >= 0.0) || !(in->S_fcs[l] >= 0.0)) return DEL_E_ARG;
+    if (conf && (!(in->S_tcs[l] >= 0.0) || !(in->S_fcs[l] >= 0.0))) return DEL_E_ARG;
+  }
+  for (int l = 1; l <= ctx->L; ++l) {
+    ctx->pol.Sc[l] = in->S_c[l];
+    if (conf) {
       ctx->pol.St[l] = in->S_tcs[l];
       ctx->pol.Sf[l] = in->S_fcs[l];
     }
+  }
   ctx->pol.Sn = in->S_n;
   ctx->pol.select();
   return DEL_OK;

@@ -115,6 +115,9 @@ hipError_t launch_attention_merge(const AttnP& p, hipStream_t s);
 // Causal attention of p.m token rows on the matrix cores (bf16 caches, head_dim 64 or 128); writes O and
 // XsOut directly (no partials).  Needs VcT.
 hipError_t launch_attention_flash(const AttnP& p, hipStream_t s);
+// The same for m <= 16 token rows (verify), split over the context into S spans of at least rps_min cache rows
+// (a multiple of 32): one partial per (row, head, split) in PM / PL / PA, to be merged by launch_attention_merge.
+hipError_t launch_attention_flash_split(const AttnP& p, int S, int rps_min, hipStream_t s);
 bool attention_decode_supported(int kvdtype, int hd, int G);
 hipError_t launch_embed(const void* Et, int wdtype, int KT, int vocab, const int* ids, int m,
                         float* out, int ld, int d_model, hipStream_t s);

@@ -1234,6 +1234,113 @@ __global__ void __launch_bounds__(256) attn_flash_k(AttnP p) {
   }
 }
 
+// ---------------------------------------------------------------------------------------
+// The same matrix-core attention for a few token rows (the verify pass: m <= 16 rows, Section 2
+// "verifies all draft tokens in parallel"), split over the context: one wave = all m queries of
+// one query head against one span of cache rows, so the cache is read once for all rows and there
+// are (splits x query heads) waves to keep in flight.  Each wave leaves a soft-max partial
+// (max, sum, weighted values) per (token row, head, split); attn_combine_k merges them.
+// ---------------------------------------------------------------------------------------
+template <int HD>
+__global__ void __launch_bounds__(256) attn_flash_split_k(AttnP p, int S, int rps_min) {
+  constexpr int KT = HD / 32, DT = HD / 16;
+  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63, g = lane >> 4, qi = lane & 15;
+  const int split = blockIdx.x * 4 + wave;
+  if (split >= S) return;                      // wave-uniform; the kernel has no barriers
+  const int h = blockIdx.y, kvh = h / (p.n_q / p.n_kv);
+  const int nrow = p.m;                        // <= 16, checked by the launcher
+  const int T0 = p.state[0] + p.row_off;       // cache position of token row 0
+  const int pos = T0 + qi;                     // this lane's query attends cache rows <= pos
+  const int t_end = T0 + nrow;                 // cache rows the pass needs: [0, t_end)
+  // rows per split: whole tiles of 32, at least what the launcher planned for
+  const int rps = max(rps_min, ((t_end + S - 1) / S + 31) / 32 * 32);
+  const int t_lo = split * rps, t_hi = min(t_end, t_lo + rps);
+  uint4 qh[KT], ql[KT];
+  {
+    const float scale = 1.0f / sqrtf((float)HD);
+    const float* qp = p.Q + (size_t)min(qi, nrow - 1) * p.ldq + (size_t)h * HD + 8 * g;
+#pragma unroll
+    for (int kt = 0; kt < KT; ++kt) {
+      const float4 a = *(const float4*)(qp + 32 * kt), b = *(const float4*)(qp + 32 * kt + 4);
+      const float v[8] = {a.x * scale, a.y * scale, a.z * scale, a.w * scale,
+                          b.x * scale, b.y * scale, b.z * scale, b.w * scale};
+      split8(v, qh[kt], ql[kt]);
+    }
+  }
+  floatx4 o[DT];
+#pragma unroll
+  for (int dt = 0; dt < DT; ++dt) o[dt] = (floatx4){0.f, 0.f, 0.f, 0.f};
+  float mrun = -INFINITY, lrun = 0.f;
+  const uint16_t* Kb = (const uint16_t*)p.Kc + (size_t)kvh * p.Tcap * HD + 8 * g;
+  const uint16_t* Vt = (const uint16_t*)p.VcT + ((size_t)kvh * HD + qi) * p.TcapT + 8 * g;
+  const int rho = 8 * (qi >> 2) + (qi & 3);
+  for (int t0 = t_lo; t0 < t_hi; t0 += 32) {
+    floatx4 s0 = {0.f, 0.f, 0.f, 0.f}, s1 = {0.f, 0.f, 0.f, 0.f};
+    // rows past the pass's last one are read from that last row and masked below
+    const uint16_t* k0 = Kb + (size_t)min(t0 + rho, t_end - 1) * HD;
+    const uint16_t* k1 = Kb + (size_t)min(t0 + rho + 4, t_end - 1) * HD;
+    uint4 a0[KT], a1[KT], av[DT];
+#pragma unroll
+    for (int kt = 0; kt < KT; ++kt) {
+      a0[kt] = *(const uint4*)(k0 + 32 * kt);
+      a1[kt] = *(const uint4*)(k1 + 32 * kt);
+    }
+#pragma unroll
+    for (int dt = 0; dt < DT; ++dt) av[dt] = *(const uint4*)(Vt + (size_t)(16 * dt) * p.TcapT + t0);
+#pragma unroll
+    for (int kt = 0; kt < KT; ++kt) {
+      const bf16x8 x0 = __builtin_bit_cast(bf16x8, a0[kt]), x1 = __builtin_bit_cast(bf16x8, a1[kt]);
+      const bf16x8 bh = __builtin_bit_cast(bf16x8, qh[kt]), bl = __builtin_bit_cast(bf16x8, ql[kt]);
+      s0 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(x0, bh, s0, 0, 0, 0);
+      s1 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(x1, bh, s1, 0, 0, 0);
+      s0 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(x0, bl, s0, 0, 0, 0);
+      s1 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(x1, bl, s1, 0, 0, 0);
+    }
+    // this lane: scores of cache rows t0 + 8g + e, e = 0..7, for query qi
+    float sv[8] = {s0[0], s0[1], s0[2], s0[3], s1[0], s1[1], s1[2], s1[3]};
+    float mx = -INFINITY;
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+      if (t0 + 8 * g + e > pos) sv[e] = -INFINITY;
+      mx = fmaxf(mx, sv[e]);
+    }
+    mx = fmaxf(mx, __shfl_xor(mx, 16));
+    mx = fmaxf(mx, __shfl_xor(mx, 32));
+    // a split may hold no row this query may see (the rows of later tokens only): everything stays
+    // at (max = -inf, sum = 0, values = 0), which the merge gives weight 0
+    const float mnew = fmaxf(mrun, mx);
+    const float c = mrun > -INFINITY ? expf(mrun - mnew) : 0.f;
+    float pv[8], ls = 0.f;
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+      pv[e] = sv[e] > -INFINITY ? expf(sv[e] - mnew) : 0.f;
+      ls += pv[e];
+    }
+    ls += __shfl_xor(ls, 16);
+    ls += __shfl_xor(ls, 32);
+    lrun = lrun * c + ls;
+    mrun = mnew;
+    uint4 ph, pl;
+    split8(pv, ph, pl);
+    const bf16x8 bh = __builtin_bit_cast(bf16x8, ph), bl = __builtin_bit_cast(bf16x8, pl);
+#pragma unroll
+    for (int dt = 0; dt < DT; ++dt) {
+#pragma unroll
+      for (int j = 0; j < 4; ++j) o[dt][j] *= c;
+      const bf16x8 x = __builtin_bit_cast(bf16x8, av[dt]);
+      o[dt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(x, bh, o[dt], 0, 0, 0);
+      o[dt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(x, bl, o[dt], 0, 0, 0);
+    }
+  }
+  if (qi >= nrow) return;
+  // this lane: features 16*dt + 4g + j of head h for token row qi, as an unnormalised partial
+  const size_t prow = ((size_t)qi * p.n_q + h) * p.nch_max + split;
+  if (g == 0) { p.PM[prow] = mrun; p.PL[prow] = lrun; }
+  float* pa = p.PA + prow * HD + 4 * g;
+#pragma unroll
+  for (int dt = 0; dt < DT; ++dt) *(float4*)(pa + 16 * dt) = make_float4(o[dt][0], o[dt][1], o[dt][2], o[dt][3]);
+}
+
 __global__ void __launch_bounds__(128) attn_combine_k(AttnP p) {
   const int row = blockIdx.x;  // mi * n_q + h
   const int d = threadIdx.x;
@@ -1584,6 +1691,7 @@ hipError_t launch_head_gemm(const void* Wt, int NB, int KT, int N, const uint16_
                             hipEvent_t ev_stop) {
   if (NB <= 0 || KT <= 0 || R <= 0) return hipErrorInvalidValue;
   const int CB = (R + 15) / 16, NS = (NB + HG_W - 1) / HG_W;
+  *n_slabs = NS;
   const size_t lds = (size_t)2 * HG_CB * 128 * sizeof(uint4);
   static bool raised = false;
   if (!raised) {
@@ -1597,7 +1705,6 @@ hipError_t launch_head_gemm(const void* Wt, int NB, int KT, int N, const uint16_
   else
     hipLaunchKernelGGL(head_gemm_k, dim3(NS, (CB + HG_CB - 1) / HG_CB), dim3(512), lds, s, (const uint4*)Wt, NB, KT, N,
                        (const uint4*)Xs, CB, R, rowscale, pval, pidx, psum, NS);
-  *n_slabs = NS;
   return hipGetLastError();
 }
 
@@ -1645,6 +1752,18 @@ hipError_t launch_attention_flash(const AttnP& p, hipStream_t s) {
   dim3 grid((p.m + 63) / 64, p.n_q), block(256);
   if (p.hd == 128) hipLaunchKernelGGL((attn_flash_k<128>), grid, block, 0, s, p);
   else hipLaunchKernelGGL((attn_flash_k<64>), grid, block, 0, s, p);
+  return hipGetLastError();
+}
+
+// Few token rows (m <= 16) on the matrix cores, S context splits of at least rps_min rows (a multiple of 32)
+// each: writes S partials per (row, head); the caller merges them with launch_attention_merge (nsplit = S).
+hipError_t launch_attention_flash_split(const AttnP& p, int S, int rps_min, hipStream_t s) {
+  if (p.m < 1 || p.m > 16 || p.kvdtype != 1 || !p.VcT || p.TcapT % 32 != 0 || p.TcapT < p.Tcap || p.n_q % p.n_kv != 0 ||
+      (p.hd != 64 && p.hd != 128) || S < 1 || S > p.nch_max || rps_min < 32 || rps_min % 32 != 0)
+    return hipErrorInvalidValue;
+  dim3 grid((S + 3) / 4, p.n_q), block(256);
+  if (p.hd == 128) hipLaunchKernelGGL((attn_flash_split_k<128>), grid, block, 0, s, p, S, rps_min);
+  else hipLaunchKernelGGL((attn_flash_split_k<64>), grid, block, 0, s, p, S, rps_min);
   return hipGetLastError();
 }
 

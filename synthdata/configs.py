@@ -92,6 +92,9 @@ CONFIGS = {
     # one kv head for eight query heads, n_q*head_dim != d_model
     "mini_g8": ModelConfig("mini_g8", 4, 256, 8, 1, 128, 704, 3000, 1e4, False, "bf16", 0.6,
                            53, 40, 7, 14, norm_gain_std=0.1),
+    # the paper's cap on the speculation length (Appendix B.2: d_max = 18): rounds of more than 16 rows
+    "mini_d18": ModelConfig("mini_d18", 5, 512, 8, 2, 64, 1384, 5000, 1e4, False, "bf16", 0.6,
+                            40, 64, 18, 15, norm_gain_std=0.1),
     "mini_fp32": ModelConfig("mini_fp32", 3, 192, 6, 2, 32, 520, 3000, 1e4, False, "fp32", 0.6,
                              21, 24, 5, 13, norm_gain_std=0.1),
 }

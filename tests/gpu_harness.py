@@ -378,3 +378,124 @@ def lockstep_sample(cfg, oracle: Oracle, ctx: DelContext, prompt, n_tokens, temp
     rep.tokens = emitted
     rep.decisions = decisions
     return rep
+
+
+# ---- replay of stored oracle records (full-size shapes) ------------------------------------
+# tests/golden/make_fullsize_records.py runs the oracle on the CPU ahead of time and stores what
+# lockstep() compares round by round; here the library is driven through the same rounds and held
+# to the same rules (exact ids / counts / selection outside near-ties, re-prefill + statistics
+# import after a tolerated flip).  Hidden rows are stored for three layers of a few rounds.
+
+def load_records(name):
+    import json
+    import os
+    path = os.path.join(os.path.dirname(os.path.abspath(__file__)), "golden", f"fullsize_{name}.npz")
+    z = np.load(path)
+    rec = {k: z[k] for k in z.files}
+    rec["meta"] = json.loads(str(z["meta"]))
+    return rec
+
+
+def _resync_records(ctx: DelContext, prompt, emitted, S_c, S_n, S_tcs, S_fcs, T, pending, rep):
+    first, _, _ = ctx.prefill(list(prompt) + emitted[:-1])
+    if first != emitted[-1]:
+        ctx.set_pending(emitted[-1])
+    ctx.set_stats(list(S_c), float(S_n), list(S_tcs), list(S_fcs))
+    assert ctx.state() == (T, pending)
+    rep.resyncs += 1
+
+
+def lockstep_records(cfg, rec, ctx: DelContext, max_rounds=None) -> ParityReport:
+    """Drive the library through the rounds of a stored oracle run (DEL-selected (E, gamma))."""
+    rep = ParityReport()
+    L = cfg.n_layers
+    meta = rec["meta"]
+    for k, v in meta["config"].items():        # the record was made for this very configuration
+        assert getattr(cfg, k) == v, (k, getattr(cfg, k), v)
+    prompt = rec["prompt"].tolist()
+    from synthdata import gen_prompt
+    assert prompt == gen_prompt(cfg).tolist()
+    hid_layers = [int(x) for x in rec["hidden_layers"]]
+    first, gE, gg = ctx.prefill(prompt)
+    st = ctx.stats()
+    w = int(rec["pre_window"])
+    pre_first = int(rec["pre_first_token"])
+    near = rec["pre_gaps"] < GAP_TOL
+    if first != pre_first:
+        assert float(rec["pre_first_gap"]) < GAP_TOL, f"first token {first} != {pre_first}"
+        rep.flips += 1
+    for l in range(1, L + 1):
+        slack = int(np.sum(near[l] | near[L]))
+        assert abs(st["last_c"][l] - int(rec["pre_c"][l])) <= slack, (l, st["last_c"][l], int(rec["pre_c"][l]), slack)
+    for k, l in enumerate(hid_layers):
+        err = _rel_err(ctx.hidden(l, ctx.last_rows() - 1), rec["pre_hidden"][k])
+        rep.max_hidden_err = max(rep.max_hidden_err, err)
+        assert err <= HID_TOL, ("prefill hidden", l, err)
+    emitted = [pre_first]
+    exact = first == pre_first and all(st["last_c"][l] == int(rec["pre_c"][l]) for l in range(1, L + 1))
+    if exact:
+        assert (gE, gg) == (int(rec["pre_next_E"]), int(rec["pre_next_gamma"]))
+        for l in range(1, L + 1):
+            assert abs(st["alpha"][l] - rec["pre_alpha"][l]) < 1e-12
+            assert _close(st["tau"][l], rec["pre_tau"][l], CONF_RTOL), ("prefill tau", l)
+    else:
+        _resync_records(ctx, prompt, emitted, rec["pre_c"].astype(np.float64), float(w), rec["pre_tcs"],
+                        rec["pre_fcs"], len(prompt), pre_first, rep)
+    R = len(rec["E"]) if max_rounds is None else min(max_rounds, len(rec["E"]))
+    hid_at = {int(r): k for k, r in enumerate(rec["hidden_rounds"])}
+    for r in range(R):
+        E, g, u = int(rec["E"][r]), int(rec["gamma"][r]), int(rec["u"][r])
+        assert ctx.state()[0] == int(rec["T_before"][r])
+        out = ctx.round(E, g)
+        st = ctx.stats()
+        rep.rounds += 1
+        drafts = rec["draft_ids"][r, :g].tolist()
+        target = rec["target_ids"][r, :g + 1].tolist()
+        same_rows = g + 1
+        for i in range(g):
+            if st["last_draft"][i] != drafts[i]:
+                same_rows = i + 1
+                break
+        flipped = False
+        for l in range(1, L + 1):
+            for i in range(same_rows):
+                rep.compared_ids += 1
+                want = int(rec["shadow"][r, l, i])
+                if st["last_shadow"][l][i] == want:
+                    assert _close(st["last_conf"][l][i], rec["conf"][r, l, i], CONF_RTOL), (
+                        "confidence", r, l, i, st["last_conf"][l][i], rec["conf"][r, l, i])
+                else:
+                    assert rec["gaps"][r, l, i] < GAP_TOL, (
+                        f"round {r + 1} E={E} g={g} layer {l} row {i}: gpu {st['last_shadow'][l][i]} "
+                        f"oracle {want} gap {rec['gaps'][r, l, i]}")
+                    rep.flips += 1
+                    flipped = True
+        if r in hid_at:
+            for k, l in enumerate(hid_layers):
+                want = rec["hidden"][hid_at[r], k, :same_rows]
+                got = np.stack([ctx.hidden(l, i) for i in range(same_rows)])
+                err = _rel_err(got, want)
+                rep.max_hidden_err = max(rep.max_hidden_err, err)
+                assert err <= HID_TOL, ("hidden", r, l, err)
+        out_want = target[:u + 1]
+        emitted.extend(out_want)
+        T_after, pending = int(rec["T_before"][r]) + u + 1, out_want[-1]
+        if not flipped and same_rows == g + 1:
+            assert out == out_want, (out, out_want)
+            assert st["last_u"] == u and st["last_n"] == int(rec["n"][r])
+            assert st["last_c"][1:] == rec["c"][r, 1:].tolist()
+            assert st["last_draft"][:g] == drafts
+            for l in range(1, L + 1):
+                assert abs(st["S_c"][l] - rec["S_c"][r, l]) <= 1e-9 * max(1.0, rec["S_c"][r, l])
+                assert abs(st["alpha"][l] - rec["alpha"][r, l]) <= 1e-9
+                assert _close(st["S_tcs"][l], rec["S_tcs"][r, l], CONF_RTOL)
+                assert _close(st["S_fcs"][l], rec["S_fcs"][r, l], CONF_RTOL)
+                assert _close(st["tau"][l], rec["tau"][r, l], CONF_RTOL), ("tau", r, l)
+            assert abs(st["S_n"] - rec["S_n"][r]) <= 1e-9 * rec["S_n"][r]
+            assert (st["next_E"], st["next_gamma"]) == (int(rec["next_E"][r]), int(rec["next_gamma"][r]))
+            assert ctx.state() == (T_after, pending)
+        else:
+            _resync_records(ctx, prompt, emitted, rec["S_c"][r], rec["S_n"][r], rec["S_tcs"][r], rec["S_fcs"][r],
+                            T_after, pending, rep)
+    rep.tokens = emitted
+    return rep

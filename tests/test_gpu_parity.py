@@ -295,3 +295,18 @@ def test_unsplit_attention_for_multi_row_passes(name, monkeypatch):
     rep = lockstep(cfg, oracle, ctx, gen_prompt(cfg).tolist(), cfg.gen_len)
     _check_report(rep, f"{name} unsplit attention")
     ctx.close()
+
+
+def test_paper_d_max_18_rounds_of_more_than_16_rows():
+    """Appendix B.2's d_max = 18: rounds whose verify pass has up to 19 rows (more than one block of 16
+    token rows), fixed long schedules and the DEL-driven run, on the matrix-core and on the vector path."""
+    from gpu_harness import lockstep
+    for use_mfma in (True, False):
+        cfg, ctx, oracle = _setup("mini_d18", use_mfma=use_mfma)
+        prompt = gen_prompt(cfg).tolist()
+        for sched in ((2, 18), (4, 16), (1, 17), None):
+            rep = lockstep(cfg, oracle, ctx, prompt, cfg.gen_len, schedule=sched)
+            _check_report(rep, f"mini_d18 mfma={use_mfma} schedule={sched}")
+        rep = lockstep(cfg, oracle, ctx, prompt, 40, dynamic=True)
+        _check_report(rep, f"mini_d18 mfma={use_mfma} dynamic")
+        ctx.close()
