@@ -405,8 +405,13 @@ def _resync_records(ctx: DelContext, prompt, emitted, S_c, S_n, S_tcs, S_fcs, T,
     rep.resyncs += 1
 
 
-def lockstep_records(cfg, rec, ctx: DelContext, max_rounds=None) -> ParityReport:
-    """Drive the library through the rounds of a stored oracle run (DEL-selected (E, gamma))."""
+def lockstep_records(cfg, rec, ctx: DelContext, max_rounds=None, conf_rtol=None) -> ParityReport:
+    """Drive the library through the rounds of a stored oracle run (DEL-selected (E, gamma)).
+    conf_rtol: relative tolerance of confidences and of the sums and thresholds built from them.  A
+    confidence is exp(z_top - logsumexp(z)), so its relative error is at most twice the largest absolute
+    logit error; at the full-size shapes (d_model 4096-8192, logits of a few units, fp32 oracle) that is
+    up to about 1e-2, so the default here is the 2e-2 the logits themselves are held to."""
+    CONF_RTOL = HID_TOL if conf_rtol is None else conf_rtol
     rep = ParityReport()
     L = cfg.n_layers
     meta = rec["meta"]
