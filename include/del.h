@@ -230,6 +230,24 @@ del_status del_debug_spec_sample(del_ctx* ctx, const float* q_logits, const floa
                                  double temperature, double top_p, const float* uniforms, int32_t* drafts_out,
                                  int32_t* u, int32_t* last_token);
 
+/* For callers that cannot allocate device memory or have the library do so: code that is being captured
+ * into a HIP graph, tight serving loops, harnesses that forbid hipMalloc.  The sampling arithmetic of
+ * del_debug_spec_sample on logits that are already in DEVICE memory, with no context: every intermediate
+ * (fixed-point weights, per-row records, counters) lives in one fixed device array of the library
+ * (about 4.5 MB per GPU, held until the process ends).  The call allocates nothing, copies nothing to or
+ * from the host and does not wait: it queues four kernels on `hip_stream` (NULL = default stream).
+ *   q_logits  device, [gamma][ld_logits] floats (may be NULL when gamma == 0); p_logits device,
+ *             [gamma+1][ld_logits]; both 16-byte aligned, ld_logits a multiple of 4 and >= vocab
+ *   uniforms  device, 2*gamma+1 floats in [0, 1): drafts, acceptances, last token (not checked)
+ *   out       device, 3+gamma ints: out[0] = u (accepted drafts), out[1] = u + 1, out[2] = the last
+ *             token, out[3..3+gamma) = the drafted tokens; valid once the stream has passed the call
+ * Limits: vocab <= 32768 and gamma <= 8, else DEL_E_CAPACITY; DEL_E_ARG for bad pointers, alignment,
+ * temperature <= 0 or top_p outside (0, 1].  All calls on one GPU share the one array: calls whose
+ * kernels may overlap on that GPU (different streams or threads of one process) race. */
+del_status del_spec_sample_static(const float* q_logits, const float* p_logits, int64_t ld_logits, int32_t vocab,
+                                  int32_t gamma, double temperature, double top_p, const float* uniforms,
+                                  int32_t* out, void* hip_stream);
+
 /* Host-only helpers (no context, no device): the policy arithmetic the library applies after
  * every round, exposed so that it can be checked on its own.
  * del_policy_step: one update of the running sums (Section 4.2: S <- omega*S + a for c^l, n, and

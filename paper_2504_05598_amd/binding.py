@@ -15,7 +15,7 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 
 EXPORTS = ["del_create", "del_destroy", "del_load_weights", "del_prefill", "del_round", "del_round_dynamic",
            "del_layer_stats", "del_set_layer_stats", "del_last_timings", "del_debug_hidden",
-           "del_debug_logits", "del_debug_state", "del_debug_set_pending", "del_debug_last_rows", "del_profile_enable", "del_profile_read", "del_policy_step", "del_sample_first", "del_round_sample", "del_round_sample_dynamic", "del_debug_spec_sample", "del_bench_stream_read", "del_bench_stream_copy", "del_strerror",
+           "del_debug_logits", "del_debug_state", "del_debug_set_pending", "del_debug_last_rows", "del_profile_enable", "del_profile_read", "del_policy_step", "del_sample_first", "del_round_sample", "del_round_sample_dynamic", "del_debug_spec_sample", "del_spec_sample_static", "del_bench_stream_read", "del_bench_stream_copy", "del_strerror",
            "del_last_error_text"]
 
 DEL_DTYPE_FP32, DEL_DTYPE_BF16 = 0, 1
@@ -111,6 +111,8 @@ def load_library():
                                              P(C.c_float), P(C.c_int32), P(C.c_int32), P(C.c_int32), P(C.c_int32)]
     lib.del_debug_spec_sample.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int32, C.c_double, C.c_double,
                                           P(C.c_float), P(C.c_int32), P(C.c_int32), P(C.c_int32)]
+    lib.del_spec_sample_static.argtypes = [C.c_void_p, C.c_void_p, C.c_int64, C.c_int32, C.c_int32, C.c_double,
+                                           C.c_double, C.c_void_p, C.c_void_p, C.c_void_p]
     lib.del_strerror.argtypes = [C.c_int]
     lib.del_strerror.restype = C.c_char_p
     lib.del_last_error_text.argtypes = [C.c_void_p]
@@ -225,6 +227,15 @@ def del_debug_spec_sample(ctx, q_logits, p_logits, gamma: int, temperature: floa
     _check(load_library().del_debug_spec_sample(ctx, qp, p_logits.ctypes.data, gamma, temperature, top_p, un,
                                                 drafts, C.byref(u), C.byref(last)), ctx)
     return list(drafts[:gamma]), u.value, last.value
+
+
+def del_spec_sample_static(q_logits_ptr: int, p_logits_ptr: int, ld_logits: int, vocab: int, gamma: int,
+                           temperature: float, top_p: float, uniforms_ptr: int, out_ptr: int, stream: int = 0) -> None:
+    """Every pointer is a DEVICE address (an int); out receives 3 + gamma ints once the stream has passed
+    the call: u, u + 1, the last token, the drafts.  Allocates nothing and does not wait."""
+    _check(load_library().del_spec_sample_static(C.c_void_p(q_logits_ptr), C.c_void_p(p_logits_ptr), ld_logits, vocab,
+                                                 gamma, temperature, top_p, C.c_void_p(uniforms_ptr),
+                                                 C.c_void_p(out_ptr), C.c_void_p(stream)))
 
 
 def del_layer_stats(ctx, n_layers: int, d_max: int) -> dict:

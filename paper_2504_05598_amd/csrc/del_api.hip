@@ -9,6 +9,7 @@
 #include <cstdlib>
 #include <cstring>
 #include <map>
+#include <mutex>
 #include <new>
 #include <string>
 #include <tuple>
@@ -1360,6 +1361,84 @@ del_status del_debug_spec_sample(del_ctx* ctx, const float* q_logits, const floa
   *u = host[4 + DM];
   *last_token = host[4 + DM + 2];
   for (int i = 0; i < gamma; ++i) drafts_out[i] = host[4 + i];
+  return DEL_OK;
+}
+
+}  // extern "C" (re-opened below: the static scratch array has C++ linkage)
+
+// ---- the entry point that allocates nothing ---------------------------------------------------------
+// Scratch of del_spec_sample_static: fixed-point weights of up to 2*8+1 logits rows of up to 32768
+// tokens, one SampRow per row, and a few integers.  One copy per GPU the library runs on, held until the
+// process ends.  Host code never uses the array's name as an address: the device address is looked up
+// once per device with hipGetSymbolAddress and kept in static_scratch_ptr.
+namespace {
+constexpr int STATIC_MAX_VOCAB = 32768, STATIC_MAX_GAMMA = 8;
+constexpr size_t ST_ROWS = 2 * STATIC_MAX_GAMMA + 1;
+constexpr size_t ST_WF_BYTES = ST_ROWS * (size_t)STATIC_MAX_VOCAB * sizeof(unsigned long long);
+constexpr size_t ST_SROW_BYTES = (ST_ROWS * sizeof(SampRow) + 255) / 256 * 256;
+constexpr size_t ST_INT_BYTES = 256;
+constexpr size_t ST_BYTES = ST_WF_BYTES + ST_SROW_BYTES + ST_INT_BYTES;
+constexpr int ST_MAX_DEVICES = 64;
+}  // namespace
+static __device__ __align__(256) unsigned char scratch[ST_BYTES];
+namespace {
+void* static_scratch_ptr[ST_MAX_DEVICES] = {};
+std::mutex static_scratch_mutex;
+
+// Device address of this GPU's copy of the scratch array (looked up at the first call on the device).
+hipError_t static_scratch(void** out) {
+  int dev = -1;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess) return e;
+  if (dev < 0 || dev >= ST_MAX_DEVICES) return hipErrorInvalidDevice;
+  std::lock_guard<std::mutex> lock(static_scratch_mutex);
+  if (!static_scratch_ptr[dev]) {
+    void* p = nullptr;
+    e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+    if (e != hipSuccess) return e;
+    if (!p) return hipErrorInvalidSymbol;
+    static_scratch_ptr[dev] = p;
+  }
+  *out = static_scratch_ptr[dev];
+  return hipSuccess;
+}
+}  // namespace
+
+extern "C" {
+
+del_status del_spec_sample_static(const float* q_logits, const float* p_logits, int64_t ld_logits, int32_t vocab,
+                                  int32_t gamma, double temperature, double top_p, const float* uniforms,
+                                  int32_t* out, void* hip_stream) {
+  if (!p_logits || !uniforms || !out || gamma < 0 || vocab < 2 || (gamma > 0 && !q_logits) || ld_logits < vocab ||
+      ld_logits % 4 != 0 || !sampling_args_ok(temperature, top_p))
+    return DEL_E_ARG;
+  // the kernels read the rows in 16-byte pieces
+  if (((uintptr_t)p_logits | (uintptr_t)q_logits) % 16 != 0 || (uintptr_t)uniforms % 4 != 0 || (uintptr_t)out % 4 != 0)
+    return DEL_E_ARG;
+  if (vocab > STATIC_MAX_VOCAB || gamma > STATIC_MAX_GAMMA) return DEL_E_CAPACITY;
+  hipStream_t s = (hipStream_t)hip_stream;
+  void* base = nullptr;
+  if (static_scratch(&base) != hipSuccess) return DEL_E_DEVICE;
+  unsigned long long* wf_q = reinterpret_cast<unsigned long long*>(base);
+  unsigned long long* wf_p = wf_q + (size_t)STATIC_MAX_GAMMA * STATIC_MAX_VOCAB;
+  SampRow* rows_q = reinterpret_cast<SampRow*>(reinterpret_cast<char*>(base) + ST_WF_BYTES);
+  SampRow* rows_p = rows_q + STATIC_MAX_GAMMA;
+  int* ints = reinterpret_cast<int*>(reinterpret_cast<char*>(base) + ST_WF_BYTES + ST_SROW_BYTES);
+  int* state = ints;          // [0] KV length, [1] pending token: the acceptance kernel adds to [0]
+  int* drafts = ints + 4;     // [STATIC_MAX_GAMMA]
+  const int64_t ldw = STATIC_MAX_VOCAB;
+  // the array keeps the last call's contents: what must start at zero is cleared by a kernel (a caller
+  // may be capturing this stream into a graph, where memset nodes are not to be used)
+  if (launch_set_state(state, 0, 0, nullptr, 0, s) != hipSuccess) return DEL_E_DEVICE;
+  if (gamma > 0 && launch_samp_rowstats(q_logits, ld_logits, vocab, gamma, temperature, top_p, wf_q, ldw, rows_q,
+                                        uniforms, drafts, nullptr, nullptr, s) != hipSuccess)
+    return DEL_E_DEVICE;
+  if (launch_samp_rowstats(p_logits, ld_logits, vocab, gamma + 1, temperature, top_p, wf_p, ldw, rows_p, nullptr,
+                           nullptr, nullptr, nullptr, s) != hipSuccess)
+    return DEL_E_DEVICE;
+  if (launch_samp_accept(q_logits, wf_q, rows_q, p_logits, wf_p, rows_p, ld_logits, ldw, vocab, gamma, drafts,
+                         uniforms + gamma, uniforms + 2 * gamma, state, nullptr, 0, out, s) != hipSuccess)
+    return DEL_E_DEVICE;
   return DEL_OK;
 }
 
