@@ -41,19 +41,50 @@ def round_bytes(cfg, E, gamma, T):
     return (gamma * E + L) * b_layer + (gamma + 1) * b_head + kv_read + kv_write + hidden
 
 
+def segment_bytes(cfg, E, gamma, T):
+    """Algorithmic HBM bytes of a round's segments at KV length T: (draft layer passes incl. the last-token
+    pass, draft heads, verify layer passes, shadow/verify head).  Same accounting as round_bytes."""
+    L = cfg.n_layers
+    es = 2 if cfg.weight_dtype == "bf16" else 4
+    b_layer, b_head = cfg.layer_weight_bytes(), cfg.head_weight_bytes()
+    kv_row = 2 * cfg.n_kv_heads * cfg.head_dim * es
+    draft = sum(E * (b_layer + (T + i + 1) * kv_row + kv_row) for i in range(gamma + 1))
+    heads = gamma * b_head
+    m = gamma + 1
+    verify = (L - E) * (b_layer + (T + m) * kv_row + m * kv_row)
+    shadow = b_head + 2 * L * m * cfg.d_model * 4
+    return draft, heads, verify, shadow
+
+
+def library_source_hash():
+    """sha256 over the HIP sources the library is built from (what a stored profile is valid for)."""
+    import hashlib
+    root = os.path.join(os.path.dirname(os.path.abspath(__file__)), "paper_2504_05598_amd", "csrc")
+    h = hashlib.sha256()
+    for name in sorted(os.listdir(root)):
+        if name.endswith((".hip", ".h")):
+            h.update(name.encode())
+            h.update(open(os.path.join(root, name), "rb").read())
+    return h.hexdigest()[:16]
+
+
 def measured_traffic(cfg_name, kernel):
     """HBM bytes per launch of `kernel` from the committed rocprofv3 PMC summary (FETCH_SIZE and
-    WRITE_SIZE, each scaled by a plain copy kernel of known size), or None if there is none."""
+    WRITE_SIZE, each scaled by a plain copy kernel of known size).  The summary names the sources it
+    was measured on (library_source_hash); None if there is no summary or the library has changed since."""
     path = os.path.join(os.path.dirname(os.path.abspath(__file__)), "profiles",
                         f"bench_{cfg_name}_hbm_traffic.txt")
+    value, valid = None, False
     try:
         for line in open(path):
             parts = line.split()
             if len(parts) == 3 and parts[0] == "traffic_bytes_per_launch" and parts[1] == kernel:
-                return int(float(parts[2]))
+                value = int(float(parts[2]))
+            if len(parts) == 2 and parts[0] == "library_source_hash":
+                valid = parts[1] == library_source_hash()
     except OSError:
         pass
-    return None
+    return value if valid else None
 
 
 def main():
@@ -116,8 +147,9 @@ def main():
     prefill_s = time.time() - t0
     run(W)
     torch.cuda.synchronize()
+    timed = []
     t0 = time.perf_counter()
-    tokens = run(K)
+    tokens = run(K, timed)      # per round: two host-side reads of state the library already holds
     torch.cuda.synchronize()
     dt = time.perf_counter() - t0
     value = tokens / dt
@@ -126,8 +158,7 @@ def main():
     ctx.prefill(prompt)
     run(W)
     ctx.profile_enable(True)
-    recs = []
-    run(K, recs)
+    run(K, [])
     prof = ctx.profile_read()
     ctx.profile_enable(False)
     by_kernel = {}
@@ -141,11 +172,21 @@ def main():
     dom_bytes = dom["bytes"] / dom["launches"]
     dom_us = 1e3 * dom["total_ms"] / dom["launches"]
     achieved = dom_bytes / (dom_us * 1e-6) / 1e9
+    # round split and segment fractions from the TIMED run's own per-round event times
+    recs = timed
     alg_bytes = sum(round_bytes(cfg, E, g, T) for (E, g, T, n, d, v, s) in recs)
     seg = [sum(r[i] for r in recs) / len(recs) for i in (4, 5, 6)]
     round_ms_prof = sum(seg)
     layers_loaded = sum(g * E + cfg.n_layers for (E, g, T, n, d, v, s) in recs)
     etpl = sum(r[3] for r in recs) / layers_loaded
+    sb = [segment_bytes(cfg, E, g, T) for (E, g, T, n, d, v, s) in recs]
+    draft_seg_bytes = sum(b[0] + b[1] for b in sb)
+    verify_seg_bytes = sum(b[2] for b in sb)
+    shadow_seg_bytes = sum(b[3] for b in sb)
+    draft_s = sum(r[4] for r in recs) * 1e-3
+    verify_s = sum(r[5] for r in recs) * 1e-3
+    shadow_s = sum(r[6] for r in recs) * 1e-3
+    verify_layer_passes = sum(cfg.n_layers - E for (E, g, T, n, d, v, s) in recs)
 
     # ---- vanilla (gamma = 0) rounds with the same library, for the speed-up figure
     ctx.prefill(prompt)
@@ -158,6 +199,31 @@ def main():
         ctx.round(1, 0)
     torch.cuda.synchronize()
     vanilla_tps = nv / (time.perf_counter() - t0)
+    # ---- the draft layer pass on its own: a round with E = L and gamma = 0 is L one-row layer passes in its
+    #      draft segment (no head there) and nothing in its verify segment
+    ctx.prefill(prompt)
+    run(W)
+    lp = []
+    for _ in range(8):
+        T = ctx.state()[0]
+        ctx.round(cfg.n_layers, 0)
+        lp.append((T, ctx.timings()[0]))
+    # ---- static (E, gamma) schedules around DEL's choice (the LayerSkip baseline of Section 5.1)
+    meanE = sum(r[0] for r in timed) / len(timed)
+    statics = []
+    for Es in sorted({max(1, int(round(meanE)) + dE) for dE in (-4, -2, 0, 2)}):
+        for gs in sorted({min(cfg.d_max, g) for g in (2, 3, 4, 6)}):
+            if Es >= cfg.n_layers:
+                continue
+            ctx.prefill(prompt)
+            for _ in range(2):
+                ctx.round(Es, gs)
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            nt = sum(len(ctx.round(Es, gs)) for _ in range(12))
+            torch.cuda.synchronize()
+            statics.append((nt / (time.perf_counter() - t0), Es, gs))
+    best_static = max(statics) if statics else None
     # ---- the same K rounds with dynamic draft-exiting (Section 4.4): E and tau_E from the statistics
     ctx.prefill(prompt)
 
@@ -234,6 +300,30 @@ def main():
     stream_gbs = ctx.stream_read_gbps(min(4 << 30, cfg.layer_weight_bytes() * cfg.n_layers), 10)
     copy_gbs = ctx.stream_copy_gbps(1 << 30, 5)     # also the known-size kernel for counter calibration
 
+    # one-row layer pass: time and algorithmic bytes (a layer's weights + its KV rows read and one row written)
+    es = 2 if cfg.weight_dtype == "bf16" else 4
+    kv_row = 2 * cfg.n_kv_heads * cfg.head_dim * es
+    lp_us = 1e3 * sum(t for _, t in lp) / len(lp) / cfg.n_layers
+    lp_T = int(sum(T for T, _ in lp) / len(lp))
+    lp_bytes = cfg.layer_weight_bytes() + (lp_T + 2) * kv_row
+    # the shadow-head GEMM (Section 4.2): rows, HBM and matrix-core fractions; model flops = 2 * rows * d * V, the
+    # matrix cores execute twice that (activations enter as a bf16 high and low part)
+    shadow_info = None
+    hk = [e for e in prof if e["kernel"] == "head_gemm_k"]
+    if hk:
+        h_ms = sum(e["total_ms"] for e in hk)
+        h_n = sum(e["launches"] for e in hk)
+        h_rows = sum(e["rows"] * e["launches"] for e in hk) / h_n
+        h_bytes = sum(e["weight_bytes"] * e["launches"] for e in hk)
+        h_flops = sum(2.0 * e["rows"] * cfg.d_model * cfg.vocab * e["launches"] for e in hk)
+        shadow_info = {"kernel": "head_gemm_k", "launches": h_n, "mean_rows": round(h_rows, 1),
+                       "avg_us": round(1e3 * h_ms / h_n, 2),
+                       "hbm_frac": round(h_bytes / (h_ms * 1e-3) / 1e9 / HBM_PEAK_GBS, 4),
+                       "mfma_frac_model_flops": round(h_flops / (h_ms * 1e-3) / 1e12 / MFMA_BF16_PEAK_TFLOPS, 4),
+                       "mfma_frac_executed": round(2 * h_flops / (h_ms * 1e-3) / 1e12 / MFMA_BF16_PEAK_TFLOPS, 4),
+                       "hi_lo_factor": 2,
+                       "note": "weights streamed once per 16 blocks of 16 token rows; executed = model flops x 2"}
+
     result = {
         "metric": "accepted tokens/sec at batch 1 (Llama-2-7B shape)",
         "value": round(value, 2),
@@ -274,6 +364,25 @@ def main():
             "stream_read_GBs": round(stream_gbs, 1), "stream_copy_GBs": round(copy_gbs, 1),
             "paper_speedup_over_autoregressive": "2.16-2.62x on A100-40G / 2xH100-PCIe (context only)",
         },
+        "segments": {
+            "note": "from the timed run's own per-round event times; algorithmic bytes / time / 8 TB/s "
+                    "(and / the measured stream-read ceiling); draft_segment includes the gamma draft heads",
+            "draft_segment_hbm_frac": round(draft_seg_bytes / draft_s / 1e9 / HBM_PEAK_GBS, 4),
+            "verify_layers_hbm_frac": round(verify_seg_bytes / verify_s / 1e9 / HBM_PEAK_GBS, 4) if verify_s > 0 else None,
+            "verify_layer_pass_us": round(1e6 * verify_s / max(1, verify_layer_passes), 2),
+            "shadow_segment_hbm_frac": round(shadow_seg_bytes / shadow_s / 1e9 / HBM_PEAK_GBS, 4),
+            "draft_layer_pass_us": round(lp_us, 2), "draft_layer_pass_T": lp_T,
+            "draft_layers_hbm_frac": round(lp_bytes / (lp_us * 1e-6) / 1e9 / HBM_PEAK_GBS, 4),
+            "draft_layers_frac_of_stream_ceiling": round(lp_bytes / (lp_us * 1e-6) / 1e9 / stream_gbs, 4),
+            "verify_layers_frac_of_stream_ceiling": round(verify_seg_bytes / verify_s / 1e9 / stream_gbs, 4) if verify_s > 0 else None,
+            "draft_layer_pass_source": "8 rounds with E = L, gamma = 0: their draft segment is L one-row layer passes, no head",
+        },
+        "shadow_head": shadow_info,
+        "best_static_schedule": ({"E": best_static[1], "gamma": best_static[2], "tokens_per_s": round(best_static[0], 2),
+                                  "del_tokens_per_s": round(value, 2), "tried": len(statics),
+                                  "note": "static (E, gamma) around DEL's mean exit layer, 12 rounds each; the paper's cost "
+                                          "model (Section 4.1) ignores the LM head, 0.65 of a layer per draft step here"}
+                                 if best_static else None),
         "prefill": prefill_info,
         "kernels": {n: {"launches": k["launches"], "avg_us": round(1e3 * k["total_ms"] / k["launches"], 2),
                         "GBs": round(k["bytes"] / (k["total_ms"] * 1e-3) / 1e9, 1)}
