@@ -368,7 +368,7 @@ del_status run_layer(del_ctx* ctx, int l, int row0, int m, bool chained) {
     const int S = ceil_div(ctx->Tcap, rps);
     a.VcT = VcT; a.TcapT = ctx->TcapT;
     HIPCHK(launch_attention_flash_split(a, S, rps, ctx->stream));
-    a.nsplit = S;
+    a.nsplit = S; a.rps = rps;
     HIPCHK(launch_attention_merge(a, ctx->stream));
   } else if (dec_any && m > 1 && ctx->attn_direct_rows > 0 && m >= ctx->attn_direct_rows) {
     a.nsplit = -1;   // one split per row: the kernel writes the output rows and their tiles itself

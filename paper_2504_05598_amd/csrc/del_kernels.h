@@ -91,6 +91,8 @@ struct AttnP {
   uint16_t* XsOut;              // optional: the same rows as split tiles (input of the O projection)
   long long xs_cb_stride;       // 16-bit elements between the tiles of consecutive blocks of 16 token rows
   int rw;                       // token rows per work-group of the register kernel (set by the launcher)
+  int rps;                      // > 0: the partials come from the matrix-core kernel split into spans of at least
+                                // this many cache rows (a multiple of 32); spans past the context hold nothing
 };
 
 hipError_t launch_gemm_valu(const GemmP& p, int epi, int waves, hipStream_t s);

@@ -1252,9 +1252,11 @@ __global__ void __launch_bounds__(256) attn_flash_split_k(AttnP p, int S, int rp
   const int T0 = p.state[0] + p.row_off;       // cache position of token row 0
   const int pos = T0 + qi;                     // this lane's query attends cache rows <= pos
   const int t_end = T0 + nrow;                 // cache rows the pass needs: [0, t_end)
-  // rows per split: whole tiles of 32, at least what the launcher planned for
+  // rows per split: whole tiles of 32, at least what the launcher planned for (attn_combine_k derives the
+  // same number from p.rps)
   const int rps = max(rps_min, ((t_end + S - 1) / S + 31) / 32 * 32);
   const int t_lo = split * rps, t_hi = min(t_end, t_lo + rps);
+  if (t_lo >= t_end) return;                   // a span past the context: the merge does not read its partial
   uint4 qh[KT], ql[KT];
   {
     const float scale = 1.0f / sqrtf((float)HD);
@@ -1346,7 +1348,11 @@ __global__ void __launch_bounds__(128) attn_combine_k(AttnP p) {
   const int d = threadIdx.x;
   if (d >= p.hd) return;
   const int T_end = p.state[0] + p.row_off + p.m;
-  const int nch = p.nsplit > 0 ? p.nsplit : (T_end + p.ct - 1) / p.ct;   // partials per row
+  int nch = p.nsplit > 0 ? p.nsplit : (T_end + p.ct - 1) / p.ct;   // partials per row
+  if (p.rps > 0) {   // matrix-core kernel, split by spans of rows: only the spans that reach into the context
+    const int rps = max(p.rps, ((T_end + p.nsplit - 1) / p.nsplit + 31) / 32 * 32);
+    nch = min(nch, (T_end + rps - 1) / rps);
+  }
   const float* pm = p.PM + (size_t)row * p.nch_max;
   const float* pl = p.PL + (size_t)row * p.nch_max;
   const float* pa = p.PA + (size_t)row * p.nch_max * p.hd + d;
