@@ -278,10 +278,15 @@ __global__ void __launch_bounds__(1024) gemm_valu_k(GemmP p) {
   const int kt_lo = min(p.KT, wave * per), kt_hi = min(p.KT, kt_lo + per);
   const int ngroups = (kt_hi - kt_lo) / GU;
   const uint4* wp = (const uint4*)p.Wt + ((size_t)nb * p.KT + kt_lo) * 64 + lane;
-  uint4 cur[GU], nxt[GU];
+  // two groups of GU tiles in flight (A: even groups, B: odd groups), requested before the input row is staged
+  uint4 ta[GU], tb[GU];
   if (ngroups > 0) {
 #pragma unroll
-    for (int u = 0; u < GU; ++u) cur[u] = ld_stream(wp + u * 64);
+    for (int u = 0; u < GU; ++u) ta[u] = ld_stream(wp + u * 64);
+  }
+  if (ngroups > 1) {
+#pragma unroll
+    for (int u = 0; u < GU; ++u) tb[u] = ld_stream(wp + (GU + u) * 64);
   }
   if (M == 1) {
     // stage the gained input row in LDS, four 16-byte pieces per thread at a time: loads first,
@@ -334,19 +339,37 @@ __global__ void __launch_bounds__(1024) gemm_valu_k(GemmP p) {
     }
     __syncthreads();
   }
-  // steady state: branch-free, the next group's loads are in flight while this one is consumed
-  for (int gi = 0; gi + 1 < ngroups; ++gi) {
-    const uint4* wn = wp + (size_t)(gi + 1) * GU * 64;
+  // Steady state: branch-free, and no register that a load is still filling is ever copied (a copy would
+  // make the wave wait for every load in flight): group gi is used from A, A is refilled with group gi + 2,
+  // then the same for B with gi + 1 and gi + 3, so two groups (2 * GU KiB per wave) stay in flight.
+  auto use = [&](const uint4* tl, int gi) {
 #pragma unroll
-    for (int u = 0; u < GU; ++u) nxt[u] = ld_stream(wn + u * 64);
+    for (int u = 0; u < GU; ++u) valu_tile<KPL, M>(tl[u], kt_lo + gi * GU + u, g, xs, p, has_gain, acc, ss);
+  };
+  auto fill = [&](uint4* tl, int gi) {
+    const uint4* wn = wp + (size_t)gi * GU * 64;
 #pragma unroll
-    for (int u = 0; u < GU; ++u) valu_tile<KPL, M>(cur[u], kt_lo + gi * GU + u, g, xs, p, has_gain, acc, ss);
-#pragma unroll
-    for (int u = 0; u < GU; ++u) cur[u] = nxt[u];
+    for (int u = 0; u < GU; ++u) tl[u] = ld_stream(wn + u * 64);
+  };
+  int gi = 0;
+  for (; gi + 4 <= ngroups; gi += 2) {
+    use(ta, gi);
+    fill(ta, gi + 2);
+    use(tb, gi + 1);
+    fill(tb, gi + 3);
   }
-  if (ngroups > 0) {
-#pragma unroll
-    for (int u = 0; u < GU; ++u) valu_tile<KPL, M>(cur[u], kt_lo + (ngroups - 1) * GU + u, g, xs, p, has_gain, acc, ss);
+  // one to three groups are left, the first two of them already requested
+  const int left = ngroups - gi;
+  if (left == 3) {
+    use(ta, gi);
+    fill(ta, gi + 2);
+    use(tb, gi + 1);
+    use(ta, gi + 2);
+  } else if (left == 2) {
+    use(ta, gi);
+    use(tb, gi + 1);
+  } else if (left == 1) {
+    use(ta, gi);
   }
   for (int kt = kt_lo + ngroups * GU; kt < kt_hi; ++kt) {
     const uint4 w = ld_stream(wp + (size_t)(kt - kt_lo) * 64);

@@ -135,7 +135,7 @@ def main():
         for k, r in enumerate(have):
             h = kept_hidden[r]
             hidden[k, :, :h.shape[1]] = h
-        meta = dict(config=cfg.as_dict(), n_tokens=n_tokens, tokens_emitted=len(toks), rounds=R, complete=final,
+        meta = dict(config=cfg.as_dict(), n_tokens=n_tokens, tokens_emitted=len(toks), rounds=R, complete=bool(final and len(toks) >= n_tokens),
                     oracle_dtype="float32", prompt_len=len(prompt),
                     schedule="DEL-selected (E, gamma), gamma clamped to remaining - 1",
                     writer="tests/golden/make_fullsize_records.py (oracle/ + synthdata/ only)")

@@ -77,7 +77,7 @@ def test_records_are_self_consistent(path):
         assert np.all(z["gaps"][r, 1:, :gr + 1] >= 0)
         assert np.all((z["conf"][r, 1:, :gr + 1] > 0) & (z["conf"][r, 1:, :gr + 1] <= 1.0 + 1e-12))
     assert tokens == z["tokens"].tolist()
-    if meta["complete"]:
+    if meta["tokens_emitted"] >= n_tokens:    # a record cut short by --max-rounds holds fewer
         assert len(tokens) == n_tokens
     assert z["hidden"].shape[0] == len(z["hidden_rounds"]) >= 1
     assert np.isfinite(z["hidden"]).all() and np.abs(z["hidden"][0, :, 0]).max() > 0
