@@ -213,6 +213,16 @@ __device__ __forceinline__ uint4 ld_stream(const uint4* p) {
 
 constexpr int GU = 4;  // tiles in flight per wave and pipeline stage (x2: current + next)
 
+// The k tiles of a row block are split over the waves in whole groups of `grp` tiles, as evenly as the
+// group count allows; only the last wave can be left with fewer than `grp` tiles at its end.  (A
+// remainder is loaded tile by tile with its latency exposed, so a split in tiles, which leaves one in
+// every wave, costs about two memory latencies per launch.)
+__device__ __forceinline__ void wave_span(int KT, int nw, int wave, int grp, int& lo, int& hi) {
+  const int G = KT / grp;
+  lo = (G * wave / nw) * grp;
+  hi = wave == nw - 1 ? KT : (G * (wave + 1) / nw) * grp;
+}
+
 // ---------------------------------------------------------------------------------------
 // Vector-ALU GEMV (M = 1) / skinny GEMM (M = 2, 4, 8): one work-group per 16-row block; each
 // lane accumulates one weight row over its wave's span of k tiles, fp32 throughout.
@@ -273,12 +283,65 @@ __global__ void __launch_bounds__(1024) gemm_valu_k(GemmP p) {
 #pragma unroll
   for (int m = 0; m < M; ++m) { acc[m] = 0.f; ss[m] = 0.f; }
   const bool has_gain = p.gain != nullptr;
-  // this wave's span of k tiles: full groups of GU tiles, then a remainder of fewer than GU
-  const int per = (p.KT + nw - 1) / nw;
-  const int kt_lo = min(p.KT, wave * per), kt_hi = min(p.KT, kt_lo + per);
+  // this wave's span of k tiles: full groups of GU tiles (the last wave: plus a remainder of fewer than GU)
+  int kt_lo, kt_hi;
+  wave_span(p.KT, nw, wave, GU, kt_lo, kt_hi);
   const int ngroups = (kt_hi - kt_lo) / GU;
   const uint4* wp = (const uint4*)p.Wt + ((size_t)nb * p.KT + kt_lo) * 64 + lane;
-  // two groups of GU tiles in flight (A: even groups, B: odd groups), requested before the input row is staged
+  // Order of the first memory requests: the input row (it comes from the cache and is needed by every
+  // wave before the first product), then two groups of GU weight tiles per wave (A: even groups, B: odd
+  // groups).  Loads complete in order, so the row is in LDS and the barrier passed while the tiles are
+  // still arriving, and every wave refills as soon as its own tiles are there; requested after the tiles,
+  // the row would arrive behind the whole first burst of the grid and the memory pipe would run dry
+  // while the work-group waits at the barrier.
+  const int Kp = p.KT * TK, stride = blockDim.x * 4;
+  float4 xv[4], gv[4];
+  auto stage_load = [&](int base) {
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      const int k = base + j * stride;
+      xv[j] = make_float4(0.f, 0.f, 0.f, 0.f);
+      gv[j] = make_float4(1.f, 1.f, 1.f, 1.f);
+      if (k < Kp) {
+        if (p.att_S > 0) {
+          // the input row is the attention output: merge the S per-split softmax partials here
+          if (k < p.K) {
+            const int h = k / p.att_hd, d = k - h * p.att_hd;
+            const float* pm = p.att_PM + (size_t)h * p.att_stride;
+            const float* pl = p.att_PL + (size_t)h * p.att_stride;
+            float mx = -INFINITY;
+            for (int sidx = 0; sidx < p.att_S; ++sidx) mx = fmaxf(mx, pm[sidx]);
+            float L = 0.f;
+            float4 a = make_float4(0.f, 0.f, 0.f, 0.f);
+            for (int sidx = 0; sidx < p.att_S; ++sidx) {
+              const float ms = pm[sidx];
+              const float c = ms > -INFINITY ? expf(ms - mx) : 0.f;
+              L += c * pl[sidx];
+              const float4 t = *(const float4*)(p.att_PA + ((size_t)h * p.att_stride + sidx) * p.att_hd + d);
+              a.x += c * t.x; a.y += c * t.y; a.z += c * t.z; a.w += c * t.w;
+            }
+            const float inv = 1.0f / L;
+            xv[j] = make_float4(a.x * inv, a.y * inv, a.z * inv, a.w * inv);
+          }
+        } else {
+          xv[j] = *(const float4*)(p.X + k);
+        }
+        if (has_gain) gv[j] = *(const float4*)(p.gain + k);
+      }
+    }
+  };
+  auto stage_store = [&](int base) {
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      const int k = base + j * stride;
+      if (k < Kp) {
+        const float4 x = xv[j], gg = gv[j];
+        ss[0] += x.x * x.x + x.y * x.y + x.z * x.z + x.w * x.w;
+        *(float4*)(xs + k) = make_float4(x.x * gg.x, x.y * gg.y, x.z * gg.z, x.w * gg.w);
+      }
+    }
+  };
+  if (M == 1) stage_load(tid * 4);
   uint4 ta[GU], tb[GU];
   if (ngroups > 0) {
 #pragma unroll
@@ -289,53 +352,12 @@ __global__ void __launch_bounds__(1024) gemm_valu_k(GemmP p) {
     for (int u = 0; u < GU; ++u) tb[u] = ld_stream(wp + (GU + u) * 64);
   }
   if (M == 1) {
-    // stage the gained input row in LDS, four 16-byte pieces per thread at a time: loads first,
-    // then the stores (one memory latency per batch; one batch covers up to 16 floats x threads)
-    const int Kp = p.KT * TK, stride = blockDim.x * 4;
-    for (int base = tid * 4; base < Kp; base += 4 * stride) {
-      float4 xv[4], gv[4];
-#pragma unroll
-      for (int j = 0; j < 4; ++j) {
-        const int k = base + j * stride;
-        xv[j] = make_float4(0.f, 0.f, 0.f, 0.f);
-        gv[j] = make_float4(1.f, 1.f, 1.f, 1.f);
-        if (k < Kp) {
-          if (p.att_S > 0) {
-            // the input row is the attention output: merge the S per-split softmax partials here
-            xv[j] = make_float4(0.f, 0.f, 0.f, 0.f);
-            if (k < p.K) {
-              const int h = k / p.att_hd, d = k - h * p.att_hd;
-              const float* pm = p.att_PM + (size_t)h * p.att_stride;
-              const float* pl = p.att_PL + (size_t)h * p.att_stride;
-              float mx = -INFINITY;
-              for (int sidx = 0; sidx < p.att_S; ++sidx) mx = fmaxf(mx, pm[sidx]);
-              float L = 0.f;
-              float4 a = make_float4(0.f, 0.f, 0.f, 0.f);
-              for (int sidx = 0; sidx < p.att_S; ++sidx) {
-                const float ms = pm[sidx];
-                const float c = ms > -INFINITY ? expf(ms - mx) : 0.f;
-                L += c * pl[sidx];
-                const float4 t = *(const float4*)(p.att_PA + ((size_t)h * p.att_stride + sidx) * p.att_hd + d);
-                a.x += c * t.x; a.y += c * t.y; a.z += c * t.z; a.w += c * t.w;
-              }
-              const float inv = 1.0f / L;
-              xv[j] = make_float4(a.x * inv, a.y * inv, a.z * inv, a.w * inv);
-            }
-          } else {
-            xv[j] = *(const float4*)(p.X + k);
-          }
-          if (has_gain) gv[j] = *(const float4*)(p.gain + k);
-        }
-      }
-#pragma unroll
-      for (int j = 0; j < 4; ++j) {
-        const int k = base + j * stride;
-        if (k < Kp) {
-          const float4 x = xv[j], gg = gv[j];
-          ss[0] += x.x * x.x + x.y * x.y + x.z * x.z + x.w * x.w;
-          *(float4*)(xs + k) = make_float4(x.x * gg.x, x.y * gg.y, x.z * gg.z, x.w * gg.w);
-        }
-      }
+    // four 16-byte pieces per thread and batch: one batch covers 16 floats x threads, i.e. the whole row
+    // for every shape but the widest rows on the smaller work-groups
+    stage_store(tid * 4);
+    for (int base = tid * 4 + 4 * stride; base < Kp; base += 4 * stride) {
+      stage_load(base);
+      stage_store(base);
     }
     __syncthreads();
   }
@@ -430,21 +452,35 @@ __global__ void __launch_bounds__(1024) gemm_mfma_k(GemmP p) {
   // (same cache lines as the active lanes, no extra traffic, no divergent loads); their output
   // columns are never used.
   const int blane = token < mvalid ? lane : (lane & 48);
-  const int per = (p.KT + nw - 1) / nw;
-  const int kt_lo = min(p.KT, wave * per), kt_hi = min(p.KT, kt_lo + per);
+  int kt_lo, kt_hi;
+  wave_span(p.KT, nw, wave, U, kt_lo, kt_hi);
   const int ngroups = (kt_hi - kt_lo) / U;
   const uint4* wp = (const uint4*)p.Wt + ((size_t)nb * p.KT + kt_lo) * 64 + lane;
   const uint4* xp = (const uint4*)p.Xs + ((size_t)cb * p.KT + kt_lo) * 128 + blane;
   floatx4 acc = {0.f, 0.f, 0.f, 0.f}, acc2 = {0.f, 0.f, 0.f, 0.f};   // hi and lo products, independent chains
-  uint4 a[U], bh[U], bl[U], an[U], bhn[U], bln[U];
-  if (ngroups > 0) {
+  // two register sets (even and odd groups), never copied: a copy of a register that a load is still
+  // filling would make the wave wait for every load in flight
+  uint4 a0[U], h0[U], l0[U], a1[U], h1[U], l1[U];
+  auto fill = [&](uint4* a, uint4* bh, uint4* bl, int gi) {
+    const uint4* wn = wp + (size_t)gi * U * 64;
+    const uint4* xn = xp + (size_t)gi * U * 128;
 #pragma unroll
     for (int u = 0; u < U; ++u) {
-      a[u] = ld_stream(wp + u * 64);
-      bh[u] = xp[u * 128];
-      bl[u] = xp[u * 128 + 64];
+      a[u] = ld_stream(wn + u * 64);
+      bh[u] = xn[u * 128];
+      bl[u] = xn[u * 128 + 64];
     }
-  }
+  };
+  auto use = [&](const uint4* a, const uint4* bh, const uint4* bl) {
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      const bf16x8 av = __builtin_bit_cast(bf16x8, a[u]);
+      acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(av, __builtin_bit_cast(bf16x8, bh[u]), acc, 0, 0, 0);
+      acc2 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(av, __builtin_bit_cast(bf16x8, bl[u]), acc2, 0, 0, 0);
+    }
+  };
+  if (ngroups > 0) fill(a0, h0, l0, 0);
+  if (ngroups > 1) fill(a1, h1, l1, 1);
   if (p.ssq_in) {   // RMS scale per token row from the producer's per-block sums of squares
     for (int mi = wave; mi < mvalid; mi += nw) {
       float q = 0.f;
@@ -453,32 +489,25 @@ __global__ void __launch_bounds__(1024) gemm_mfma_k(GemmP p) {
       if (lane == 0) scl[mi] = 1.0f / sqrtf(q / (float)p.K + p.eps);
     }
   }
-  // steady state: branch-free
-  for (int gi = 0; gi + 1 < ngroups; ++gi) {
-    const uint4* wn = wp + (size_t)(gi + 1) * U * 64;
-    const uint4* xn = xp + (size_t)(gi + 1) * U * 128;
-#pragma unroll
-    for (int u = 0; u < U; ++u) {
-      an[u] = ld_stream(wn + u * 64);
-      bhn[u] = xn[u * 128];
-      bln[u] = xn[u * 128 + 64];
-    }
-#pragma unroll
-    for (int u = 0; u < U; ++u) {
-      const bf16x8 av = __builtin_bit_cast(bf16x8, a[u]);
-      acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(av, __builtin_bit_cast(bf16x8, bh[u]), acc, 0, 0, 0);
-      acc2 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(av, __builtin_bit_cast(bf16x8, bl[u]), acc2, 0, 0, 0);
-    }
-#pragma unroll
-    for (int u = 0; u < U; ++u) { a[u] = an[u]; bh[u] = bhn[u]; bl[u] = bln[u]; }
+  // steady state: branch-free, two groups in flight
+  int gi = 0;
+  for (; gi + 4 <= ngroups; gi += 2) {
+    use(a0, h0, l0);
+    fill(a0, h0, l0, gi + 2);
+    use(a1, h1, l1);
+    fill(a1, h1, l1, gi + 3);
   }
-  if (ngroups > 0) {
-#pragma unroll
-    for (int u = 0; u < U; ++u) {
-      const bf16x8 av = __builtin_bit_cast(bf16x8, a[u]);
-      acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(av, __builtin_bit_cast(bf16x8, bh[u]), acc, 0, 0, 0);
-      acc2 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(av, __builtin_bit_cast(bf16x8, bl[u]), acc2, 0, 0, 0);
-    }
+  const int left = ngroups - gi;   // one to three groups, the first two already requested
+  if (left == 3) {
+    use(a0, h0, l0);
+    fill(a0, h0, l0, gi + 2);
+    use(a1, h1, l1);
+    use(a0, h0, l0);
+  } else if (left == 2) {
+    use(a0, h0, l0);
+    use(a1, h1, l1);
+  } else if (left == 1) {
+    use(a0, h0, l0);
   }
   for (int kt = kt_lo + ngroups * U; kt < kt_hi; ++kt) {
     const uint4 aw = ld_stream(wp + (size_t)(kt - kt_lo) * 64);
