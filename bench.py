@@ -95,6 +95,8 @@ def main():
     ap.add_argument("--config", default="llama7b")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-mfma", action="store_true")
+    ap.add_argument("--micro", action="store_true",
+                    help="only the GEMV decomposition table (del_bench_gemv_parts) for this config's matrix shapes")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this build runs on one GPU only (batch-1 decode on a single MI355X); "
@@ -108,6 +110,8 @@ def main():
     from synthdata import gen_prompt, gen_tensor, get_config, iter_tensor_specs
 
     cfg = get_config(args.config)
+    if args.micro:
+        return micro(cfg, DelContext)
     K, W = args.steps, args.warmup
     max_context = cfg.prompt_len + (2 * K + W + 8) * (cfg.d_max + 1) + cfg.d_max + 1
     want_cpu = not args.no_cpu_baseline
@@ -394,6 +398,34 @@ def main():
     if want_cpu:
         result["cpu_baseline"] = cpu_baseline(cfg, host, prompt)
     print(json.dumps(result), flush=True)
+
+
+def micro(cfg, DelContext):
+    """Where a one-row GEMV launch spends its time beyond the weight stream: the library's GEMV with parts
+    switched off (del_bench_gemv_parts), at this config's matrix shapes and launch geometry, back-to-back
+    launches over different parts of the (zero-filled) weight arena.  Prints a table, not the bench line."""
+    ctx = DelContext(cfg)
+    d, f, V = cfg.d_model, cfg.d_ffn, cfg.vocab
+    qkv_rows = (cfg.n_q_heads + 2 * cfg.n_kv_heads) * cfg.head_dim
+    up16 = lambda n: (n + 15) // 16
+    up8 = lambda n: (n + 7) // 8
+    shapes = [("QKV", up16(qkv_rows), d // 32), ("O", up16(d), cfg.n_q_heads * cfg.head_dim // 32),
+              ("gate/up", up8(f), d // 32), ("down", up16(d), (f + 31) // 32), ("head", up16(V), d // 32)]
+    cols = [("tile loads only", 0), ("+ decode/FMA (constant row)", 2), ("+ row staged via LDS", 3),
+            ("loads + FMA + reduce/store", 6), ("whole kernel", 7)]
+    ceiling = ctx.stream_read_gbps(min(4 << 30, cfg.layer_weight_bytes() * cfg.n_layers), 10)
+    print(f"# del_bench_gemv_parts, {cfg.name}: microseconds per launch (200 back-to-back launches, rotating matrices)")
+    print(f"# streaming read of the arena: {ceiling:.0f} GB/s; ideal = tile bytes / that rate")
+    print(f"{'matrix':8s} {'blocks':>6s} {'ktiles':>6s} {'waves':>5s} {'MB':>7s} {'ideal':>7s} " + " ".join(f"{c[0]:>28s}" for c in cols))
+    for name, nb, kt in shapes:
+        if kt > 480:
+            print(f"{name:8s} k tiles {kt} beyond the measurement kernel's limit")
+            continue
+        waves = 8 if nb * 8 >= 2 * 3072 else 16   # the library's own choice of waves per row block
+        mb = nb * kt * 1024
+        row = [ctx.gemv_parts_us(nb, kt, waves, parts) for _, parts in cols]
+        print(f"{name:8s} {nb:6d} {kt:6d} {waves:5d} {mb / 1e6:7.1f} {mb / ceiling / 1e3:7.2f} " + " ".join(f"{v:28.2f}" for v in row))
+    ctx.close()
 
 
 def cpu_baseline(cfg, host, prompt):

@@ -177,6 +177,16 @@ del_status del_debug_set_pending(del_ctx* ctx, int32_t token);
  * the GEMV kernels' access pattern (sets the achievable-bandwidth ceiling), and
  * the time of the last such call in ms. */
 del_status del_bench_stream_read(del_ctx* ctx, int64_t bytes, int32_t iters, float* ms_per_iter);
+/* The draft path's one-row GEMV (Section 4.1: a draft step streams E layers of weights for one row)
+ * with parts of it switched off, timed over `iters` back-to-back launches on an n_blocks x k_tiles
+ * tile matrix taken from the weight arena (consecutive launches read different parts of it): where a
+ * launch spends its time beyond the weight stream.  parts: bit 0 = input row and gain staged through
+ * LDS, bit 1 = bf16 decode + fp32 FMA, bit 2 = cross-wave reduction + RMS scale + residual store;
+ * 0 = the tile loads alone in the GEMV's geometry.  waves per 16-row block: 4, 8 or 16; k_tiles <= 480.
+ * Results of the arithmetic are discarded.  us_per_launch: host pointer.  DEL_E_ARG for arguments out
+ * of range, DEL_E_CAPACITY if the matrix is larger than the arena. */
+del_status del_bench_gemv_parts(del_ctx* ctx, int32_t n_blocks, int32_t k_tiles, int32_t waves, int32_t parts,
+                                int32_t iters, float* us_per_launch);
 /* A plain device-to-device copy kernel of `bytes` (reads and writes that many bytes of a
  * temporary buffer): the known-size kernel the profiler's HBM byte counters are scaled by. */
 del_status del_bench_stream_copy(del_ctx* ctx, int64_t bytes, int32_t iters, float* ms_per_iter);

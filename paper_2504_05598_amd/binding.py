@@ -15,7 +15,7 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 
 EXPORTS = ["del_create", "del_destroy", "del_load_weights", "del_prefill", "del_round", "del_round_dynamic",
            "del_layer_stats", "del_set_layer_stats", "del_last_timings", "del_debug_hidden",
-           "del_debug_logits", "del_debug_state", "del_debug_set_pending", "del_debug_last_rows", "del_profile_enable", "del_profile_read", "del_policy_step", "del_sample_first", "del_round_sample", "del_round_sample_dynamic", "del_debug_spec_sample", "del_spec_sample_static", "del_bench_stream_read", "del_bench_stream_copy", "del_strerror",
+           "del_debug_logits", "del_debug_state", "del_debug_set_pending", "del_debug_last_rows", "del_profile_enable", "del_profile_read", "del_policy_step", "del_sample_first", "del_round_sample", "del_round_sample_dynamic", "del_debug_spec_sample", "del_spec_sample_static", "del_bench_stream_read", "del_bench_stream_copy", "del_bench_gemv_parts", "del_strerror",
            "del_last_error_text"]
 
 DEL_DTYPE_FP32, DEL_DTYPE_BF16 = 0, 1
@@ -99,6 +99,7 @@ def load_library():
     lib.del_profile_enable.argtypes = [C.c_void_p, C.c_int32]
     lib.del_profile_read.argtypes = [C.c_void_p, P(del_prof_entry), C.c_int32, P(C.c_int32)]
     lib.del_bench_stream_read.argtypes = [C.c_void_p, C.c_int64, C.c_int32, P(C.c_float)]
+    lib.del_bench_gemv_parts.argtypes = [C.c_void_p, C.c_int32, C.c_int32, C.c_int32, C.c_int32, C.c_int32, P(C.c_float)]
     lib.del_bench_stream_copy.argtypes = [C.c_void_p, C.c_int64, C.c_int32, P(C.c_float)]
     lib.del_policy_step.argtypes = [C.c_int32, C.c_int32, C.c_double, P(C.c_int32), C.c_int32, P(C.c_double),
                                     P(C.c_double), P(C.c_double), P(C.c_double), P(C.c_double), P(C.c_double),
@@ -440,6 +441,12 @@ class DelContext:
         ms = C.c_float()
         _check(load_library().del_bench_stream_copy(self.ctx, nbytes, iters, C.byref(ms)), self.ctx)
         return 2 * nbytes / (ms.value * 1e-3) / 1e9
+
+    def gemv_parts_us(self, n_blocks: int, k_tiles: int, waves: int, parts: int, iters: int = 200) -> float:
+        """del_bench_gemv_parts: microseconds per launch of the one-row GEMV with only `parts` switched on."""
+        us = C.c_float(0.0)
+        _check(load_library().del_bench_gemv_parts(self.ctx, n_blocks, k_tiles, waves, parts, iters, C.byref(us)), self.ctx)
+        return float(us.value)
 
     def stream_read_gbps(self, nbytes: int, iters: int = 20) -> float:
         ms = C.c_float()

@@ -1597,6 +1597,40 @@ del_status del_bench_stream_read(del_ctx* ctx, int64_t bytes, int32_t iters, flo
   return DEL_OK;
 }
 
+del_status del_bench_gemv_parts(del_ctx* ctx, int32_t n_blocks, int32_t k_tiles, int32_t waves, int32_t parts,
+                                int32_t iters, float* us_per_launch) {
+  if (!ctx || !us_per_launch || iters < 1 || n_blocks < 1 || k_tiles < 1 || k_tiles > 480 || parts < 0 || parts > 7 ||
+      (waves != 4 && waves != 8 && waves != 16))
+    return DEL_E_ARG;
+  const size_t mat = (size_t)n_blocks * k_tiles * 1024;
+  if (mat > ctx->arena_bytes) return DEL_E_CAPACITY;
+  // consecutive launches read different parts of the arena, cycling through at least 1 GiB where the
+  // arena has it, so that no launch finds its matrix in a cache
+  size_t span = ctx->arena_bytes < ((size_t)1 << 30) ? ctx->arena_bytes : ((size_t)1 << 30);
+  if (span < mat) span = mat;
+  const int nmat = (int)(span / mat);
+  float* buf = nullptr;
+  const size_t kf = (size_t)k_tiles * 32, nf = (size_t)n_blocks * 16;
+  HIPCHK(hipMalloc((void**)&buf, (2 * kf + 2 * nf) * sizeof(float)));
+  float *X = buf, *G = buf + kf, *R = buf + 2 * kf, *Y = R + nf;
+  hipError_t e = hipMemsetAsync(buf, 0, (2 * kf + 2 * nf) * sizeof(float), ctx->stream);
+  auto go = [&](int i) {
+    return launch_gemv_parts((const char*)ctx->arena + (size_t)(i % nmat) * mat, X, G, R, Y, n_blocks, k_tiles, waves, parts,
+                             ctx->stream);
+  };
+  for (int i = 0; i < 3 && e == hipSuccess; ++i) e = go(i);
+  if (e == hipSuccess) e = hipEventRecord(ctx->ev[0], ctx->stream);
+  for (int i = 0; i < iters && e == hipSuccess; ++i) e = go(i);
+  if (e == hipSuccess) e = hipEventRecord(ctx->ev[1], ctx->stream);
+  if (e == hipSuccess) e = hipStreamSynchronize(ctx->stream);
+  float ms = 0.f;
+  if (e == hipSuccess) e = hipEventElapsedTime(&ms, ctx->ev[0], ctx->ev[1]);
+  (void)hipFree(buf);
+  if (e != hipSuccess) return ctx->fail(e, "del_bench_gemv_parts");
+  *us_per_launch = ms * 1e3f / iters;
+  return DEL_OK;
+}
+
 del_status del_bench_stream_copy(del_ctx* ctx, int64_t bytes, int32_t iters, float* ms_per_iter) {
   if (!ctx || !ms_per_iter || iters < 1 || bytes < 1024) return DEL_E_ARG;
   char* buf = nullptr;

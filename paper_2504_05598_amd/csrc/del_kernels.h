@@ -139,6 +139,10 @@ hipError_t launch_tile_scatter(const void* src, int wdtype, int64_t row0, int64_
 hipError_t launch_pad_gain(const float* src, int K, float* dst, int Kpad, hipStream_t s);
 hipError_t launch_stream_copy(const void* src, void* dst, int64_t bytes, hipStream_t s);
 hipError_t launch_stream_read(const void* base, int64_t bytes, float* sink, hipStream_t s);
+// The one-row GEMV with parts switched off (bit 0 staging, bit 1 decode + FMA, bit 2 reduce + store) on an
+// NB x KT tile matrix at W; X, G: KT*32 floats, R, Y: NB*16 floats.  KT <= 480, waves 4, 8 or 16.
+hipError_t launch_gemv_parts(const void* W, const float* X, const float* G, const float* R, float* Y, int NB, int KT,
+                             int waves, int parts, hipStream_t s);
 
 // ---- speculative sampling (del_sampling.hip) ----
 // What the sampling kernels keep of one logits row: token j is in the nucleus when the order key of

@@ -1619,6 +1619,109 @@ __global__ void __launch_bounds__(256) stream_copy_k(const uint4* __restrict__ s
   for (long long i = (long long)blockIdx.x * 256 + threadIdx.x; i < n; i += (long long)gridDim.x * 256) dst[i] = src[i];
 }
 
+// The one-row GEMV with parts of it switched off, for measurement only (results are not used): where a
+// launch spends its time beyond the weight stream.  PARTS bit 0: the input row and gain staged through
+// LDS (with the sum of squares); bit 1: bf16 decode and fp32 FMA (with the staged row, or with constants
+// when bit 0 is off); bit 2: cross-wave reduction, RMS scale, residual add and store.  PARTS = 0 leaves
+// the tile loads in the GEMV's geometry and schedule (two groups of GU tiles per wave in flight).
+template <int PARTS>
+__global__ void __launch_bounds__(1024) gemv_parts_k(const uint4* __restrict__ W, const float* __restrict__ X,
+                                                    const float* __restrict__ G, const float* __restrict__ R,
+                                                    float* __restrict__ Y, int KT) {
+  constexpr bool STG = PARTS & 1, CMP = PARTS & 2, RED = PARTS & 4;
+  extern __shared__ __align__(16) float xs[];
+  __shared__ float red[MAXW][16];
+  __shared__ float ssr[MAXW];
+  const int tid = threadIdx.x, nw = blockDim.x >> 6, wave = tid >> 6, lane = tid & 63, g = lane >> 4, nb = blockIdx.x;
+  int kt_lo, kt_hi;
+  wave_span(KT, nw, wave, GU, kt_lo, kt_hi);
+  const int ngroups = (kt_hi - kt_lo) / GU;
+  const uint4* wp = W + ((size_t)nb * KT + kt_lo) * 64 + lane;
+  float acc = 0.f, ss = 0.f;
+  const int Kp = KT * 32, stride = blockDim.x * 4;
+  float4 xv[4], gv[4];
+  auto stage_load = [&](int base) {
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      const int kk = base + j * stride;
+      xv[j] = make_float4(0.f, 0.f, 0.f, 0.f);
+      gv[j] = make_float4(1.f, 1.f, 1.f, 1.f);
+      if (kk < Kp) { xv[j] = *(const float4*)(X + kk); gv[j] = *(const float4*)(G + kk); }
+    }
+  };
+  auto stage_store = [&](int base) {
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      const int kk = base + j * stride;
+      if (kk < Kp) {
+        const float4 x = xv[j], gg = gv[j];
+        ss += x.x * x.x + x.y * x.y + x.z * x.z + x.w * x.w;
+        *(float4*)(xs + kk) = make_float4(x.x * gg.x, x.y * gg.y, x.z * gg.z, x.w * gg.w);
+      }
+    }
+  };
+  if (STG) stage_load(tid * 4);
+  uint4 ta[GU], tb[GU];
+  if (ngroups > 0) {
+#pragma unroll
+    for (int u = 0; u < GU; ++u) ta[u] = ld_stream(wp + u * 64);
+  }
+  if (ngroups > 1) {
+#pragma unroll
+    for (int u = 0; u < GU; ++u) tb[u] = ld_stream(wp + (GU + u) * 64);
+  }
+  if (STG) {
+    stage_store(tid * 4);
+    for (int base = tid * 4 + 4 * stride; base < Kp; base += 4 * stride) { stage_load(base); stage_store(base); }
+    __syncthreads();
+  }
+  auto tile = [&](const uint4& w, int kt) {
+    if (CMP) {
+      float wf[8];
+      WDec<8>::dec(w, wf);
+      float4 a = make_float4(1.f, 2.f, 3.f, 4.f), b = make_float4(.5f, .25f, .125f, 2.f);
+      if (STG) { a = *(const float4*)(xs + kt * 32 + g * 8); b = *(const float4*)(xs + kt * 32 + g * 8 + 4); }
+      acc += wf[0] * a.x; acc += wf[1] * a.y; acc += wf[2] * a.z; acc += wf[3] * a.w;
+      acc += wf[4] * b.x; acc += wf[5] * b.y; acc += wf[6] * b.z; acc += wf[7] * b.w;
+    } else {
+      acc += __uint_as_float((w.x ^ w.y ^ w.z ^ w.w) & 0x3fffffffu);
+    }
+  };
+  auto use = [&](const uint4* tl, int gi) {
+#pragma unroll
+    for (int u = 0; u < GU; ++u) tile(tl[u], kt_lo + gi * GU + u);
+  };
+  auto fill = [&](uint4* tl, int gi) {
+    const uint4* wn = wp + (size_t)gi * GU * 64;
+#pragma unroll
+    for (int u = 0; u < GU; ++u) tl[u] = ld_stream(wn + u * 64);
+  };
+  int gi = 0;
+  for (; gi + 4 <= ngroups; gi += 2) { use(ta, gi); fill(ta, gi + 2); use(tb, gi + 1); fill(tb, gi + 3); }
+  const int left = ngroups - gi;
+  if (left == 3) { use(ta, gi); fill(ta, gi + 2); use(tb, gi + 1); use(ta, gi + 2); }
+  else if (left == 2) { use(ta, gi); use(tb, gi + 1); }
+  else if (left == 1) { use(ta, gi); }
+  for (int kt = kt_lo + ngroups * GU; kt < kt_hi; ++kt) tile(ld_stream(wp + (size_t)(kt - kt_lo) * 64), kt);
+  if (!RED) {
+    if (acc == 123.456f || ss == 77.f) Y[nb * 16 + (lane & 15)] = acc;   // practically never; keeps the work alive
+    return;
+  }
+  acc += __shfl_xor(acc, 16);
+  acc += __shfl_xor(acc, 32);
+  for (int o = 1; o < 64; o <<= 1) ss += __shfl_xor(ss, o);
+  if (lane < 16) red[wave][lane] = acc;
+  if (lane == 0) ssr[wave] = ss;
+  __syncthreads();
+  if (tid < 16) {
+    float s = 0.f, q = 0.f;
+    for (int w = 0; w < nw; ++w) s += red[w][tid];
+    for (int w = 0; w < nw; ++w) q += ssr[w];
+    s *= 1.0f / sqrtf(q / (float)(KT * 32) + 1e-5f);
+    Y[nb * 16 + tid] = s + R[nb * 16 + tid];
+  }
+}
+
 // ---------------------------------------------------------------------------------------
 // Launchers
 // ---------------------------------------------------------------------------------------
@@ -1915,6 +2018,20 @@ hipError_t launch_stream_read(const void* base, int64_t bytes, float* sink, hipS
   const long long n_tiles = bytes / 1024;
   if (n_tiles <= 0) return hipErrorInvalidValue;
   hipLaunchKernelGGL(stream_read_k, dim3(256 * 8), dim3(512), 0, s, (const uint4*)base, n_tiles, sink);
+  return hipGetLastError();
+}
+
+hipError_t launch_gemv_parts(const void* W, const float* X, const float* G, const float* R, float* Y, int NB, int KT,
+                             int waves, int parts, hipStream_t s) {
+  if (NB < 1 || KT < 1 || KT > 480 || (waves != 4 && waves != 8 && waves != 16) || parts < 0 || parts > 7)
+    return hipErrorInvalidValue;
+  const dim3 grid(NB), block(64 * waves);
+  const size_t lds = (size_t)KT * 32 * sizeof(float);
+  switch (parts) {
+#define GP(v) case v: hipLaunchKernelGGL((gemv_parts_k<v>), grid, block, lds, s, (const uint4*)W, X, G, R, Y, KT); break;
+    GP(0) GP(1) GP(2) GP(3) GP(4) GP(5) GP(6) GP(7)
+#undef GP
+  }
   return hipGetLastError();
 }
 
