@@ -145,6 +145,7 @@ struct del_ctx {
   int last_stopped = 0;
   float t_draft = 0, t_verify = 0, t_shadow = 0;
   int target_waves = 3072;
+  int head_form = 4;          // shadow-head kernel: 4 = register-blocked, 1 = one row block per wave (DEL_HEAD_FORM)
   // Optional (DEL_GRAPHS=1): the segments of a round are captured once per (kind, E, gamma) into HIP
   // graphs and replayed; positions and token ids live in device memory, so a graph depends on
   // nothing else.  Off by default: on this GPU the kernels of a round already run back to back
@@ -552,7 +553,7 @@ del_status shadow_head(del_ctx* ctx, int m, int row0 = 0) {
     const int pr = prof_begin(ctx, 2, EPI_ARGMAX, R, (int64_t)ctx->NBv * ctx->KTd * 1024);
     HIPCHK(launch_head_gemm(ctx->head_t, ctx->NBv, ctx->KTd, ctx->V, ctx->xs_shadow, R, ctx->rowscale, ctx->pval,
                             ctx->pidx, ctx->psum, &nparts, ctx->stream, pr >= 0 ? ctx->prof_ev[2 * pr] : nullptr,
-                            pr >= 0 ? ctx->prof_ev[2 * pr + 1] : nullptr));
+                            pr >= 0 ? ctx->prof_ev[2 * pr + 1] : nullptr, ctx->head_form));
     prof_end(ctx, pr);
   } else {
     for (int l = 1; l <= ctx->L; ++l) {
@@ -682,6 +683,10 @@ del_status del_create(const del_config* cfg, void* hip_stream, del_ctx** out) {
   if (const char* tw = getenv("DEL_TARGET_WAVES")) {
     const int v = atoi(tw);
     if (v >= 64 && v <= 65536) ctx->target_waves = v;
+  }
+  if (const char* hf = getenv("DEL_HEAD_FORM")) {
+    const int v = atoi(hf);
+    if (v == 1 || v == 4) ctx->head_form = v;
   }
 
   const size_t tile = 1024;

@@ -97,10 +97,11 @@ struct AttnP {
 
 hipError_t launch_gemm_valu(const GemmP& p, int epi, int waves, hipStream_t s);
 hipError_t launch_gemm_mfma(const GemmP& p, int epi, int waves, int col_blocks, hipStream_t s);
-// Shadow-head GEMM with fused arg-max over R rows; partials are [R][*n_slabs].
+// Shadow-head GEMM with fused arg-max over R rows; partials are [R][*n_slabs].  form 4: the register-blocked
+// kernel (needs KT % 4 == 0, otherwise the other one runs); any other value: one row block per wave.
 hipError_t launch_head_gemm(const void* Wt, int NB, int KT, int N, const uint16_t* Xs, int R, const float* rowscale,
                             float* pval, int* pidx, float* psum, int* n_slabs, hipStream_t s,
-                            hipEvent_t ev_start = nullptr, hipEvent_t ev_stop = nullptr);
+                            hipEvent_t ev_start = nullptr, hipEvent_t ev_stop = nullptr, int form = 1);
 // Many token rows at once (prefill): 8 row blocks x up to 256 token rows per work-group, the split
 // activation tiles ([cb][kt] for p.M rows) staged through LDS.  epi: EPI_RESID, EPI_QKV or EPI_SWIGLU.
 hipError_t launch_gemm_wide(const GemmP& p, int epi, hipStream_t s);

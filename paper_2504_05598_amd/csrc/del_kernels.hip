@@ -691,6 +691,236 @@ __global__ void __launch_bounds__(512) head_gemm_k(const uint4* __restrict__ Wt,
 }
 
 // ---------------------------------------------------------------------------------------
+// Shadow-head GEMM, register-blocked form.  What bounds the form above is LDS operand traffic: a wave
+// owns one row block and reads every activation tile from LDS for a single matrix instruction (about
+// 1 KiB of LDS reads per instruction, four SIMDs sharing one LDS port).  Here a wave owns H4_RB = 4 row
+// blocks and H4_CB = 8 column blocks (128 accumulator registers), so that an activation tile read from
+// LDS feeds 4 instructions, and the k range is split over the waves instead: work-group = the same
+// slab of 8 row blocks, wave = (half of the slab, quarter of the k tiles).  Per step every quarter
+// consumes its own k tile, whose activation tiles (4 x 8 x 2 KiB) are staged in LDS, double-buffered,
+// one barrier per step (KT / 4 barriers per launch instead of KT).  The four quarters are summed
+// through LDS at the end; output format as above (per row and slab: best logit, index, soft-max sum).
+// Needs KT % 4 == 0.  blockIdx.y picks a group of 8 column blocks (128 token rows).
+// ---------------------------------------------------------------------------------------
+constexpr int H4_RB = 4, H4_CB = 8, H4_KQ = 4;
+constexpr int H4_STAGE = H4_KQ * H4_CB * 128;   // uint4 per stage
+
+__global__ void __launch_bounds__(512) head_gemm4_k(const uint4* __restrict__ Wt, int NB, int KT, int N,
+                                                    const uint4* __restrict__ Xs, int CB, int R,
+                                                    const float* __restrict__ rowscale, float* pval, int* pidx,
+                                                    float* psum, int NS) {
+  // two stages as separate arrays: the compiler then knows that the loads filling one stage do not touch
+  // the stage being read (otherwise every LDS read after such a load waits for all of them)
+  __shared__ __align__(16) uint4 st0[H4_STAGE];
+  __shared__ __align__(16) uint4 st1[H4_STAGE];
+  uint4* const bs = st0;   // the epilogue reuses stage 0
+  // the wave index as a scalar: everything derived from it (row blocks, k quarter, staging sources) then lives
+  // in scalar registers and an address is a scalar base plus the lane's 16 bytes; the accumulators leave
+  // no vector registers for per-lane pointers
+  const int tid = threadIdx.x, wave = __builtin_amdgcn_readfirstlane(tid >> 6), lane = tid & 63;
+  const int rg = wave & 1, kq = wave >> 1;
+  const int slab = blockIdx.x, cb0 = blockIdx.y * H4_CB;
+  const int ncb = min(H4_CB, CB - cb0);
+  const int KTq = KT / H4_KQ, kt0 = kq * KTq;
+  const int nb0 = slab * HG_W + rg * H4_RB;
+  // loads are unconditional with clamped addresses (no branches around memory operations); row blocks
+  // beyond the last one re-read it and are masked in the arg-max
+  size_t wrow[H4_RB];   // first tile of this wave's k quarter in each of its row blocks (scalar)
+#pragma unroll
+  for (int r = 0; r < H4_RB; ++r) wrow[r] = ((size_t)min(nb0 + r, NB - 1) * KT + kt0) * 64;
+  floatx4 acc[H4_RB][H4_CB];
+#pragma unroll
+  for (int r = 0; r < H4_RB; ++r)
+#pragma unroll
+    for (int c = 0; c < H4_CB; ++c) acc[r][c] = (floatx4){0.f, 0.f, 0.f, 0.f};
+  // staging: element idx = tid + 512 j of a stage is (quarter idx / 1024, column block idx / 128 % 8, piece idx % 128)
+  // Staging goes from global memory straight into LDS (no registers: the accumulators leave none to
+  // spare): element idx = tid + 512 j of a stage is (quarter idx / 1024, column block idx / 128 % 8, piece
+  // idx % 128); a wave's 64 lanes fill 64 consecutive 16-byte pieces.  A column block beyond ncb gets a
+  // copy of block ncb - 1: its products are computed and never used.
+  // (with tid = 64 wave + lane: quarter = j / 2, column block = wave / 2 + 4 (j % 2), piece = 64 (wave % 2) + lane)
+  size_t bsrc[2];
+#pragma unroll
+  for (int h = 0; h < 2; ++h) bsrc[h] = (size_t)(cb0 + min((wave >> 1) + 4 * h, ncb - 1)) * KT * 128 + (wave & 1) * 64;
+  typedef const void __attribute__((address_space(1)))* gptr_t;
+  typedef void __attribute__((address_space(3)))* lptr_t;
+  auto stageB = [&](int s, uint4* stage) {
+#pragma unroll
+    for (int j = 0; j < 8; ++j)
+      __builtin_amdgcn_global_load_lds((gptr_t)(Xs + (bsrc[j & 1] + (size_t)((j >> 1) * KTq + s) * 128) + lane),
+                                       (lptr_t)(stage + wave * 64 + 512 * j), 16, 0, 0);
+  };
+  uint4 a0[H4_RB], a1[H4_RB];
+  auto fillA = [&](uint4* a, int s) {
+#pragma unroll
+    for (int r = 0; r < H4_RB; ++r) a[r] = ld_stream(Wt + (wrow[r] + (size_t)s * 64) + lane);
+  };
+  // the activation tiles of column block c + 1 are read from LDS while the matrix pipe works on block c
+  auto mma = [&](const uint4* a, const uint4* stage) {
+    const uint4* bp = stage + kq * (H4_CB * 128) + lane;
+    uint4 bh[2], bl[2];
+    bh[0] = bp[0];
+    bl[0] = bp[64];
+#pragma unroll
+    for (int c = 0; c < H4_CB; ++c) {
+      const int cur = c & 1, nxt = cur ^ 1;
+      if (c + 1 < H4_CB) {
+        bh[nxt] = bp[(c + 1) * 128];
+        bl[nxt] = bp[(c + 1) * 128 + 64];
+      }
+#pragma unroll
+      for (int r = 0; r < H4_RB; ++r)
+        acc[r][c] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, a[r]), __builtin_bit_cast(bf16x8, bh[cur]),
+                                                            acc[r][c], 0, 0, 0);
+#pragma unroll
+      for (int r = 0; r < H4_RB; ++r)
+        acc[r][c] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, a[r]), __builtin_bit_cast(bf16x8, bl[cur]),
+                                                            acc[r][c], 0, 0, 0);
+    }
+    // schedule: two LDS reads, then eight matrix instructions, eight times over
+    __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);
+#pragma unroll
+    for (int c = 0; c < H4_CB; ++c) {
+      __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);
+      __builtin_amdgcn_sched_group_barrier(0x008, 2 * H4_RB, 0);
+    }
+  };
+  // One step: request the next step's activation tiles into the other stage and the weight tiles of the
+  // step after next into the register set that is free, multiply this step's, then wait for the staging
+  // (the four weight loads behind it stay in flight) and meet the other waves.  Loads complete in order,
+  // so waiting for the staging also waits for every older load: the weight tiles are therefore requested
+  // two steps ahead and after the staging loads (three register sets), which gives them two steps to
+  // arrive; requested at the end of a step into the set just used (two sets), they had one step, and a
+  // step then lasted as long as a loaded HBM access.
+  // (the fences pin this order: the wait counts on the four weight loads being the youngest)
+  auto step = [&](const uint4* use, uint4* fill, int s, const uint4* cur, uint4* nxt) {
+    stageB(min(s + 1, KTq - 1), nxt);
+    __builtin_amdgcn_sched_barrier(0);
+    fillA(fill, min(s + 2, KTq - 1));
+    __builtin_amdgcn_sched_barrier(0);
+    mma(use, cur);
+    __builtin_amdgcn_sched_barrier(0);
+    __builtin_amdgcn_s_waitcnt(0x0F74);   // vmcnt(4): everything but the four loads just issued
+    __builtin_amdgcn_s_barrier();
+  };
+  uint4 a2[H4_RB];
+  stageB(0, st0);
+  fillA(a0, 0);
+  fillA(a1, min(1, KTq - 1));
+  __builtin_amdgcn_sched_barrier(0);
+  __builtin_amdgcn_s_waitcnt(0x0F70);     // vmcnt(0)
+  __builtin_amdgcn_s_barrier();
+  int s = 0;
+  for (; s + 6 <= KTq; s += 6) {   // stages alternate, register sets rotate: period 6
+    step(a0, a2, s, st0, st1);
+    step(a1, a0, s + 1, st1, st0);
+    step(a2, a1, s + 2, st0, st1);
+    step(a0, a2, s + 3, st1, st0);
+    step(a1, a0, s + 4, st0, st1);
+    step(a2, a1, s + 5, st1, st0);
+  }
+  const int rem = KTq - s;   // 0..5 steps left, starting again with set 0 and stage 0
+  if (rem > 0) step(a0, a2, s, st0, st1);
+  if (rem > 1) step(a1, a0, s + 1, st1, st0);
+  if (rem > 2) step(a2, a1, s + 2, st0, st1);
+  if (rem > 3) step(a0, a2, s + 3, st1, st0);
+  if (rem > 4) step(a1, a0, s + 4, st0, st1);
+  __syncthreads();
+  // sum the four k quarters into the waves of quarter 0, one quarter at a time through LDS
+  floatx4* red = (floatx4*)bs;   // [2 row groups][H4_RB][H4_CB][64 lanes]: 64 KiB = stage 0
+  for (int q = 1; q < H4_KQ; ++q) {
+    if (kq == q) {
+#pragma unroll
+      for (int r = 0; r < H4_RB; ++r)
+#pragma unroll
+        for (int c = 0; c < H4_CB; ++c) red[((rg * H4_RB + r) * H4_CB + c) * 64 + lane] = acc[r][c];
+    }
+    __syncthreads();
+    if (kq == 0) {
+#pragma unroll
+      for (int r = 0; r < H4_RB; ++r)
+#pragma unroll
+        for (int c = 0; c < H4_CB; ++c) {
+          const floatx4 v = red[((rg * H4_RB + r) * H4_CB + c) * 64 + lane];
+          acc[r][c][0] += v[0]; acc[r][c][1] += v[1]; acc[r][c][2] += v[2]; acc[r][c][3] += v[3];
+        }
+    }
+    __syncthreads();
+  }
+  // arg-max by the two waves of quarter 0: a lane holds rows 4g + j of its four row blocks for token
+  // lane % 16 of every column block.  The per-row RMS scale is positive (it cannot change the arg-max);
+  // it is applied because the stored maximum and the soft-max sums are in logit units.
+  float* wv = (float*)bs;                    // [2][H4_CB][16]
+  int* wi = (int*)(wv + 2 * H4_CB * 16);
+  float* ws = (float*)(wi + 2 * H4_CB * 16);
+  const int g = lane >> 4, token = lane & 15;
+  if (kq == 0) {
+#pragma unroll
+    for (int c = 0; c < H4_CB; ++c) {
+      const int row = (cb0 + c) * 16 + token;
+      const float sc = (c < ncb && row < R && rowscale) ? rowscale[row] : 1.0f;
+      float best = -INFINITY;
+      int bi = 0x7FFFFFFF;
+      if (c < ncb) {
+#pragma unroll
+        for (int r = 0; r < H4_RB; ++r)
+#pragma unroll
+          for (int j = 0; j < 4; ++j) {
+            const int n = (nb0 + r) * 16 + 4 * g + j;
+            const float v = acc[r][c][j] * sc;
+            if (nb0 + r < NB && n < N && v > best) { best = v; bi = n; }   // ascending n: strict > keeps the lowest index
+          }
+      }
+#pragma unroll
+      for (int o = 16; o < 64; o <<= 1) {
+        const float ov = __shfl_xor(best, o);
+        const int oi = __shfl_xor(bi, o);
+        if (ov > best || (ov == best && oi < bi)) { best = ov; bi = oi; }
+      }
+      float se = 0.f;
+      if (psum && c < ncb) {
+#pragma unroll
+        for (int r = 0; r < H4_RB; ++r)
+#pragma unroll
+          for (int j = 0; j < 4; ++j)
+            if (nb0 + r < NB && (nb0 + r) * 16 + 4 * g + j < N) se += expf(acc[r][c][j] * sc - best);
+        se += __shfl_xor(se, 16);
+        se += __shfl_xor(se, 32);
+      }
+      if (g == 0) {
+        wv[(rg * H4_CB + c) * 16 + token] = best;
+        wi[(rg * H4_CB + c) * 16 + token] = bi;
+        ws[(rg * H4_CB + c) * 16 + token] = se;
+      }
+    }
+  }
+  __syncthreads();
+  if (tid < H4_CB * 16) {
+    const int c = tid >> 4, tk = tid & 15;
+    const int row = (cb0 + c) * 16 + tk;
+    if (c < ncb && row < R) {
+      float best = -INFINITY;
+      int bi = 0x7FFFFFFF;
+      for (int w = 0; w < 2; ++w) {
+        const float v = wv[(w * H4_CB + c) * 16 + tk];
+        const int ix = wi[(w * H4_CB + c) * 16 + tk];
+        if (v > best || (v == best && ix < bi)) { best = v; bi = ix; }
+      }
+      pval[(size_t)row * NS + slab] = best;
+      pidx[(size_t)row * NS + slab] = bi;
+      if (psum) {
+        float se = 0.f;
+        for (int w = 0; w < 2; ++w) {
+          const float v = wv[(w * H4_CB + c) * 16 + tk];
+          if (v > -INFINITY) se += ws[(w * H4_CB + c) * 16 + tk] * expf(v - best);
+        }
+        psum[(size_t)row * NS + slab] = se;
+      }
+    }
+  }
+}
+
+// ---------------------------------------------------------------------------------------
 // Wide GEMM for passes over many token rows (prefill).  A work-group takes RBW row blocks of the
 // matrix times 8 * CPW blocks of 16 token rows.  The weight tiles of a k tile (RBW KiB) are staged
 // in LDS, double-buffered, and shared by the 8 waves; every wave owns CPW blocks of token rows,
@@ -1849,23 +2079,34 @@ hipError_t launch_rowscale(const float* ssq, int nb, int M, int K, float eps, fl
 
 hipError_t launch_head_gemm(const void* Wt, int NB, int KT, int N, const uint16_t* Xs, int R, const float* rowscale,
                             float* pval, int* pidx, float* psum, int* n_slabs, hipStream_t s, hipEvent_t ev_start,
-                            hipEvent_t ev_stop) {
+                            hipEvent_t ev_stop, int form) {
   if (NB <= 0 || KT <= 0 || R <= 0) return hipErrorInvalidValue;
   const int CB = (R + 15) / 16, NS = (NB + HG_W - 1) / HG_W;
   *n_slabs = NS;
-  const size_t lds = (size_t)2 * HG_CB * 128 * sizeof(uint4);
+  // form 4: the register-blocked kernel (4 row blocks x 8 column blocks per wave, k split over the waves)
+  const bool blocked = form == 4 && KT % 4 == 0;
+  const size_t lds = blocked ? 0 : (size_t)2 * HG_CB * 128 * sizeof(uint4);   // the blocked kernel's stages are static
   static bool raised = false;
-  if (!raised) {
+  if (!blocked && !raised) {
     hipError_t e = hipFuncSetAttribute((const void*)head_gemm_k, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
     if (e != hipSuccess) return e;
     raised = true;
   }
-  if (ev_start && ev_stop)
-    hipExtLaunchKernelGGL(head_gemm_k, dim3(NS, (CB + HG_CB - 1) / HG_CB), dim3(512), (uint32_t)lds, s, ev_start, ev_stop,
-                          0, (const uint4*)Wt, NB, KT, N, (const uint4*)Xs, CB, R, rowscale, pval, pidx, psum, NS);
-  else
-    hipLaunchKernelGGL(head_gemm_k, dim3(NS, (CB + HG_CB - 1) / HG_CB), dim3(512), lds, s, (const uint4*)Wt, NB, KT, N,
-                       (const uint4*)Xs, CB, R, rowscale, pval, pidx, psum, NS);
+  const dim3 grid(NS, blocked ? (CB + H4_CB - 1) / H4_CB : (CB + HG_CB - 1) / HG_CB);
+  if (blocked) {
+    if (ev_start && ev_stop)
+      hipExtLaunchKernelGGL(head_gemm4_k, grid, dim3(512), (uint32_t)lds, s, ev_start, ev_stop, 0, (const uint4*)Wt, NB, KT, N,
+                            (const uint4*)Xs, CB, R, rowscale, pval, pidx, psum, NS);
+    else
+      hipLaunchKernelGGL(head_gemm4_k, grid, dim3(512), lds, s, (const uint4*)Wt, NB, KT, N, (const uint4*)Xs, CB, R,
+                         rowscale, pval, pidx, psum, NS);
+  } else if (ev_start && ev_stop) {
+    hipExtLaunchKernelGGL(head_gemm_k, grid, dim3(512), (uint32_t)lds, s, ev_start, ev_stop, 0, (const uint4*)Wt, NB, KT, N,
+                          (const uint4*)Xs, CB, R, rowscale, pval, pidx, psum, NS);
+  } else {
+    hipLaunchKernelGGL(head_gemm_k, grid, dim3(512), lds, s, (const uint4*)Wt, NB, KT, N, (const uint4*)Xs, CB, R, rowscale,
+                       pval, pidx, psum, NS);
+  }
   return hipGetLastError();
 }
 
