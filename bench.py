@@ -320,13 +320,15 @@ def main():
         h_rows = sum(e["rows"] * e["launches"] for e in hk) / h_n
         h_bytes = sum(e["weight_bytes"] * e["launches"] for e in hk)
         h_flops = sum(2.0 * e["rows"] * cfg.d_model * cfg.vocab * e["launches"] for e in hk)
-        shadow_info = {"kernel": "head_gemm_k", "launches": h_n, "mean_rows": round(h_rows, 1),
+        blocked = os.environ.get("DEL_HEAD_FORM", "4") != "1" and (cfg.d_model // 32) % 4 == 0
+        shadow_info = {"kernel": "head_gemm4_k" if blocked else "head_gemm_k", "launches": h_n, "mean_rows": round(h_rows, 1),
                        "avg_us": round(1e3 * h_ms / h_n, 2),
                        "hbm_frac": round(h_bytes / (h_ms * 1e-3) / 1e9 / HBM_PEAK_GBS, 4),
                        "mfma_frac_model_flops": round(h_flops / (h_ms * 1e-3) / 1e12 / MFMA_BF16_PEAK_TFLOPS, 4),
                        "mfma_frac_executed": round(2 * h_flops / (h_ms * 1e-3) / 1e12 / MFMA_BF16_PEAK_TFLOPS, 4),
                        "hi_lo_factor": 2,
-                       "note": "weights streamed once per 16 blocks of 16 token rows; executed = model flops x 2"}
+                       "note": f"weights streamed once per {8 if blocked else 16} blocks of 16 token rows (hbm_frac counts every "
+                               "pass); executed = model flops x 2"}
 
     result = {
         "metric": "accepted tokens/sec at batch 1 (Llama-2-7B shape)",

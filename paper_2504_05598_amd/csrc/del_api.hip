@@ -550,7 +550,9 @@ del_status shadow_head(del_ctx* ctx, int m, int row0 = 0) {
     HIPCHK(launch_prep_split(ctx->hid_row(1, row0), R, m, (int64_t)ctx->hrows * ctx->dpad, ctx->dpad, ctx->d,
                              ctx->KTd, ctx->gain_final(), 1, ctx->cfg.rms_eps, ctx->xs_shadow, ctx->rowscale,
                              ctx->stream));
-    const int pr = prof_begin(ctx, 2, EPI_ARGMAX, R, (int64_t)ctx->NBv * ctx->KTd * 1024);
+    // the head is streamed once per group of column blocks: 8 blocks of 16 rows in the register-blocked form, 16 otherwise
+    const int cbs = (R + 15) / 16, per_pass = (ctx->head_form == 4 && ctx->KTd % 4 == 0) ? 8 : 16;
+    const int pr = prof_begin(ctx, 2, EPI_ARGMAX, R, (int64_t)((cbs + per_pass - 1) / per_pass) * ctx->NBv * ctx->KTd * 1024);
     HIPCHK(launch_head_gemm(ctx->head_t, ctx->NBv, ctx->KTd, ctx->V, ctx->xs_shadow, R, ctx->rowscale, ctx->pval,
                             ctx->pidx, ctx->psum, &nparts, ctx->stream, pr >= 0 ? ctx->prof_ev[2 * pr] : nullptr,
                             pr >= 0 ? ctx->prof_ev[2 * pr + 1] : nullptr, ctx->head_form));
