@@ -1558,12 +1558,13 @@ __global__ void __launch_bounds__(256) attn_flash_split_k(AttnP p, int S, int rp
   const uint16_t* Kb = (const uint16_t*)p.Kc + (size_t)kvh * p.Tcap * HD + 8 * g;
   const uint16_t* Vt = (const uint16_t*)p.VcT + ((size_t)kvh * HD + qi) * p.TcapT + 8 * g;
   const int rho = 8 * (qi >> 2) + (qi & 3);
-  for (int t0 = t_lo; t0 < t_hi; t0 += 32) {
-    floatx4 s0 = {0.f, 0.f, 0.f, 0.f}, s1 = {0.f, 0.f, 0.f, 0.f};
-    // rows past the pass's last one are read from that last row and masked below
+  // two register sets, filled and used in turn: the rows of the next tile are requested before the current
+  // tile is multiplied (a span is two or three tiles: without this each tile costs a full memory latency).
+  // Branch-free: an odd tile count runs one more, fully masked, tile on a re-read of the last one.
+  auto load = [&](int t0, uint4* a0, uint4* a1, uint4* av) {
+    // rows past the pass's last one are read from that last row and masked in the scores
     const uint16_t* k0 = Kb + (size_t)min(t0 + rho, t_end - 1) * HD;
     const uint16_t* k1 = Kb + (size_t)min(t0 + rho + 4, t_end - 1) * HD;
-    uint4 a0[KT], a1[KT], av[DT];
 #pragma unroll
     for (int kt = 0; kt < KT; ++kt) {
       a0[kt] = *(const uint4*)(k0 + 32 * kt);
@@ -1571,6 +1572,9 @@ __global__ void __launch_bounds__(256) attn_flash_split_k(AttnP p, int S, int rp
     }
 #pragma unroll
     for (int dt = 0; dt < DT; ++dt) av[dt] = *(const uint4*)(Vt + (size_t)(16 * dt) * p.TcapT + t0);
+  };
+  auto compute = [&](int t0, const uint4* a0, const uint4* a1, const uint4* av) {
+    floatx4 s0 = {0.f, 0.f, 0.f, 0.f}, s1 = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
     for (int kt = 0; kt < KT; ++kt) {
       const bf16x8 x0 = __builtin_bit_cast(bf16x8, a0[kt]), x1 = __builtin_bit_cast(bf16x8, a1[kt]);
@@ -1580,12 +1584,14 @@ __global__ void __launch_bounds__(256) attn_flash_split_k(AttnP p, int S, int rp
       s0 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(x0, bl, s0, 0, 0, 0);
       s1 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(x1, bl, s1, 0, 0, 0);
     }
-    // this lane: scores of cache rows t0 + 8g + e, e = 0..7, for query qi
+    // this lane: scores of cache rows t0 + 8g + e, e = 0..7, for query qi; rows of the next span (the extra
+    // tile of an odd count) and rows the query may not see count for nothing
     float sv[8] = {s0[0], s0[1], s0[2], s0[3], s1[0], s1[1], s1[2], s1[3]};
     float mx = -INFINITY;
 #pragma unroll
     for (int e = 0; e < 8; ++e) {
-      if (t0 + 8 * g + e > pos) sv[e] = -INFINITY;
+      const int row = t0 + 8 * g + e;
+      if (row > pos || row >= t_hi) sv[e] = -INFINITY;
       mx = fmaxf(mx, sv[e]);
     }
     mx = fmaxf(mx, __shfl_xor(mx, 16));
@@ -1614,6 +1620,17 @@ __global__ void __launch_bounds__(256) attn_flash_split_k(AttnP p, int S, int rp
       const bf16x8 x = __builtin_bit_cast(bf16x8, av[dt]);
       o[dt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(x, bh, o[dt], 0, 0, 0);
       o[dt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(x, bl, o[dt], 0, 0, 0);
+    }
+  };
+  {
+    const int last = t_lo + (t_hi - t_lo - 1) / 32 * 32;   // first row of the span's last tile
+    uint4 ka0[KT], ka1[KT], va[DT], kb0[KT], kb1[KT], vb[DT];
+    load(t_lo, ka0, ka1, va);
+    for (int t0 = t_lo; t0 < t_hi; t0 += 64) {
+      load(min(t0 + 32, last), kb0, kb1, vb);
+      compute(t0, ka0, ka1, va);
+      load(min(t0 + 64, last), ka0, ka1, va);
+      compute(t0 + 32, kb0, kb1, vb);
     }
   }
   if (qi >= nrow) return;
