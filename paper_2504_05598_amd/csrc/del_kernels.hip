@@ -5,6 +5,7 @@
 // del_kernels.h); activations stay fp32 on the vector path and are split into bf16 hi + lo
 // halves (16 mantissa bits together) on the matrix-core path, accumulating in fp32.
 #include "del_kernels.h"
+#include <cstdlib>
 #include <hip/hip_ext.h>
 
 namespace del {
@@ -1026,6 +1027,120 @@ __global__ void __launch_bounds__(256) rowscale_k(const float* ssq, int nb, int 
   for (int b = lane; b < nb; b += 64) q += ssq[(size_t)row * nb + b];
   for (int o = 32; o > 0; o >>= 1) q += __shfl_xor(q, o);
   if (lane == 0) rowscale[row] = 1.0f / sqrtf(q / (float)K + eps);
+}
+
+// The same wide GEMM with the loads four k tiles deep.  In the form above every k tile waits for a memory
+// latency: the weight tile goes global -> register -> LDS and the activation registers are copied from a
+// "next" set, both inside the iteration that requested them.  Here the weight tiles are written to LDS by the
+// loads themselves (a ring of 4 stages, no registers), the activation tiles sit in a ring of 4 register sets
+// that is never copied, and iteration kt requests tile kt + 3; loads complete in order, so the wait at the
+// end of an iteration leaves exactly the requests of the last two iterations and this iteration's activation
+// loads in flight.  Needs KT % 4 == 0 (the ring is unrolled) and RBW == 8 (one weight tile per wave and stage).
+template <int EPI, int RBW, int CPW>
+__global__ void __launch_bounds__(512) gemm_wide4_k(GemmP p, int NS, int NCG) {
+  static_assert(RBW == 8, "one 1 KiB weight tile per wave and stage");
+  constexpr int CBW = 8 * CPW, D = 4;
+  constexpr int LPI = 1 + 2 * CPW;              // loads per thread and iteration: the weight tile, then the activation tiles
+  // the stages as separate arrays: the compiler then knows that a load filling one stage does not touch the
+  // stage being read (otherwise LDS reads wait for every load in flight)
+  __shared__ __align__(16) uint4 as0[RBW * 64];   // reused by the epilogue ([8 waves][256] floats)
+  __shared__ __align__(16) uint4 as1[RBW * 64];
+  __shared__ __align__(16) uint4 as2[RBW * 64];
+  __shared__ __align__(16) uint4 as3[RBW * 64];
+  const int tid = threadIdx.x, wave = __builtin_amdgcn_readfirstlane(tid >> 6), lane = tid & 63;
+  const int xcd = blockIdx.x & 7, local = blockIdx.x >> 3;
+  const int cg = local % NCG, slab = (local / NCG) * 8 + xcd;
+  if (slab >= NS) return;
+  const int NB = p.NB, KT = p.KT;
+  const int CB = (p.M + 15) >> 4;
+  const int nb0 = slab * RBW, cb0 = cg * CBW + wave * CPW;
+  const uint4* Wt = (const uint4*)p.Wt;
+  const uint4* Xs = (const uint4*)p.Xs;
+  floatx4 acc[RBW][CPW];
+#pragma unroll
+  for (int r = 0; r < RBW; ++r)
+#pragma unroll
+    for (int c = 0; c < CPW; ++c) acc[r][c] = (floatx4){0.f, 0.f, 0.f, 0.f};
+  // addresses are clamped (row blocks past the matrix, token-row blocks past the pass, k tiles past the end):
+  // no branches around memory operations; such results are dropped or never used
+  const size_t wrow = (size_t)min(nb0 + wave, NB - 1) * KT * 64;   // scalar: this wave stages row block nb0 + wave
+  size_t xrow[CPW];
+#pragma unroll
+  for (int c = 0; c < CPW; ++c) xrow[c] = (size_t)min(cb0 + c, CB - 1) * KT * 128;
+  typedef const void __attribute__((address_space(1)))* gptr_t;
+  typedef void __attribute__((address_space(3)))* lptr_t;
+  uint4 bh[D][CPW], bl[D][CPW];
+  auto request = [&](int kt, int st, uint4* stage) {
+    const int k = min(kt, KT - 1);
+    __builtin_amdgcn_global_load_lds((gptr_t)(Wt + (wrow + (size_t)k * 64) + lane), (lptr_t)(stage + wave * 64), 16, 0, 0);
+    __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+    for (int c = 0; c < CPW; ++c) {
+      bh[st][c] = Xs[xrow[c] + (size_t)k * 128 + lane];
+      bl[st][c] = Xs[xrow[c] + (size_t)k * 128 + 64 + lane];
+    }
+    __builtin_amdgcn_sched_barrier(0);
+  };
+  auto multiply = [&](int st, const uint4* stage) {
+    const uint4* ap = stage + lane;
+#pragma unroll
+    for (int r = 0; r < RBW; ++r) {
+      const bf16x8 av = __builtin_bit_cast(bf16x8, ap[r * 64]);
+#pragma unroll
+      for (int c = 0; c < CPW; ++c) {
+        acc[r][c] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(av, __builtin_bit_cast(bf16x8, bh[st][c]), acc[r][c], 0, 0, 0);
+        acc[r][c] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(av, __builtin_bit_cast(bf16x8, bl[st][c]), acc[r][c], 0, 0, 0);
+      }
+    }
+  };
+  // vmcnt(n): at most n of this wave's loads still in flight (bits 3:0 and 15:14 of the immediate; the other
+  // counters left at their maximum)
+  request(0, 0, as0);
+  request(1, 1, as1);
+  request(2, 2, as2);
+  __builtin_amdgcn_s_waitcnt(0x0F70 | (2 * LPI));            // tile 0 complete (tiles 1 and 2 may be in flight)
+  __builtin_amdgcn_s_barrier();
+  auto iter = [&](int kt, int st, const uint4* cur, uint4* ahead) {
+    request(kt + 3, (st + 3) & 3, ahead);
+    multiply(st, cur);
+    __builtin_amdgcn_sched_barrier(0);
+    // the weight tile of kt + 1 was requested two iterations ago: everything younger may stay in flight
+    // (its own activation tiles, and all of the two iterations since)
+    __builtin_amdgcn_s_waitcnt(0x0F70 | (2 * CPW + 2 * LPI));
+    __builtin_amdgcn_s_barrier();
+  };
+  for (int kt = 0; kt < KT; kt += 4) {
+    iter(kt, 0, as0, as3);
+    iter(kt + 1, 1, as1, as0);
+    iter(kt + 2, 2, as2, as1);
+    iter(kt + 3, 3, as3, as2);
+  }
+  __builtin_amdgcn_s_waitcnt(0x0F70);   // the clamped requests past the end still write LDS: let them land
+  __syncthreads();
+  // epilogue: lane holds rows 4g+j of a row block for token lane%16 of a block of token rows; each
+  // wave works on an LDS patch of its own, so no barrier is needed below
+  float (*fin)[16] = reinterpret_cast<float (*)[16]>(reinterpret_cast<float*>(as0) + wave * 256);
+  const int g = lane >> 4, token = lane & 15;
+#pragma unroll
+  for (int c = 0; c < CPW; ++c) {
+    if (cb0 + c >= CB) break;
+    const int rowbase = (cb0 + c) * 16;
+    const int mvalid = min(16, p.M - rowbase);
+    const float sc = (p.rowscale && token < mvalid) ? p.rowscale[rowbase + token] : 1.0f;
+    uint16_t* xs_out = p.XsOut ? p.XsOut + (size_t)(cb0 + c) * p.xs_out_cb_stride : nullptr;
+    float* ssq_out = p.ssq_out ? p.ssq_out + (size_t)rowbase * p.NB : nullptr;
+#pragma unroll
+    for (int r = 0; r < RBW; ++r) {
+      const int nb = nb0 + r;
+      if (nb < NB) {
+#pragma unroll
+        for (int j = 0; j < 4; ++j) fin[token][4 * g + j] = acc[r][c][j] * sc;
+        __builtin_amdgcn_wave_barrier();
+        epilogue<EPI, true, true>(p, nb, fin, mvalid, rowbase, xs_out, ssq_out);
+        __builtin_amdgcn_wave_barrier();
+      }
+    }
+  }
 }
 
 // ---------------------------------------------------------------------------------------
@@ -2056,6 +2171,19 @@ namespace {
 template <int EPI, int RBW, int CPW>
 hipError_t launch_wide_inst(const GemmP& p, hipStream_t s) {
   const int CB = (p.M + 15) / 16, NS = (p.NB + RBW - 1) / RBW, NCG = (CB + 8 * CPW - 1) / (8 * CPW);
+  dim3 grid((NS + 7) / 8 * 8 * NCG), block(512);
+  static const bool deep = [] { const char* e = getenv("DEL_WIDE_FORM"); return !(e && atoi(e) == 1); }();
+  // loads four k tiles deep (static LDS) where an iteration is short against a memory latency: one block of token
+  // rows per wave.  With two blocks per wave the iteration is twice as long, two work-groups per CU already hide
+  // the latency, and the ring's registers would leave room for one work-group only (measured: 343 -> 378 us on
+  // gate/up, 220 -> 270 us on QKV, against 222 -> 146 us on the output and down projections).
+  if (deep && CPW == 1 && p.KT % 4 == 0) {
+    if (p.ev_start && p.ev_stop)
+      hipExtLaunchKernelGGL((gemm_wide4_k<EPI, RBW, CPW>), grid, block, 0, s, p.ev_start, p.ev_stop, 0, p, NS, NCG);
+    else
+      hipLaunchKernelGGL((gemm_wide4_k<EPI, RBW, CPW>), grid, block, 0, s, p, NS, NCG);
+    return hipGetLastError();
+  }
   const size_t lds = (size_t)2 * RBW * 64 * sizeof(uint4);
   static bool raised = false;
   if (!raised) {
@@ -2064,7 +2192,6 @@ hipError_t launch_wide_inst(const GemmP& p, hipStream_t s) {
     if (e != hipSuccess) return e;
     raised = true;
   }
-  dim3 grid((NS + 7) / 8 * 8 * NCG), block(512);
   if (p.ev_start && p.ev_stop)
     hipExtLaunchKernelGGL((gemm_wide_k<EPI, RBW, CPW>), grid, block, (uint32_t)lds, s, p.ev_start, p.ev_stop, 0, p, NS,
                           NCG);
