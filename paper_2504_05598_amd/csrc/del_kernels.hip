@@ -1030,23 +1030,17 @@ __global__ void __launch_bounds__(256) rowscale_k(const float* ssq, int nb, int 
 }
 
 // The same wide GEMM with the loads four k tiles deep.  In the form above every k tile waits for a memory
-// latency: the weight tile goes global -> register -> LDS and the activation registers are copied from a
-// "next" set, both inside the iteration that requested them.  Here the weight tiles are written to LDS by the
-// loads themselves (a ring of 4 stages, no registers), the activation tiles sit in a ring of 4 register sets
-// that is never copied, and iteration kt requests tile kt + 3; loads complete in order, so the wait at the
-// end of an iteration leaves exactly the requests of the last two iterations and this iteration's activation
-// loads in flight.  Needs KT % 4 == 0 (the ring is unrolled) and RBW == 8 (one weight tile per wave and stage).
+// latency: the weight tile is stored to LDS, and the activation registers are copied from a "next" set, inside
+// the iteration that requested them.  Here both sit in rings of 4 register sets that are never copied (a copy of
+// a register that a load is still filling waits for every load in flight): iteration kt requests tile kt + 3,
+// multiplies tile kt and passes the weight tile of kt + 1, requested two iterations earlier, on to LDS (two
+// stages).  Needs KT % 4 == 0 (the rings are unrolled) and RBW == 8 (one 16-byte piece of the weight tiles per thread).
 template <int EPI, int RBW, int CPW>
 __global__ void __launch_bounds__(512) gemm_wide4_k(GemmP p, int NS, int NCG) {
-  static_assert(RBW == 8, "one 1 KiB weight tile per wave and stage");
+  static_assert(RBW == 8, "one piece of the weight tiles per thread and stage");
   constexpr int CBW = 8 * CPW, D = 4;
-  constexpr int LPI = 1 + 2 * CPW;              // loads per thread and iteration: the weight tile, then the activation tiles
-  // the stages as separate arrays: the compiler then knows that a load filling one stage does not touch the
-  // stage being read (otherwise LDS reads wait for every load in flight)
   __shared__ __align__(16) uint4 as0[RBW * 64];   // reused by the epilogue ([8 waves][256] floats)
   __shared__ __align__(16) uint4 as1[RBW * 64];
-  __shared__ __align__(16) uint4 as2[RBW * 64];
-  __shared__ __align__(16) uint4 as3[RBW * 64];
   const int tid = threadIdx.x, wave = __builtin_amdgcn_readfirstlane(tid >> 6), lane = tid & 63;
   const int xcd = blockIdx.x & 7, local = blockIdx.x >> 3;
   const int cg = local % NCG, slab = (local / NCG) * 8 + xcd;
@@ -1067,56 +1061,58 @@ __global__ void __launch_bounds__(512) gemm_wide4_k(GemmP p, int NS, int NCG) {
   size_t xrow[CPW];
 #pragma unroll
   for (int c = 0; c < CPW; ++c) xrow[c] = (size_t)min(cb0 + c, CB - 1) * KT * 128;
-  typedef const void __attribute__((address_space(1)))* gptr_t;
-  typedef void __attribute__((address_space(3)))* lptr_t;
-  uint4 bh[D][CPW], bl[D][CPW];
-  auto request = [&](int kt, int st, uint4* stage) {
+  // four register sets, named (not indexed) so that every access is to a fixed register
+  uint4 ar0, ar1, ar2, ar3, bh0[CPW], bh1[CPW], bh2[CPW], bh3[CPW], bl0[CPW], bl1[CPW], bl2[CPW], bl3[CPW];
+  auto request = [&](int kt, uint4& a, uint4* h, uint4* l) {
     const int k = min(kt, KT - 1);
-    __builtin_amdgcn_global_load_lds((gptr_t)(Wt + (wrow + (size_t)k * 64) + lane), (lptr_t)(stage + wave * 64), 16, 0, 0);
-    __builtin_amdgcn_sched_barrier(0);
+    a = Wt[wrow + (size_t)k * 64 + lane];
 #pragma unroll
     for (int c = 0; c < CPW; ++c) {
-      bh[st][c] = Xs[xrow[c] + (size_t)k * 128 + lane];
-      bl[st][c] = Xs[xrow[c] + (size_t)k * 128 + 64 + lane];
+      h[c] = Xs[xrow[c] + (size_t)k * 128 + lane];
+      l[c] = Xs[xrow[c] + (size_t)k * 128 + 64 + lane];
     }
-    __builtin_amdgcn_sched_barrier(0);
   };
-  auto multiply = [&](int st, const uint4* stage) {
+  auto multiply = [&](const uint4* stage, const uint4* h, const uint4* l) {
     const uint4* ap = stage + lane;
 #pragma unroll
     for (int r = 0; r < RBW; ++r) {
       const bf16x8 av = __builtin_bit_cast(bf16x8, ap[r * 64]);
 #pragma unroll
       for (int c = 0; c < CPW; ++c) {
-        acc[r][c] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(av, __builtin_bit_cast(bf16x8, bh[st][c]), acc[r][c], 0, 0, 0);
-        acc[r][c] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(av, __builtin_bit_cast(bf16x8, bl[st][c]), acc[r][c], 0, 0, 0);
+        acc[r][c] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(av, __builtin_bit_cast(bf16x8, h[c]), acc[r][c], 0, 0, 0);
+        acc[r][c] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(av, __builtin_bit_cast(bf16x8, l[c]), acc[r][c], 0, 0, 0);
       }
     }
   };
-  // vmcnt(n): at most n of this wave's loads still in flight (bits 3:0 and 15:14 of the immediate; the other
-  // counters left at their maximum)
-  request(0, 0, as0);
-  request(1, 1, as1);
-  request(2, 2, as2);
-  __builtin_amdgcn_s_waitcnt(0x0F70 | (2 * LPI));            // tile 0 complete (tiles 1 and 2 may be in flight)
-  __builtin_amdgcn_s_barrier();
-  auto iter = [&](int kt, int st, const uint4* cur, uint4* ahead) {
-    request(kt + 3, (st + 3) & 3, ahead);
-    multiply(st, cur);
-    __builtin_amdgcn_sched_barrier(0);
-    // the weight tile of kt + 1 was requested two iterations ago: everything younger may stay in flight
-    // (its own activation tiles, and all of the two iterations since)
-    __builtin_amdgcn_s_waitcnt(0x0F70 | (2 * CPW + 2 * LPI));
-    __builtin_amdgcn_s_barrier();
-  };
-  for (int kt = 0; kt < KT; kt += 4) {
-    iter(kt, 0, as0, as3);
-    iter(kt + 1, 1, as1, as0);
-    iter(kt + 2, 2, as2, as1);
-    iter(kt + 3, 3, as3, as2);
-  }
-  __builtin_amdgcn_s_waitcnt(0x0F70);   // the clamped requests past the end still write LDS: let them land
+  request(0, ar0, bh0, bl0);
+  request(1, ar1, bh1, bl1);
+  request(2, ar2, bh2, bl2);
+  as0[tid] = ar0;
   __syncthreads();
+  // (the fences keep the requests at the top of an iteration: left alone, the scheduler sinks them below the
+  // matrix instructions, next to their first use, and the ring then hides nothing)
+  for (int kt = 0; kt < KT; kt += 4) {
+    request(kt + 3, ar3, bh3, bl3);
+    __builtin_amdgcn_sched_barrier(0);
+    multiply(as0, bh0, bl0);
+    as1[tid] = ar1;
+    __syncthreads();
+    request(kt + 4, ar0, bh0, bl0);
+    __builtin_amdgcn_sched_barrier(0);
+    multiply(as1, bh1, bl1);
+    as0[tid] = ar2;
+    __syncthreads();
+    request(kt + 5, ar1, bh1, bl1);
+    __builtin_amdgcn_sched_barrier(0);
+    multiply(as0, bh2, bl2);
+    as1[tid] = ar3;
+    __syncthreads();
+    request(kt + 6, ar2, bh2, bl2);
+    __builtin_amdgcn_sched_barrier(0);
+    multiply(as1, bh3, bl3);
+    as0[tid] = ar0;
+    __syncthreads();
+  }
   // epilogue: lane holds rows 4g+j of a row block for token lane%16 of a block of token rows; each
   // wave works on an LDS patch of its own, so no barrier is needed below
   float (*fin)[16] = reinterpret_cast<float (*)[16]>(reinterpret_cast<float*>(as0) + wave * 256);
@@ -2175,8 +2171,8 @@ hipError_t launch_wide_inst(const GemmP& p, hipStream_t s) {
   static const bool deep = [] { const char* e = getenv("DEL_WIDE_FORM"); return !(e && atoi(e) == 1); }();
   // loads four k tiles deep (static LDS) where an iteration is short against a memory latency: one block of token
   // rows per wave.  With two blocks per wave the iteration is twice as long, two work-groups per CU already hide
-  // the latency, and the ring's registers would leave room for one work-group only (measured: 343 -> 378 us on
-  // gate/up, 220 -> 270 us on QKV, against 222 -> 146 us on the output and down projections).
+  // the latency, and the rings' registers would leave room for one work-group only (measured: 330 -> 348 us on
+  // gate/up, 214 -> 244 us on QKV, against 219 -> 123 us on the output and down projections).
   if (deep && CPW == 1 && p.KT % 4 == 0) {
     if (p.ev_start && p.ev_stop)
       hipExtLaunchKernelGGL((gemm_wide4_k<EPI, RBW, CPW>), grid, block, 0, s, p.ev_start, p.ev_stop, 0, p, NS, NCG);
