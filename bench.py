@@ -297,6 +297,7 @@ def main():
         prefill_info["mfma"] = {"bound": "mfma", "kernel": pw["kernel"], "rows": pw["rows"],
                                 "achieved": round(pw_tf, 1), "peak": 2500.0, "unit": "TFLOP/s",
                                 "frac": round(pw_tf / 2500.0, 4),
+                                "model_TFLOPs": round(pw_tf / 2, 1), "frac_model_flops": round(pw_tf / 2 / 2500.0, 4),
                                 "all_wide_gemms_TFLOPs": round(4 * macs / (ms * 1e-3) / 1e12, 1),
                                 "all_wide_gemms_ms": round(ms, 2),
                                 "note": "bf16 matrix instructions executed (activations as high + low part: "
