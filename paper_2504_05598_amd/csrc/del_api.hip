@@ -145,6 +145,7 @@ struct del_ctx {
   int last_stopped = 0;
   float t_draft = 0, t_verify = 0, t_shadow = 0;
   int target_waves = 3072;
+  int wide_form = 0;          // prefill GEMMs: 1 = the two-stage form for every matrix (DEL_WIDE_FORM)
   int head_form = 4;          // shadow-head kernel: 4 = register-blocked, 1 = one row block per wave (DEL_HEAD_FORM)
   // Optional (DEL_GRAPHS=1): the segments of a round are captured once per (kind, E, gamma) into HIP
   // graphs and replayed; positions and token ids live in device memory, so a graph depends on
@@ -440,6 +441,7 @@ del_status run_layer_wide(del_ctx* ctx, int l, int m, bool chained) {
   float* hout = ctx->hid_row(l, 0);
   auto wide = [&](GemmP& p, int epi) -> del_status {
     p.M = m;
+    p.wide_form = ctx->wide_form;
     const int pr = prof_begin(ctx, 3, epi, m, (int64_t)p.NB * p.KT * 1024);
     if (pr >= 0) { p.ev_start = ctx->prof_ev[2 * pr]; p.ev_stop = ctx->prof_ev[2 * pr + 1]; }
     HIPCHK(launch_gemm_wide(p, epi, s));
@@ -686,6 +688,7 @@ del_status del_create(const del_config* cfg, void* hip_stream, del_ctx** out) {
     const int v = atoi(tw);
     if (v >= 64 && v <= 65536) ctx->target_waves = v;
   }
+  if (const char* wf = getenv("DEL_WIDE_FORM")) ctx->wide_form = atoi(wf) == 1 ? 1 : 0;
   if (const char* hf = getenv("DEL_HEAD_FORM")) {
     const int v = atoi(hf);
     if (v == 1 || v == 4) ctx->head_form = v;

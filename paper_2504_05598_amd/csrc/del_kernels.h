@@ -72,6 +72,8 @@ struct GemmP {
   // host side only: when both are set the launch records the kernel's own start and stop
   // timestamps into these events (per-kernel profiling)
   hipEvent_t ev_start, ev_stop;
+  // host side only, wide GEMM: 1 = the two-stage form for every matrix (default 0: the four-deep form where it applies)
+  int wide_form;
 };
 
 struct AttnP {

@@ -5,7 +5,6 @@
 // del_kernels.h); activations stay fp32 on the vector path and are split into bf16 hi + lo
 // halves (16 mantissa bits together) on the matrix-core path, accumulating in fp32.
 #include "del_kernels.h"
-#include <cstdlib>
 #include <hip/hip_ext.h>
 
 namespace del {
@@ -1038,7 +1037,7 @@ __global__ void __launch_bounds__(256) rowscale_k(const float* ssq, int nb, int 
 template <int EPI, int RBW, int CPW>
 __global__ void __launch_bounds__(512) gemm_wide4_k(GemmP p, int NS, int NCG) {
   static_assert(RBW == 8, "one piece of the weight tiles per thread and stage");
-  constexpr int CBW = 8 * CPW, D = 4;
+  constexpr int CBW = 8 * CPW;
   __shared__ __align__(16) uint4 as0[RBW * 64];   // reused by the epilogue ([8 waves][256] floats)
   __shared__ __align__(16) uint4 as1[RBW * 64];
   const int tid = threadIdx.x, wave = __builtin_amdgcn_readfirstlane(tid >> 6), lane = tid & 63;
@@ -2168,7 +2167,7 @@ template <int EPI, int RBW, int CPW>
 hipError_t launch_wide_inst(const GemmP& p, hipStream_t s) {
   const int CB = (p.M + 15) / 16, NS = (p.NB + RBW - 1) / RBW, NCG = (CB + 8 * CPW - 1) / (8 * CPW);
   dim3 grid((NS + 7) / 8 * 8 * NCG), block(512);
-  static const bool deep = [] { const char* e = getenv("DEL_WIDE_FORM"); return !(e && atoi(e) == 1); }();
+  const bool deep = p.wide_form != 1;
   // loads four k tiles deep (static LDS) where an iteration is short against a memory latency: one block of token
   // rows per wave.  With two blocks per wave the iteration is twice as long, two work-groups per CU already hide
   // the latency, and the rings' registers would leave room for one work-group only (measured: 330 -> 348 us on

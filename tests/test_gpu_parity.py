@@ -297,6 +297,22 @@ def test_unsplit_attention_for_multi_row_passes(name, monkeypatch):
     ctx.close()
 
 
+@pytest.mark.parametrize("switch", ["DEL_HEAD_FORM=1", "DEL_WIDE_FORM=1", "DEL_VERIFY_FLASH=0", "DEL_TARGET_WAVES=8192"])
+@pytest.mark.parametrize("name", ["mini_gqa", "mini_mha"])
+def test_alternative_kernel_forms_give_the_same_rounds(name, switch, monkeypatch):
+    """The kernel forms the defaults do not take stay correct: the shadow head with one row block per wave,
+    the two-stage wide GEMM for every prefill matrix, the vector-ALU attention in the verify passes, 16 waves
+    per row block for every GEMV (the switches are read when the context is created)."""
+    from gpu_harness import lockstep
+    key, val = switch.split("=")
+    monkeypatch.setenv(key, val)
+    cfg, ctx, oracle = _setup(name)
+    monkeypatch.delenv(key)
+    rep = lockstep(cfg, oracle, ctx, gen_prompt(cfg).tolist(), cfg.gen_len)
+    _check_report(rep, f"{name} {switch}")
+    ctx.close()
+
+
 def test_paper_d_max_18_rounds_of_more_than_16_rows():
     """Appendix B.2's d_max = 18: rounds whose verify pass has up to 19 rows (more than one block of 16
     token rows), fixed long schedules and the DEL-driven run, on the matrix-core and on the vector path."""
