@@ -145,6 +145,7 @@ struct del_ctx {
   int last_stopped = 0;
   float t_draft = 0, t_verify = 0, t_shadow = 0;
   int target_waves = 3072;
+  int rows_form = 0;          // one-row GEMV: 1 = one row block per work-group for every matrix (DEL_ROWS_FORM)
   int wide_form = 0;          // prefill GEMMs: 1 = the two-stage form for every matrix (DEL_WIDE_FORM)
   int head_form = 4;          // shadow-head kernel: 4 = register-blocked, 1 = one row block per wave (DEL_HEAD_FORM)
   // Optional (DEL_GRAPHS=1): the segments of a round are captured once per (kind, E, gamma) into HIP
@@ -294,6 +295,7 @@ GemmP base_gemm(const del_ctx* ctx) {
   memset(&p, 0, sizeof(p));
   p.wdtype = ctx->wd;
   p.eps = ctx->cfg.rms_eps;
+  p.rows_form = ctx->rows_form;
   return p;
 }
 
@@ -689,6 +691,7 @@ del_status del_create(const del_config* cfg, void* hip_stream, del_ctx** out) {
     if (v >= 64 && v <= 65536) ctx->target_waves = v;
   }
   if (const char* wf = getenv("DEL_WIDE_FORM")) ctx->wide_form = atoi(wf) == 1 ? 1 : 0;
+  if (const char* rf = getenv("DEL_ROWS_FORM")) ctx->rows_form = atoi(rf) == 1 ? 1 : 0;
   if (const char* hf = getenv("DEL_HEAD_FORM")) {
     const int v = atoi(hf);
     if (v == 1 || v == 4) ctx->head_form = v;

@@ -74,6 +74,9 @@ struct GemmP {
   hipEvent_t ev_start, ev_stop;
   // host side only, wide GEMM: 1 = the two-stage form for every matrix (default 0: the four-deep form where it applies)
   int wide_form;
+  // host side only, one-row GEMV: 1 = one row block per work-group for every matrix (default 0: several row blocks per
+  // work-group where the shape allows)
+  int rows_form;
 };
 
 struct AttnP {
