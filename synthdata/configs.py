@@ -95,6 +95,10 @@ CONFIGS = {
     # the paper's cap on the speculation length (Appendix B.2: d_max = 18): rounds of more than 16 rows
     "mini_d18": ModelConfig("mini_d18", 5, 512, 8, 2, 64, 1384, 5000, 1e4, False, "bf16", 0.6,
                             40, 64, 18, 15, norm_gain_std=0.1),
+    # d_model of the 7B shape on three layers: 128 k tiles per row and at least 256 row blocks in every matrix
+    # (the shapes for which the one-row GEMV takes several row blocks per work-group), ragged vocabulary
+    "wide_d4096": ModelConfig("wide_d4096", 3, 4096, 32, 8, 128, 4096, 4111, 1e4, False, "bf16", 0.6,
+                              40, 40, 6, 16, norm_gain_std=0.1),
     "mini_fp32": ModelConfig("mini_fp32", 3, 192, 6, 2, 32, 520, 3000, 1e4, False, "fp32", 0.6,
                              21, 24, 5, 13, norm_gain_std=0.1),
 }

@@ -313,6 +313,25 @@ def test_alternative_kernel_forms_give_the_same_rounds(name, switch, monkeypatch
     ctx.close()
 
 
+@pytest.mark.parametrize("rows_form", ["0", "1"])
+def test_model_width_4096_both_forms_of_the_one_row_gemv(rows_form, monkeypatch):
+    """d_model 4096 (128 k tiles per row) with 256 or more row blocks in every matrix: the draft path's GEMVs take
+    several row blocks per work-group (form 0, the default for such shapes) or one (form 1); greedy rounds and
+    rounds with draft-exiting, in lock-step with the oracle."""
+    from gpu_harness import lockstep
+    monkeypatch.setenv("DEL_ROWS_FORM", rows_form)
+    cfg, ctx, oracle = _setup("wide_d4096")
+    monkeypatch.delenv("DEL_ROWS_FORM")
+    prompt = gen_prompt(cfg).tolist()
+    rep = lockstep(cfg, oracle, ctx, prompt, cfg.gen_len)
+    _check_report(rep, f"wide_d4096 rows_form={rows_form}")
+    rep = lockstep(cfg, oracle, ctx, prompt, 24, dynamic=True)
+    _check_report(rep, f"wide_d4096 rows_form={rows_form} dynamic")
+    rep = lockstep(cfg, oracle, ctx, prompt, 32, schedule=(2, 3))     # draft heads and multi-row verify
+    _check_report(rep, f"wide_d4096 rows_form={rows_form} E=2 gamma=3")
+    ctx.close()
+
+
 def test_paper_d_max_18_rounds_of_more_than_16_rows():
     """Appendix B.2's d_max = 18: rounds whose verify pass has up to 19 rows (more than one block of 16
     token rows), fixed long schedules and the DEL-driven run, on the matrix-core and on the vector path."""
