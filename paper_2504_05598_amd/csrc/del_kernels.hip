@@ -691,6 +691,117 @@ __global__ void __launch_bounds__(1024) gemm_mfma_k(GemmP p) {
 }
 
 // ---------------------------------------------------------------------------------------
+// The matrix-core skinny GEMM with several row blocks per work-group (up to 16 token rows, KT = 128):
+// as gemv_rows_k, one work-group of 16 waves per compute unit taking the row blocks w, w + grid, ...  A wave
+// owns 8 k tiles of every row block; the split activation tiles of those 8 k tiles do not depend on the row
+// block, so they are loaded once and stay in registers for all of the work-group's row blocks (the form
+// above fetches them again with every weight tile: two of its three loads).  Weight tiles: two named sets
+// of 4, refilled as soon as used, running on into the next row block.  Wave 0 sums the waves' 16x16 partials
+// and runs the epilogue while the others go on.
+// ---------------------------------------------------------------------------------------
+template <int EPI>
+__global__ void __launch_bounds__(1024) gemm_mfma_rows_k(GemmP p) {
+  constexpr int NG = 2;
+  __shared__ float red[2][ROWS_WAVES][16][16];
+  __shared__ float fin[16][16];
+  __shared__ float scl[16];
+  const int tid = threadIdx.x, wave = __builtin_amdgcn_readfirstlane(tid >> 6), lane = tid & 63;
+  const int wg = blockIdx.x, nwg = gridDim.x;
+  if (wg >= p.NB) return;                                // uniform, before any barrier
+  const int nblk = (p.NB - wg + nwg - 1) / nwg;
+  const int KT = p.KT;                                   // = 128
+  const int mvalid = min(16, p.M);
+  const int token = lane & 15, g = lane >> 4;
+  const int blane = token < mvalid ? lane : (lane & 48);   // lanes of rows beyond the valid ones re-read token row 0
+  const int lo_t = wave * NG * GU;
+  // this wave's activation tiles (high and low parts) for its 8 k tiles: loaded once
+  uint4 bh[NG * GU], bl[NG * GU];
+  const uint4* xp = (const uint4*)p.Xs + (size_t)lo_t * 128 + blane;
+#pragma unroll
+  for (int i = 0; i < NG * GU; ++i) {
+    bh[i] = xp[i * 128];
+    bl[i] = xp[i * 128 + 64];
+  }
+  const size_t blk_stride = (size_t)nwg * KT * 64;
+  const uint4* wp = (const uint4*)p.Wt + ((size_t)wg * KT + lo_t) * 64 + lane;
+  // weight tiles: two named sets of HS = 2 tiles (the activation tiles leave registers for no more: 16 waves per
+  // work-group cap a wave at 128), each refilled as soon as used
+  constexpr int HS = 2;
+  uint4 ta[HS], tb[HS];
+  auto fill = [&](uint4* t, const uint4* src) {
+#pragma unroll
+    for (int u = 0; u < HS; ++u) t[u] = ld_stream(src + u * 64);
+  };
+  fill(ta, wp);
+  fill(tb, wp + HS * 64);
+  if (p.ssq_in) {   // RMS scale per token row from the producer's per-block sums of squares
+    for (int mi = wave; mi < mvalid; mi += ROWS_WAVES) {
+      float q = 0.f;
+      for (int b = lane; b < p.ssq_nb; b += 64) q += p.ssq_in[(size_t)mi * p.ssq_nb + b];
+      for (int o = 32; o > 0; o >>= 1) q += __shfl_xor(q, o);
+      if (lane == 0) scl[mi] = 1.0f / sqrtf(q / (float)p.K + p.eps);
+    }
+  }
+  __syncthreads();
+  int par = 0;
+  auto finish = [&](const floatx4& acc, int nb) {
+    // D layout: lane holds D[4*(lane/16) + j][lane%16], j = 0..3 (rows = weight rows, cols = tokens)
+#pragma unroll
+    for (int j = 0; j < 4; ++j) red[par][wave][token][4 * g + j] = acc[j];
+    __builtin_amdgcn_s_waitcnt(0xC07F);   // lgkmcnt(0)
+    __builtin_amdgcn_s_barrier();
+    if (wave == 0) {
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        const int t = lane + 64 * i, mi = t >> 4, r = t & 15;
+        if (mi < mvalid) {
+          float s = 0.f;
+          for (int w = 0; w < ROWS_WAVES; ++w) s += red[par][w][mi][r];
+          if (p.rowscale) s *= p.rowscale[mi];
+          if (p.ssq_in) s *= scl[mi];
+          fin[mi][r] = s;
+        }
+      }
+      __builtin_amdgcn_wave_barrier();
+      epilogue<EPI, true, true>(p, nb, fin, mvalid, 0, p.XsOut, p.ssq_out);
+      __builtin_amdgcn_wave_barrier();
+    }
+    par ^= 1;
+  };
+  auto block = [&](int nb, bool more) {
+    floatx4 acc = {0.f, 0.f, 0.f, 0.f};
+    const uint4* wn = wp + blk_stride;
+    auto use = [&](const uint4* t, int i0) {
+#pragma unroll
+      for (int u = 0; u < HS; ++u) {
+        const bf16x8 av = __builtin_bit_cast(bf16x8, t[u]);
+        acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(av, __builtin_bit_cast(bf16x8, bh[i0 + u]), acc, 0, 0, 0);
+        acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(av, __builtin_bit_cast(bf16x8, bl[i0 + u]), acc, 0, 0, 0);
+      }
+    };
+    constexpr int NT = NG * GU;   // this wave's tiles of a row block
+#pragma unroll
+    for (int i0 = 0; i0 < NT; i0 += 2 * HS) {
+      use(ta, i0);
+      __builtin_amdgcn_sched_barrier(0);
+      if (i0 + 2 * HS < NT) fill(ta, wp + (size_t)(i0 + 2 * HS) * 64);
+      else if (more) fill(ta, wn);
+      __builtin_amdgcn_sched_barrier(0);
+      use(tb, i0 + HS);
+      __builtin_amdgcn_sched_barrier(0);
+      if (i0 + 3 * HS < NT) fill(tb, wp + (size_t)(i0 + 3 * HS) * 64);
+      else if (more) fill(tb, wn + HS * 64);
+      __builtin_amdgcn_sched_barrier(0);
+    }
+    finish(acc, nb);
+    wp = wn;
+  };
+  int nb = wg;
+  for (int b = 0; b + 1 < nblk; ++b, nb += nwg) block(nb, true);
+  block(nb, false);
+}
+
+// ---------------------------------------------------------------------------------------
 // Shadow-head GEMM with a fused arg-max (Section 4.2: every layer's hidden states through the
 // LM head in one pass): logits of R = L*(gamma+1) rows never leave the chip.  One work-group =
 // 8 waves = a slab of 8 consecutive 16-row blocks of the head, times up to 16 column blocks of
@@ -2323,8 +2434,26 @@ hipError_t launch_gemm_mfma(const GemmP& p, int epi, int waves, int col_blocks, 
   if (waves < 1 || waves > MAXW || p.NB <= 0 || p.KT <= 0 || p.wdtype != 1 || col_blocks < 1 ||
       p.M > col_blocks * 16 || p.M <= (col_blocks - 1) * 16)
     return hipErrorInvalidValue;
-  dim3 grid(p.NB, col_blocks), block(64 * waves);
   const bool timed = p.ev_start && p.ev_stop;
+  if (col_blocks == 1 && p.KT == 128 && p.NB >= ROWS_GRID && p.rows_form != 1 && epi != EPI_RESID) {
+    // several row blocks per work-group, the activation tiles held in registers (not with the residual
+    // epilogue: that instantiation does not fit 128 registers, and its matrices have one row block per
+    // work-group anyway)
+    const dim3 rgrid(ROWS_GRID), rblock(64 * ROWS_WAVES);
+#define MFMA_ROWS(E)                                                                                              \
+  if (timed) hipExtLaunchKernelGGL((gemm_mfma_rows_k<E>), rgrid, rblock, 0, s, p.ev_start, p.ev_stop, 0, p);       \
+  else hipLaunchKernelGGL((gemm_mfma_rows_k<E>), rgrid, rblock, 0, s, p);                                           \
+  return hipGetLastError();
+    switch (epi) {
+      case EPI_STORE: MFMA_ROWS(EPI_STORE)
+      case EPI_QKV: MFMA_ROWS(EPI_QKV)
+      case EPI_SWIGLU: MFMA_ROWS(EPI_SWIGLU)
+      case EPI_ARGMAX: MFMA_ROWS(EPI_ARGMAX)
+      default: return hipErrorInvalidValue;
+    }
+#undef MFMA_ROWS
+  }
+  dim3 grid(p.NB, col_blocks), block(64 * waves);
   switch (epi) {
     case EPI_STORE:
       if (timed) hipExtLaunchKernelGGL((gemm_mfma_k<EPI_STORE>), grid, block, 0, s, p.ev_start, p.ev_stop, 0, p);
