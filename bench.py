@@ -314,15 +314,15 @@ def main():
     # the shadow-head GEMM (Section 4.2): rows, HBM and matrix-core fractions; model flops = 2 * rows * d * V, the
     # matrix cores execute twice that (activations enter as a bf16 high and low part)
     shadow_info = None
-    hk = [e for e in prof if e["kernel"] == "head_gemm_k"]
+    hk = [e for e in prof if e["kernel"] in ("head_gemm_k", "head_gemm4_k")]
     if hk:
         h_ms = sum(e["total_ms"] for e in hk)
         h_n = sum(e["launches"] for e in hk)
         h_rows = sum(e["rows"] * e["launches"] for e in hk) / h_n
         h_bytes = sum(e["weight_bytes"] * e["launches"] for e in hk)
         h_flops = sum(2.0 * e["rows"] * cfg.d_model * cfg.vocab * e["launches"] for e in hk)
-        blocked = os.environ.get("DEL_HEAD_FORM", "4") != "1" and (cfg.d_model // 32) % 4 == 0
-        shadow_info = {"kernel": "head_gemm4_k" if blocked else "head_gemm_k", "launches": h_n, "mean_rows": round(h_rows, 1),
+        blocked = hk[0]["kernel"] == "head_gemm4_k"
+        shadow_info = {"kernel": hk[0]["kernel"], "launches": h_n, "mean_rows": round(h_rows, 1),
                        "avg_us": round(1e3 * h_ms / h_n, 2),
                        "hbm_frac": round(h_bytes / (h_ms * 1e-3) / 1e9 / HBM_PEAK_GBS, 4),
                        "mfma_frac_model_flops": round(h_flops / (h_ms * 1e-3) / 1e12 / MFMA_BF16_PEAK_TFLOPS, 4),

@@ -195,7 +195,8 @@ del_status del_bench_stream_copy(del_ctx* ctx, int64_t bytes, int32_t iters, flo
  * carries a pair of HIP events that receive the kernel's own start and stop timestamps
  * (hipExtLaunchKernel); per kernel class the launch count and the summed duration are
  * accumulated (throughput is still measured with profiling off).  A class is one kernel instantiation:
- * flavour (0 vector-ALU GEMV/GEMM, 1 matrix-core skinny GEMM, 2 shadow-head GEMM, 3 wide prefill GEMM), epilogue (0 store, 1 residual, 2 qkv+rotary,
+ * flavour (0 vector-ALU GEMV/GEMM, 1 matrix-core skinny GEMM, 2 shadow-head GEMM, 3 wide prefill GEMM, 4 and 5: the forms of 0 (one row)
+ * and 1 that take several row blocks per work-group, 6: the register-blocked form of 2), epilogue (0 store, 1 residual, 2 qkv+rotary,
  * 3 swiglu, 4 argmax), rows m, matrix size.  weight_bytes is what one launch of the class streams. */
 typedef struct {
   int32_t flavour, epilogue, rows, launches;

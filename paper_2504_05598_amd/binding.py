@@ -418,6 +418,12 @@ class DelContext:
     def profile_enable(self, on: bool) -> None:
         _check(load_library().del_profile_enable(self.ctx, int(on)), self.ctx)
 
+    def _rows_ng(self, e):
+        """Template argument NG of gemv_rows_k (k tiles = 64 * NG): the input width is the model width,
+        except with the residual epilogue (1), where it follows from the bytes of the [d_model, K] matrix."""
+        k = e.weight_bytes // (2 * self.cfg.d_model) if e.epilogue == 1 else self.cfg.d_model
+        return k // 2048
+
     def profile_read(self) -> List[dict]:
         cap = 256
         arr = (del_prof_entry * cap)()
@@ -429,8 +435,11 @@ class DelContext:
             if e.launches:
                 kernel = (f"gemm_valu_k<8,{e.rows},{e.epilogue}>" if e.flavour == 0
                           else f"gemm_mfma_k<{e.epilogue}>" if e.flavour == 1
-                          else f"gemm_wide_k<{e.epilogue}>" if e.flavour == 3 else "head_gemm_k")
-                out.append({"kernel": kernel, "flavour": ("valu", "mfma", "mfma", "mfma")[e.flavour],
+                          else f"gemm_wide_k<{e.epilogue}>" if e.flavour == 3
+                          else f"gemv_rows_k<{self._rows_ng(e)},{e.epilogue}>" if e.flavour == 4
+                          else f"gemm_mfma_rows_k<{e.epilogue}>" if e.flavour == 5
+                          else "head_gemm4_k" if e.flavour == 6 else "head_gemm_k")
+                out.append({"kernel": kernel, "flavour": ("valu", "mfma", "mfma", "mfma", "valu", "mfma", "mfma")[e.flavour],
                             "epilogue": names[e.epilogue], "rows": e.rows, "launches": e.launches,
                             "total_ms": e.total_ms, "avg_us": 1e3 * e.total_ms / e.launches,
                             "weight_bytes": e.weight_bytes})

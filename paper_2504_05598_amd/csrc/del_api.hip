@@ -261,7 +261,7 @@ del_status gemm(del_ctx* ctx, GemmP p, int epi, int m, bool mfma) {
       q.Xs = ctx->xs_layer;
       q.rowscale = q.rms ? ctx->rowscale : nullptr;
       q.M = mb;
-      const int pr = prof_begin(ctx, 1, epi, mb, wbytes);
+      const int pr = prof_begin(ctx, gemm_mfma_rows_applies(q, epi, 1) ? 5 : 1, epi, mb, wbytes);
       if (pr >= 0) { q.ev_start = ctx->prof_ev[2 * pr]; q.ev_stop = ctx->prof_ev[2 * pr + 1]; }
       HIPCHK(launch_gemm_mfma(q, epi, waves, 1, ctx->stream));
       prof_end(ctx, pr);
@@ -281,7 +281,7 @@ del_status gemm(del_ctx* ctx, GemmP p, int epi, int m, bool mfma) {
     if (q.ACT) q.ACT = p.ACT + (size_t)off * p.ldact;
     q.row_off = p.row_off + off;
     q.prow0 = p.prow0 + off;
-    const int pr = prof_begin(ctx, 0, epi, g, wbytes);
+    const int pr = prof_begin(ctx, gemv_rows_applies(q) ? 4 : 0, epi, g, wbytes);
     if (pr >= 0) { q.ev_start = ctx->prof_ev[2 * pr]; q.ev_stop = ctx->prof_ev[2 * pr + 1]; }
     HIPCHK(launch_gemm_valu(q, epi, waves, ctx->stream));
     prof_end(ctx, pr);
@@ -303,7 +303,7 @@ GemmP base_gemm(const del_ctx* ctx) {
 del_status gemm_mf(del_ctx* ctx, GemmP p, int epi, int m) {
   const int waves = ctx->pick_waves(p.NB, p.KT);
   p.M = m;
-  const int pr = prof_begin(ctx, 1, epi, m, (int64_t)p.NB * p.KT * 1024);
+  const int pr = prof_begin(ctx, gemm_mfma_rows_applies(p, epi, 1) ? 5 : 1, epi, m, (int64_t)p.NB * p.KT * 1024);
   if (pr >= 0) { p.ev_start = ctx->prof_ev[2 * pr]; p.ev_stop = ctx->prof_ev[2 * pr + 1]; }
   HIPCHK(launch_gemm_mfma(p, epi, waves, 1, ctx->stream));
   prof_end(ctx, pr);
@@ -556,7 +556,7 @@ del_status shadow_head(del_ctx* ctx, int m, int row0 = 0) {
                              ctx->stream));
     // the head is streamed once per group of column blocks: 8 blocks of 16 rows in the register-blocked form, 16 otherwise
     const int cbs = (R + 15) / 16, per_pass = (ctx->head_form == 4 && ctx->KTd % 4 == 0) ? 8 : 16;
-    const int pr = prof_begin(ctx, 2, EPI_ARGMAX, R, (int64_t)((cbs + per_pass - 1) / per_pass) * ctx->NBv * ctx->KTd * 1024);
+    const int pr = prof_begin(ctx, per_pass == 8 ? 6 : 2, EPI_ARGMAX, R, (int64_t)((cbs + per_pass - 1) / per_pass) * ctx->NBv * ctx->KTd * 1024);
     HIPCHK(launch_head_gemm(ctx->head_t, ctx->NBv, ctx->KTd, ctx->V, ctx->xs_shadow, R, ctx->rowscale, ctx->pval,
                             ctx->pidx, ctx->psum, &nparts, ctx->stream, pr >= 0 ? ctx->prof_ev[2 * pr] : nullptr,
                             pr >= 0 ? ctx->prof_ev[2 * pr + 1] : nullptr, ctx->head_form));

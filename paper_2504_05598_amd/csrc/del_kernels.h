@@ -101,6 +101,11 @@ struct AttnP {
 };
 
 hipError_t launch_gemm_valu(const GemmP& p, int epi, int waves, hipStream_t s);
+// Which kernel the two launchers here take for p: the forms with several row blocks per work-group
+// (gemv_rows_k: one row, bf16, 128 or 256 k tiles, at least 256 row blocks; gemm_mfma_rows_k: up to 16 rows,
+// 128 k tiles, at least 256 row blocks, any epilogue but the residual one), unless p.rows_form == 1.
+bool gemv_rows_applies(const GemmP& p);
+bool gemm_mfma_rows_applies(const GemmP& p, int epi, int col_blocks);
 hipError_t launch_gemm_mfma(const GemmP& p, int epi, int waves, int col_blocks, hipStream_t s);
 // Shadow-head GEMM with fused arg-max over R rows; partials are [R][*n_slabs].  form 4: the register-blocked
 // kernel (needs KT % 4 == 0, otherwise the other one runs); any other value: one row block per wave.

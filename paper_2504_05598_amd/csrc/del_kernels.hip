@@ -2421,12 +2421,18 @@ static hipError_t launch_valu_k(const GemmP& p, int epi, int waves, hipStream_t 
   }
 }
 
+bool gemv_rows_applies(const GemmP& p) {
+  return p.wdtype == 1 && p.M == 1 && p.rows_form != 1 && p.NB >= ROWS_GRID && !p.XsOut && (p.KT == 128 || p.KT == 256);
+}
+bool gemm_mfma_rows_applies(const GemmP& p, int epi, int col_blocks) {
+  // (not with the residual epilogue: that instantiation does not fit 128 registers, and its matrices have one row
+  // block per work-group anyway)
+  return col_blocks == 1 && p.KT == 128 && p.NB >= ROWS_GRID && p.rows_form != 1 && epi != EPI_RESID;
+}
+
 hipError_t launch_gemm_valu(const GemmP& p, int epi, int waves, hipStream_t s) {
   if (waves < 1 || waves > MAXW || p.NB <= 0 || p.KT <= 0) return hipErrorInvalidValue;
-  if (p.wdtype == 1 && p.M == 1 && p.rows_form != 1 && p.NB >= ROWS_GRID && !p.XsOut) {
-    if (p.KT == 128) return launch_rows<2>(p, epi, s);
-    if (p.KT == 256) return launch_rows<4>(p, epi, s);
-  }
+  if (gemv_rows_applies(p)) return p.KT == 128 ? launch_rows<2>(p, epi, s) : launch_rows<4>(p, epi, s);
   return p.wdtype == 1 ? launch_valu_k<8>(p, epi, waves, s) : launch_valu_k<4>(p, epi, waves, s);
 }
 
@@ -2435,10 +2441,8 @@ hipError_t launch_gemm_mfma(const GemmP& p, int epi, int waves, int col_blocks, 
       p.M > col_blocks * 16 || p.M <= (col_blocks - 1) * 16)
     return hipErrorInvalidValue;
   const bool timed = p.ev_start && p.ev_stop;
-  if (col_blocks == 1 && p.KT == 128 && p.NB >= ROWS_GRID && p.rows_form != 1 && epi != EPI_RESID) {
-    // several row blocks per work-group, the activation tiles held in registers (not with the residual
-    // epilogue: that instantiation does not fit 128 registers, and its matrices have one row block per
-    // work-group anyway)
+  if (gemm_mfma_rows_applies(p, epi, col_blocks)) {
+    // several row blocks per work-group, the activation tiles held in registers
     const dim3 rgrid(ROWS_GRID), rblock(64 * ROWS_WAVES);
 #define MFMA_ROWS(E)                                                                                              \
   if (timed) hipExtLaunchKernelGGL((gemm_mfma_rows_k<E>), rgrid, rblock, 0, s, p.ev_start, p.ev_stop, 0, p);       \
