@@ -270,7 +270,7 @@ del_status gemm(del_ctx* ctx, GemmP p, int epi, int m, bool mfma) {
   }
   int off = 0;
   while (off < m) {
-    int g = 8;
+    int g = p.wdtype == DEL_DTYPE_BF16 ? 2 : 8;   // 16-bit weights unpack to twice the registers per tile: two rows at most
     while (g > m - off) g >>= 1;
     GemmP q = p;
     q.M = g;
@@ -722,7 +722,7 @@ del_status del_create(const del_config* cfg, void* hip_stream, del_ctx** out) {
     ctx->attn_S = std::max(1, std::min(std::min(8, ctx->nch_max), ceil_div(128, ctx->nkv)));
     if (const char* e = getenv("DEL_ATTN_SPLITS")) {
       const int v = atoi(e);
-      if (v >= 0 && v <= std::min(16, ctx->nch_max)) ctx->attn_S = v;   // 0: staged kernels everywhere
+      if (v >= 0 && v <= std::min(8, ctx->nch_max)) ctx->attn_S = v;   // 0: staged kernels everywhere; 8: what the merge in the output projection takes
     }
     // enough rows give enough work-groups (rows x kv heads >= 192) without splitting the context
     ctx->attn_direct_rows = std::max(2, ceil_div(192, ctx->nkv));

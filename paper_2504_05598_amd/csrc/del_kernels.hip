@@ -224,7 +224,50 @@ __device__ __forceinline__ void wave_span(int KT, int nw, int wave, int grp, int
 }
 
 // ---------------------------------------------------------------------------------------
-// Vector-ALU GEMV (M = 1) / skinny GEMM (M = 2, 4, 8): one work-group per 16-row block; each
+// The input row of the one-row output projection is the attention output, handed over as att_S <= ATT_SMAX
+// per-split softmax partials (max, sum, weighted values): merged while the row is staged.  Request and merge
+// are separate steps: all loads of a lane's four features go out at once, with the split index clamped
+// instead of a branch around the load, so that a caller can put its weight-tile requests between the two and
+// wait for the partials alone; the sums run over the splits in ascending order.
+// ---------------------------------------------------------------------------------------
+constexpr int ATT_SMAX = 8;
+struct AttReq {
+  float pm[ATT_SMAX], pl[ATT_SMAX];
+  float4 pa[ATT_SMAX];
+};
+__device__ __forceinline__ void att_request(const GemmP& p, int k, AttReq& r) {
+  const int kc = min(k, p.K - 4);            // features past K (padding) merge to zero: any valid address will do
+  const int h = kc / p.att_hd, d = kc - h * p.att_hd;
+  const size_t row = (size_t)h * p.att_stride;
+#pragma unroll
+  for (int s = 0; s < ATT_SMAX; ++s) {
+    const int sc = min(s, p.att_S - 1);
+    r.pm[s] = p.att_PM[row + sc];
+    r.pl[s] = p.att_PL[row + sc];
+    r.pa[s] = *(const float4*)(p.att_PA + (row + sc) * p.att_hd + d);
+  }
+}
+__device__ __forceinline__ float4 att_merge(const GemmP& p, int k, const AttReq& r) {
+  float mx = -INFINITY;
+#pragma unroll
+  for (int s = 0; s < ATT_SMAX; ++s)
+    if (s < p.att_S) mx = fmaxf(mx, r.pm[s]);
+  float L = 0.f;
+  float4 a = make_float4(0.f, 0.f, 0.f, 0.f);
+#pragma unroll
+  for (int s = 0; s < ATT_SMAX; ++s)
+    if (s < p.att_S) {
+      const float ms = r.pm[s];
+      const float c = ms > -INFINITY ? expf(ms - mx) : 0.f;
+      L += c * r.pl[s];
+      a.x += c * r.pa[s].x; a.y += c * r.pa[s].y; a.z += c * r.pa[s].z; a.w += c * r.pa[s].w;
+    }
+  const float inv = 1.0f / L;
+  return k < p.K ? make_float4(a.x * inv, a.y * inv, a.z * inv, a.w * inv) : make_float4(0.f, 0.f, 0.f, 0.f);
+}
+
+// ---------------------------------------------------------------------------------------
+// Vector-ALU GEMV (M = 1) / skinny GEMM (M = 2; 4 and 8 with 32-bit weights): one work-group per 16-row block; each
 // lane accumulates one weight row over its wave's span of k tiles, fp32 throughout.
 // M = 1 (the draft path): the gained input row is staged once in LDS (dynamic, KT*TK floats)
 // while the first weight tiles are already in flight; M > 1 reads the rows through the cache.
@@ -269,8 +312,13 @@ __device__ __forceinline__ void valu_tile(const uint4& w, int kt, int g, const f
   }
 }
 
+// Waves per work-group by the number of input rows: every row adds an accumulator, a sum of squares and its
+// share of the input row to a lane's registers, so the several-row forms run with fewer, larger-register waves
+// (at 16 waves they spilled hundreds of registers).
+template <int M> struct ValuWaves { static constexpr int max = M == 1 ? 16 : 4; };
+
 template <int KPL, int M, int EPI>
-__global__ void __launch_bounds__(1024) gemm_valu_k(GemmP p) {
+__global__ void __launch_bounds__(64 * ValuWaves<M>::max) gemm_valu_k(GemmP p) {
   constexpr int TK = 4 * KPL;
   extern __shared__ __align__(16) float xs[];
   __shared__ float red[MAXW][M][16];
@@ -305,6 +353,8 @@ __global__ void __launch_bounds__(1024) gemm_valu_k(GemmP p) {
       if (k < Kp) {
         if (p.att_S > 0) {
           // the input row is the attention output: merge the S per-split softmax partials here
+          // (split by split, in a loop: the batched request of gemv_rows_k would cost this kernel, whose other
+          // instantiations run at the register limit, spills)
           if (k < p.K) {
             const int h = k / p.att_hd, d = k - h * p.att_hd;
             const float* pm = p.att_PM + (size_t)h * p.att_stride;
@@ -462,55 +512,22 @@ __global__ void __launch_bounds__(1024) gemv_rows_k(GemmP p) {
   const int lo_t = wave * NG * GU;                       // this wave's k tiles of every row block: [lo_t, lo_t + NG * GU)
   const bool has_gain = p.gain != nullptr;
   float ss = 0.f;
-  // the input row first (it comes from the cache and every wave needs it before its first product), then tiles
-  const int Kp = KT * TK, stride = blockDim.x * 4;
-  float4 xv[4], gv[4];
-  auto stage_load = [&](int base) {
+  // the input row first (it comes from the cache and every wave needs it before its first product), then tiles.
+  // The row has KT * 32 = 4096 * NJ floats: NJ float4 per thread.  Where it is the attention output, the
+  // partials of the first float4 are requested here and merged once the tile requests are out.
+  constexpr int NJ = NG / 2, XSTRIDE = 64 * ROWS_WAVES * 4;
+  const bool att = p.att_S > 0;
+  float4 xv[NJ], gv[NJ];
+  AttReq rq;
+  if (att) {
+    att_request(p, tid * 4, rq);
+  } else {
 #pragma unroll
-    for (int j = 0; j < 4; ++j) {
-      const int k = base + j * stride;
-      xv[j] = make_float4(0.f, 0.f, 0.f, 0.f);
-      gv[j] = make_float4(1.f, 1.f, 1.f, 1.f);
-      if (k < Kp) {
-        if (p.att_S > 0) {
-          // the input row is the attention output: merge the S per-split softmax partials here
-          if (k < p.K) {
-            const int h = k / p.att_hd, d = k - h * p.att_hd;
-            const float* pm = p.att_PM + (size_t)h * p.att_stride;
-            const float* pl = p.att_PL + (size_t)h * p.att_stride;
-            float mx = -INFINITY;
-            for (int sidx = 0; sidx < p.att_S; ++sidx) mx = fmaxf(mx, pm[sidx]);
-            float L = 0.f;
-            float4 a = make_float4(0.f, 0.f, 0.f, 0.f);
-            for (int sidx = 0; sidx < p.att_S; ++sidx) {
-              const float ms = pm[sidx];
-              const float c = ms > -INFINITY ? expf(ms - mx) : 0.f;
-              L += c * pl[sidx];
-              const float4 t4 = *(const float4*)(p.att_PA + ((size_t)h * p.att_stride + sidx) * p.att_hd + d);
-              a.x += c * t4.x; a.y += c * t4.y; a.z += c * t4.z; a.w += c * t4.w;
-            }
-            const float inv = 1.0f / L;
-            xv[j] = make_float4(a.x * inv, a.y * inv, a.z * inv, a.w * inv);
-          }
-        } else {
-          xv[j] = *(const float4*)(p.X + k);
-        }
-        if (has_gain) gv[j] = *(const float4*)(p.gain + k);
-      }
-    }
-  };
-  auto stage_store = [&](int base) {
+    for (int j = 0; j < NJ; ++j) xv[j] = *(const float4*)(p.X + tid * 4 + j * XSTRIDE);
+  }
 #pragma unroll
-    for (int j = 0; j < 4; ++j) {
-      const int k = base + j * stride;
-      if (k < Kp) {
-        const float4 x = xv[j], gg = gv[j];
-        ss += x.x * x.x + x.y * x.y + x.z * x.z + x.w * x.w;
-        *(float4*)(xs + k) = make_float4(x.x * gg.x, x.y * gg.y, x.z * gg.z, x.w * gg.w);
-      }
-    }
-  };
-  stage_load(tid * 4);
+  for (int j = 0; j < NJ; ++j)
+    gv[j] = has_gain ? *(const float4*)(p.gain + tid * 4 + j * XSTRIDE) : make_float4(1.f, 1.f, 1.f, 1.f);
   const size_t blk_stride = (size_t)nwg * KT * 64;
   const uint4* wp = (const uint4*)p.Wt + ((size_t)wg * KT + lo_t) * 64 + lane;   // this wave's first tile of the current row block
   uint4 ta[GU], tb[GU];
@@ -520,10 +537,19 @@ __global__ void __launch_bounds__(1024) gemv_rows_k(GemmP p) {
   };
   fill(ta, wp);
   fill(tb, wp + GU * 64);
-  stage_store(tid * 4);
-  for (int base = tid * 4 + 4 * stride; base < Kp; base += 4 * stride) {
-    stage_load(base);
-    stage_store(base);
+  if (att) {
+    xv[0] = att_merge(p, tid * 4, rq);
+#pragma unroll
+    for (int j = 1; j < NJ; ++j) {
+      att_request(p, tid * 4 + j * XSTRIDE, rq);
+      xv[j] = att_merge(p, tid * 4 + j * XSTRIDE, rq);
+    }
+  }
+#pragma unroll
+  for (int j = 0; j < NJ; ++j) {
+    const float4 x = xv[j], gg = gv[j];
+    ss += x.x * x.x + x.y * x.y + x.z * x.z + x.w * x.w;
+    *(float4*)(xs + tid * 4 + j * XSTRIDE) = make_float4(x.x * gg.x, x.y * gg.y, x.z * gg.z, x.w * gg.w);
   }
   for (int o = 1; o < 64; o <<= 1) ss += __shfl_xor(ss, o);
   if (lane == 0) ssr[wave] = ss;
@@ -2349,6 +2375,7 @@ __global__ void __launch_bounds__(1024) gemv_parts_k(const uint4* __restrict__ W
 // ---------------------------------------------------------------------------------------
 template <int KPL, int M, int EPI>
 static hipError_t launch_valu_e(const GemmP& p, int waves, hipStream_t s) {
+  while (waves > ValuWaves<M>::max) waves >>= 1;
   dim3 grid(p.NB), block(64 * waves);
   const size_t lds = M == 1 ? (size_t)p.KT * 4 * KPL * sizeof(float) : 0;
   if (lds > 48 * 1024) {  // beyond the default dynamic LDS limit: raise it for this kernel (once is enough)
@@ -2412,13 +2439,15 @@ static hipError_t launch_valu_m(const GemmP& p, int epi, int waves, hipStream_t 
 
 template <int KPL>
 static hipError_t launch_valu_k(const GemmP& p, int epi, int waves, hipStream_t s) {
-  switch (p.M) {
-    case 1: return launch_valu_m<KPL, 1>(p, epi, waves, s);
-    case 2: return launch_valu_m<KPL, 2>(p, epi, waves, s);
-    case 4: return launch_valu_m<KPL, 4>(p, epi, waves, s);
-    case 8: return launch_valu_m<KPL, 8>(p, epi, waves, s);
-    default: return hipErrorInvalidValue;
+  if (p.M == 1) return launch_valu_m<KPL, 1>(p, epi, waves, s);
+  if (p.M == 2) return launch_valu_m<KPL, 2>(p, epi, waves, s);
+  // four and eight rows with 32-bit weights only: with 16-bit weights (twice the values per tile) they do not fit
+  // a lane's registers
+  if constexpr (KPL == 4) {
+    if (p.M == 4) return launch_valu_m<KPL, 4>(p, epi, waves, s);
+    if (p.M == 8) return launch_valu_m<KPL, 8>(p, epi, waves, s);
   }
+  return hipErrorInvalidValue;
 }
 
 bool gemv_rows_applies(const GemmP& p) {
@@ -2432,6 +2461,10 @@ bool gemm_mfma_rows_applies(const GemmP& p, int epi, int col_blocks) {
 
 hipError_t launch_gemm_valu(const GemmP& p, int epi, int waves, hipStream_t s) {
   if (waves < 1 || waves > MAXW || p.NB <= 0 || p.KT <= 0) return hipErrorInvalidValue;
+  // attention partials as the input row: at most ATT_SMAX splits, whole float4 groups of features inside a head
+  if (p.att_S > 0 && (p.att_S > ATT_SMAX || p.att_S > p.att_stride || p.K < 4 || p.att_hd % 4 || p.K % p.att_hd ||
+                      !p.att_PM || !p.att_PL || !p.att_PA))
+    return hipErrorInvalidValue;
   if (gemv_rows_applies(p)) return p.KT == 128 ? launch_rows<2>(p, epi, s) : launch_rows<4>(p, epi, s);
   return p.wdtype == 1 ? launch_valu_k<8>(p, epi, waves, s) : launch_valu_k<4>(p, epi, waves, s);
 }
