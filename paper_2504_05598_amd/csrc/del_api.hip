@@ -296,6 +296,9 @@ GemmP base_gemm(const del_ctx* ctx) {
   p.wdtype = ctx->wd;
   p.eps = ctx->cfg.rms_eps;
   p.rows_form = ctx->rows_form;
+  // between rounds the host's T is the device's; not while a prompt is being absorbed, and not under graph
+  // replay (a captured launch would keep the value it was captured with)
+  p.ctx_len1 = (ctx->phase == 1 && !ctx->use_graphs) ? ctx->T + 1 : 0;
   return p;
 }
 
@@ -354,6 +357,7 @@ del_status run_layer(del_ctx* ctx, int l, int row0, int m, bool chained) {
   a.Q = ctx->q; a.ldq = ctx->qpad; a.Kc = Kc; a.Vc = Vc; a.kvdtype = ctx->wd;
   a.n_q = ctx->nq; a.n_kv = ctx->nkv; a.hd = ctx->hd; a.Tcap = ctx->Tcap; a.m = m;
   a.state = ctx->state; a.row_off = row0;
+  a.ctx_len1 = (ctx->phase == 1 && !ctx->use_graphs) ? ctx->T + 1 : 0;
   a.PM = ctx->PM; a.PL = ctx->PL; a.PA = ctx->PA; a.nch_max = ctx->nch_max; a.ct = ctx->attn_ct;
   a.O = ctx->attn; a.ldo = ctx->qpad;
   a.XsOut = mf ? ctx->xs_attn : nullptr;

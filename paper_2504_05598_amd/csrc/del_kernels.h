@@ -48,6 +48,8 @@ struct GemmP {
   void* VcT; int TcapT;         // QKV, optional: the values also feature-major, [n_kv][hd][TcapT] (bf16)
   int n_q, n_kv, hd, Tcap;
   const int* state;             // state[0] = KV length T
+  int ctx_len1;                 // 0: read T from state[0]; otherwise T + 1 as the host knows it (saves the kernel a
+                                // dependent load ahead of its rotary-table and cache addresses)
   int row_off;                  // position of row mi is state[0] + row_off + mi
   const float2* rope;           // [Tcap][hd/2] (cos, sin)
   float* ACT; int ldact; int d_ffn;  // SWIGLU
@@ -86,6 +88,7 @@ struct AttnP {
   int kvdtype;
   int n_q, n_kv, hd, Tcap, m;
   const int* state; int row_off;
+  int ctx_len1;                 // as in GemmP (one-row register kernel only)
   float* PM; float* PL; float* PA;  // partials [(mi*n_q+h)][nch_max] (+[hd])
   int nch_max;
   int ct;                       // cache rows per work-group (16, 32, 48 or 64)

@@ -136,7 +136,7 @@ __device__ __forceinline__ void epilogue(const GemmP& p, int nb, float (*fin)[16
       const int hd = p.hd, half = hd >> 1;
       const int v0 = nb * 16;
       const int hh = v0 / hd, s0 = v0 - hh * hd;
-      const int pos = p.state[0] + p.row_off + rowbase + mi;
+      const int pos = (p.ctx_len1 ? p.ctx_len1 - 1 : p.state[0]) + p.row_off + rowbase + mi;
       if (hh < p.n_q + p.n_kv) {  // rotary heads: rows r and r+8 are the pair (j, j + hd/2)
         if (r < 8) {
           const int j = (s0 >> 4) * 8 + r;
@@ -1643,7 +1643,7 @@ __global__ void __launch_bounds__(512) attn_decode_k(AttnP p) {
   const int split = blockIdx.x, kvh = blockIdx.y, S = gridDim.x;
   const int mi0 = blockIdx.z * RW;                        // first token row of this work-group
   const int nrow = min(RW, p.m - mi0);                    // rows it really has
-  const int T0 = p.state[0] + p.row_off + mi0;            // row mi0 + r attends cache rows <= T0 + r
+  const int T0 = (p.ctx_len1 ? p.ctx_len1 - 1 : p.state[0]) + p.row_off + mi0;   // row mi0 + r attends cache rows <= T0 + r
   const int T_end = T0 + nrow;
   const int rps = ((T_end + S - 1) / S + RPL - 1) / RPL * RPL;   // rows per split, whole loads
   const int t_lo = split * rps, t_hi = min(T_end, t_lo + rps);
