@@ -428,6 +428,13 @@ def micro(cfg, DelContext):
         mb = nb * kt * 1024
         row = [ctx.gemv_parts_us(nb, kt, waves, parts) for _, parts in cols]
         print(f"{name:8s} {nb:6d} {kt:6d} {waves:5d} {mb / 1e6:7.1f} {mb / ceiling / 1e3:7.2f} " + " ".join(f"{v:28.2f}" for v in row))
+    # issue rate of the two bf16 matrix instructions (del_bench_mfma_rate): one wave per SIMD, independent accumulators,
+    # no memory traffic; TFLOP/s = 1024 SIMDs x flops per instruction / time per instruction
+    print("# del_bench_mfma_rate: ns per instruction and SIMD, TFLOP/s over 256 CUs x 4 SIMDs (dense bf16 peak 2500)")
+    for shape, label, flops, accs in ((0, "v_mfma_f32_16x16x32_bf16", 16384, (2, 4, 8, 16)), (1, "v_mfma_f32_32x32x16_bf16", 32768, (1, 2, 4))):
+        for n_acc in accs:
+            ns = min(ctx.mfma_rate_ns(shape, n_acc) for _ in range(3))
+            print(f"{label:26s} {n_acc:2d} accumulators {ns:7.2f} ns {1024 * flops / ns / 1e3:8.1f} TFLOP/s")
     ctx.close()
 
 

@@ -187,6 +187,12 @@ del_status del_bench_stream_read(del_ctx* ctx, int64_t bytes, int32_t iters, flo
  * of range, DEL_E_CAPACITY if the matrix is larger than the arena. */
 del_status del_bench_gemv_parts(del_ctx* ctx, int32_t n_blocks, int32_t k_tiles, int32_t waves, int32_t parts,
                                 int32_t iters, float* us_per_launch);
+/* Issue rate of the matrix instructions the shadow-head GEMM (Section 4.2) and the prefill GEMMs are built
+ * from: 256 work-groups of 4 waves (one wave per SIMD) each run `iters` rounds of n_acc independent
+ * accumulations with no memory traffic.  shape 0: v_mfma_f32_16x16x32_bf16, n_acc 2, 4, 8 or 16; shape 1:
+ * v_mfma_f32_32x32x16_bf16, n_acc 1, 2 or 4.  ns_per_instruction (host pointer): nanoseconds per instruction
+ * and SIMD; flops per instruction: 16384 (shape 0), 32768 (shape 1).  DEL_E_ARG otherwise. */
+del_status del_bench_mfma_rate(del_ctx* ctx, int32_t shape, int32_t n_acc, int32_t iters, float* ns_per_instruction);
 /* A plain device-to-device copy kernel of `bytes` (reads and writes that many bytes of a
  * temporary buffer): the known-size kernel the profiler's HBM byte counters are scaled by. */
 del_status del_bench_stream_copy(del_ctx* ctx, int64_t bytes, int32_t iters, float* ms_per_iter);

@@ -15,7 +15,7 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 
 EXPORTS = ["del_create", "del_destroy", "del_load_weights", "del_prefill", "del_round", "del_round_dynamic",
            "del_layer_stats", "del_set_layer_stats", "del_last_timings", "del_debug_hidden",
-           "del_debug_logits", "del_debug_state", "del_debug_set_pending", "del_debug_last_rows", "del_profile_enable", "del_profile_read", "del_policy_step", "del_sample_first", "del_round_sample", "del_round_sample_dynamic", "del_debug_spec_sample", "del_spec_sample_static", "del_bench_stream_read", "del_bench_stream_copy", "del_bench_gemv_parts", "del_strerror",
+           "del_debug_logits", "del_debug_state", "del_debug_set_pending", "del_debug_last_rows", "del_profile_enable", "del_profile_read", "del_policy_step", "del_sample_first", "del_round_sample", "del_round_sample_dynamic", "del_debug_spec_sample", "del_spec_sample_static", "del_bench_stream_read", "del_bench_stream_copy", "del_bench_gemv_parts", "del_bench_mfma_rate", "del_strerror",
            "del_last_error_text"]
 
 DEL_DTYPE_FP32, DEL_DTYPE_BF16 = 0, 1
@@ -100,6 +100,7 @@ def load_library():
     lib.del_profile_read.argtypes = [C.c_void_p, P(del_prof_entry), C.c_int32, P(C.c_int32)]
     lib.del_bench_stream_read.argtypes = [C.c_void_p, C.c_int64, C.c_int32, P(C.c_float)]
     lib.del_bench_gemv_parts.argtypes = [C.c_void_p, C.c_int32, C.c_int32, C.c_int32, C.c_int32, C.c_int32, P(C.c_float)]
+    lib.del_bench_mfma_rate.argtypes = [C.c_void_p, C.c_int32, C.c_int32, C.c_int32, P(C.c_float)]
     lib.del_bench_stream_copy.argtypes = [C.c_void_p, C.c_int64, C.c_int32, P(C.c_float)]
     lib.del_policy_step.argtypes = [C.c_int32, C.c_int32, C.c_double, P(C.c_int32), C.c_int32, P(C.c_double),
                                     P(C.c_double), P(C.c_double), P(C.c_double), P(C.c_double), P(C.c_double),
@@ -456,6 +457,12 @@ class DelContext:
         us = C.c_float(0.0)
         _check(load_library().del_bench_gemv_parts(self.ctx, n_blocks, k_tiles, waves, parts, iters, C.byref(us)), self.ctx)
         return float(us.value)
+
+    def mfma_rate_ns(self, shape: int, n_acc: int, iters: int = 20000) -> float:
+        """del_bench_mfma_rate: nanoseconds per matrix instruction and SIMD (shape 0: 16x16x32 bf16, 1: 32x32x16 bf16)."""
+        ns = C.c_float(0.0)
+        _check(load_library().del_bench_mfma_rate(self.ctx, shape, n_acc, iters, C.byref(ns)), self.ctx)
+        return float(ns.value)
 
     def stream_read_gbps(self, nbytes: int, iters: int = 20) -> float:
         ms = C.c_float()

@@ -1648,6 +1648,27 @@ del_status del_bench_gemv_parts(del_ctx* ctx, int32_t n_blocks, int32_t k_tiles,
   return DEL_OK;
 }
 
+del_status del_bench_mfma_rate(del_ctx* ctx, int32_t shape, int32_t n_acc, int32_t iters, float* ns_per_instruction) {
+  if (!ctx || !ns_per_instruction || iters < 1 || iters > 10000000 || shape < 0 || shape > 1) return DEL_E_ARG;
+  const bool ok = shape == 0 ? (n_acc == 2 || n_acc == 4 || n_acc == 8 || n_acc == 16) : (n_acc == 1 || n_acc == 2 || n_acc == 4);
+  if (!ok) return DEL_E_ARG;
+  float* buf = nullptr;
+  const size_t n_init = 512 + 64 * 64, n_all = n_init + 256;
+  HIPCHK(hipMalloc((void**)&buf, n_all * sizeof(float)));
+  hipError_t e = hipMemsetAsync(buf, 0, n_all * sizeof(float), ctx->stream);
+  if (e == hipSuccess) e = launch_mfma_rate(shape, n_acc, buf, buf + n_init, iters, ctx->stream);   // warm-up
+  if (e == hipSuccess) e = hipEventRecord(ctx->ev[0], ctx->stream);
+  if (e == hipSuccess) e = launch_mfma_rate(shape, n_acc, buf, buf + n_init, iters, ctx->stream);
+  if (e == hipSuccess) e = hipEventRecord(ctx->ev[1], ctx->stream);
+  if (e == hipSuccess) e = hipStreamSynchronize(ctx->stream);
+  float ms = 0.f;
+  if (e == hipSuccess) e = hipEventElapsedTime(&ms, ctx->ev[0], ctx->ev[1]);
+  (void)hipFree(buf);
+  if (e != hipSuccess) return ctx->fail(e, "del_bench_mfma_rate");
+  *ns_per_instruction = ms * 1e6f / ((float)iters * (float)n_acc);   // one wave per SIMD: per wave = per SIMD
+  return DEL_OK;
+}
+
 del_status del_bench_stream_copy(del_ctx* ctx, int64_t bytes, int32_t iters, float* ms_per_iter) {
   if (!ctx || !ms_per_iter || iters < 1 || bytes < 1024) return DEL_E_ARG;
   char* buf = nullptr;

@@ -155,6 +155,9 @@ hipError_t launch_stream_copy(const void* src, void* dst, int64_t bytes, hipStre
 hipError_t launch_stream_read(const void* base, int64_t bytes, float* sink, hipStream_t s);
 // The one-row GEMV with parts switched off (bit 0 staging, bit 1 decode + FMA, bit 2 reduce + store) on an
 // NB x KT tile matrix at W; X, G: KT*32 floats, R, Y: NB*16 floats.  KT <= 480, waves 4, 8 or 16.
+// Issue rate of the bf16 matrix instructions (shape 0: 16x16x32 with 2, 4, 8 or 16 accumulators; 1: 32x32x16 with
+// 1, 2 or 4): 256 work-groups of 4 waves run `iters` rounds of n_acc instructions each.
+hipError_t launch_mfma_rate(int shape, int n_acc, const float* init, float* out, int iters, hipStream_t s);
 hipError_t launch_gemv_parts(const void* W, const float* X, const float* G, const float* R, float* Y, int NB, int KT,
                              int waves, int parts, hipStream_t s);
 

@@ -2756,6 +2756,67 @@ hipError_t launch_stream_read(const void* base, int64_t bytes, float* sink, hipS
   return hipGetLastError();
 }
 
+// ---------------------------------------------------------------------------------------
+// Measurement kernel: issue rate of the two bf16 matrix instructions with NACC independent accumulators per
+// wave and no memory traffic in the loop (one wave per SIMD, one work-group per compute unit).  SHAPE 0:
+// v_mfma_f32_16x16x32_bf16 (the instruction the weight tiles are laid out for), 1: v_mfma_f32_32x32x16_bf16.
+// The accumulators start from memory so that they are distinct values; results are discarded.
+// ---------------------------------------------------------------------------------------
+typedef float floatx16 __attribute__((ext_vector_type(16)));
+template <int SHAPE, int NACC>
+__global__ void __launch_bounds__(256) mfma_rate_k(const float* init, float* out, int iters) {
+  const int lane = threadIdx.x & 63;
+  bf16x8 a, b;
+  {
+    const uint4 ua = *(const uint4*)(init + 4 * lane), ub = *(const uint4*)(init + 256 + 4 * lane);
+    a = __builtin_bit_cast(bf16x8, ua);
+    b = __builtin_bit_cast(bf16x8, ub);
+  }
+  float s = 0.f;
+  if (SHAPE == 0) {
+    floatx4 acc[NACC];
+#pragma unroll
+    for (int n = 0; n < NACC; ++n)
+#pragma unroll
+      for (int j = 0; j < 4; ++j) acc[n][j] = init[512 + (n * 4 + j) * 64 + lane];
+    for (int it = 0; it < iters; ++it) {
+#pragma unroll
+      for (int n = 0; n < NACC; ++n) acc[n] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, b, acc[n], 0, 0, 0);
+    }
+#pragma unroll
+    for (int n = 0; n < NACC; ++n) s += acc[n][0] + acc[n][1] + acc[n][2] + acc[n][3];
+  } else {
+    floatx16 acc[NACC];
+#pragma unroll
+    for (int n = 0; n < NACC; ++n)
+#pragma unroll
+      for (int j = 0; j < 16; ++j) acc[n][j] = init[512 + (n * 16 + j) * 64 + lane];
+    for (int it = 0; it < iters; ++it) {
+#pragma unroll
+      for (int n = 0; n < NACC; ++n) acc[n] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, acc[n], 0, 0, 0);
+    }
+#pragma unroll
+    for (int n = 0; n < NACC; ++n)
+#pragma unroll
+      for (int j = 0; j < 16; ++j) s += acc[n][j];
+  }
+  if (s == 12345.678f) out[threadIdx.x] = s;   // keeps the loop alive; the buffers hold zeros
+}
+
+// init: 512 + 64 * 64 floats (zeros will do), out: 256 floats
+hipError_t launch_mfma_rate(int shape, int n_acc, const float* init, float* out, int iters, hipStream_t s) {
+  const dim3 grid(256), block(256);
+#define MFMA_RATE(S, N)                                                                     \
+  if (shape == S && n_acc == N) {                                                           \
+    hipLaunchKernelGGL((mfma_rate_k<S, N>), grid, block, 0, s, init, out, iters);           \
+    return hipGetLastError();                                                               \
+  }
+  MFMA_RATE(0, 2) MFMA_RATE(0, 4) MFMA_RATE(0, 8) MFMA_RATE(0, 16)
+  MFMA_RATE(1, 1) MFMA_RATE(1, 2) MFMA_RATE(1, 4)
+#undef MFMA_RATE
+  return hipErrorInvalidValue;
+}
+
 hipError_t launch_gemv_parts(const void* W, const float* X, const float* G, const float* R, float* Y, int NB, int KT,
                              int waves, int parts, hipStream_t s) {
   if (NB < 1 || KT < 1 || KT > 480 || (waves != 4 && waves != 8 && waves != 16) || parts < 0 || parts > 7)

@@ -27,3 +27,21 @@ def test_gemv_parts_and_stream_hooks_run_and_validate():
         assert lib.del_bench_gemv_parts(ctx.ctx, 1 << 24, 480, 8, 0, 5, C.byref(us)) == 3     # DEL_E_CAPACITY
     finally:
         ctx.close()
+
+
+def test_matrix_instruction_rate_hook_runs_and_validates():
+    from paper_2504_05598_amd.binding import DelContext, load_library
+    from synthdata import get_config
+    ctx = DelContext(get_config("mini_gqa"))
+    try:
+        for shape, n_acc in ((0, 2), (0, 4), (0, 8), (0, 16), (1, 1), (1, 2), (1, 4)):
+            ns = ctx.mfma_rate_ns(shape, n_acc, iters=2000)
+            # a 16x16x32 instruction cannot take less than 16 clocks, a 32x32x16 one less than 32; the clock is below 3 GHz
+            assert (5.0 if shape == 0 else 10.0) < ns < 1e3, (shape, n_acc, ns)
+        lib = load_library()
+        out = C.c_float(0.0)
+        for bad in ((2, 2), (-1, 2), (0, 3), (0, 1), (1, 8), (1, 0)):
+            assert lib.del_bench_mfma_rate(ctx.ctx, bad[0], bad[1], 100, C.byref(out)) == 1, bad   # DEL_E_ARG
+        assert lib.del_bench_mfma_rate(ctx.ctx, 0, 2, 0, C.byref(out)) == 1
+    finally:
+        ctx.close()
