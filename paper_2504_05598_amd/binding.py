@@ -419,11 +419,15 @@ class DelContext:
     def profile_enable(self, on: bool) -> None:
         _check(load_library().del_profile_enable(self.ctx, int(on)), self.ctx)
 
+    def _rows_name(self, e):
+        ng = self._rows_ng(e)
+        return f"gemv_rows_k<2,{e.epilogue},5>" if ng == "2,5" else f"gemv_rows_k<{ng},{e.epilogue}>"
+
     def _rows_ng(self, e):
         """Template argument NG of gemv_rows_k (k tiles = 64 * NG): the input width is the model width,
         except with the residual epilogue (1), where it follows from the bytes of the [d_model, K] matrix."""
         k = e.weight_bytes // (2 * self.cfg.d_model) if e.epilogue == 1 else self.cfg.d_model
-        return k // 2048
+        return "2,5" if k == 5120 else str(k // 2048)      # 160 k tiles: two groups of 5 tiles per wave
 
     def profile_read(self) -> List[dict]:
         cap = 256
@@ -437,7 +441,7 @@ class DelContext:
                 kernel = (f"gemm_valu_k<8,{e.rows},{e.epilogue}>" if e.flavour == 0
                           else f"gemm_mfma_k<{e.epilogue}>" if e.flavour == 1
                           else f"gemm_wide_k<{e.epilogue}>" if e.flavour == 3
-                          else f"gemv_rows_k<{self._rows_ng(e)},{e.epilogue}>" if e.flavour == 4
+                          else self._rows_name(e) if e.flavour == 4
                           else f"gemm_mfma_rows_k<{e.epilogue}>" if e.flavour == 5
                           else "head_gemm4_k" if e.flavour == 6 else "head_gemm_k")
                 out.append({"kernel": kernel, "flavour": ("valu", "mfma", "mfma", "mfma", "valu", "mfma", "mfma")[e.flavour],

@@ -105,7 +105,7 @@ struct AttnP {
 
 hipError_t launch_gemm_valu(const GemmP& p, int epi, int waves, hipStream_t s);
 // Which kernel the two launchers here take for p: the forms with several row blocks per work-group
-// (gemv_rows_k: one row, bf16, 128 or 256 k tiles, at least 256 row blocks; gemm_mfma_rows_k: up to 16 rows,
+// (gemv_rows_k: one row, bf16, 128, 160 or 256 k tiles, at least 256 row blocks; gemm_mfma_rows_k: up to 16 rows,
 // 128 k tiles, at least 256 row blocks, any epilogue but the residual one), unless p.rows_form == 1.
 bool gemv_rows_applies(const GemmP& p);
 bool gemm_mfma_rows_applies(const GemmP& p, int epi, int col_blocks);

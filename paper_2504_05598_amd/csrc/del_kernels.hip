@@ -483,7 +483,8 @@ __global__ void __launch_bounds__(64 * ValuWaves<M>::max) gemm_valu_k(GemmP p) {
 }
 
 // ---------------------------------------------------------------------------------------
-// One-row GEMV, several row blocks per work-group (bf16 weights, KT = 64 * NG k tiles): the grid is one
+// One-row GEMV, several row blocks per work-group (bf16 weights, KT = 16 * NG * GUX k tiles: 64 * NG with groups
+// of 4 tiles, 160 with NG = 2 groups of 5): the grid is one
 // work-group of 16 waves per compute unit and work-group w takes the row blocks w, w + grid, ...  The input
 // row is staged once per work-group instead of once per row block, and a wave's tile requests run on across
 // the row blocks: each wave owns NG groups of 4 tiles of every row block and keeps two groups in flight in two
@@ -496,7 +497,7 @@ __global__ void __launch_bounds__(64 * ValuWaves<M>::max) gemm_valu_k(GemmP p) {
 // ---------------------------------------------------------------------------------------
 constexpr int ROWS_WAVES = 16;
 
-template <int NG, int EPI>
+template <int NG, int EPI, int GUX = GU>
 __global__ void __launch_bounds__(1024) gemv_rows_k(GemmP p) {
   static_assert(NG >= 2 && NG % 2 == 0, "the two register sets take the groups of a row block in turn");
   constexpr int KPL = 8, TK = 32;
@@ -508,14 +509,16 @@ __global__ void __launch_bounds__(1024) gemv_rows_k(GemmP p) {
   const int wg = blockIdx.x, nwg = gridDim.x;
   if (wg >= p.NB) return;                                // uniform, before any barrier
   const int nblk = (p.NB - wg + nwg - 1) / nwg;          // row blocks of this work-group (>= 1)
-  const int KT = p.KT;                                   // = 64 * NG
-  const int lo_t = wave * NG * GU;                       // this wave's k tiles of every row block: [lo_t, lo_t + NG * GU)
+  const int KT = p.KT;                                   // = 16 * NG * GUX (groups of GUX tiles: 4, or 5 for 160 k tiles)
+  const int lo_t = wave * NG * GUX;                      // this wave's k tiles of every row block: [lo_t, lo_t + NG * GUX)
   const bool has_gain = p.gain != nullptr;
   float ss = 0.f;
   // the input row first (it comes from the cache and every wave needs it before its first product), then tiles.
-  // The row has KT * 32 = 4096 * NJ floats: NJ float4 per thread.  Where it is the attention output, the
-  // partials of the first float4 are requested here and merged once the tile requests are out.
-  constexpr int NJ = NG / 2, XSTRIDE = 64 * ROWS_WAVES * 4;
+  // The row has KP = KT * 32 floats: NJ float4 per thread, the last one only for the threads that still fall
+  // inside the row.  Where it is the attention output, the partials of the first float4 are requested here and
+  // merged once the tile requests are out.
+  constexpr int XSTRIDE = 64 * ROWS_WAVES * 4, KP = ROWS_WAVES * NG * GUX * TK, NJ = (KP + XSTRIDE - 1) / XSTRIDE;
+  auto inside = [&](int j) { return (j + 1) * XSTRIDE <= KP || tid * 4 + j * XSTRIDE < KP; };
   const bool att = p.att_S > 0;
   float4 xv[NJ], gv[NJ];
   AttReq rq;
@@ -523,33 +526,40 @@ __global__ void __launch_bounds__(1024) gemv_rows_k(GemmP p) {
     att_request(p, tid * 4, rq);
   } else {
 #pragma unroll
-    for (int j = 0; j < NJ; ++j) xv[j] = *(const float4*)(p.X + tid * 4 + j * XSTRIDE);
+    for (int j = 0; j < NJ; ++j) {
+      // (a thread past the row's end reads the row's last float4 and drops it: no branch around the load)
+      xv[j] = *(const float4*)(p.X + min(tid * 4 + j * XSTRIDE, KP - 4));
+      if (!inside(j)) xv[j] = make_float4(0.f, 0.f, 0.f, 0.f);
+    }
   }
 #pragma unroll
   for (int j = 0; j < NJ; ++j)
-    gv[j] = has_gain ? *(const float4*)(p.gain + tid * 4 + j * XSTRIDE) : make_float4(1.f, 1.f, 1.f, 1.f);
+    gv[j] = has_gain ? *(const float4*)(p.gain + min(tid * 4 + j * XSTRIDE, KP - 4)) : make_float4(1.f, 1.f, 1.f, 1.f);
   const size_t blk_stride = (size_t)nwg * KT * 64;
   const uint4* wp = (const uint4*)p.Wt + ((size_t)wg * KT + lo_t) * 64 + lane;   // this wave's first tile of the current row block
-  uint4 ta[GU], tb[GU];
+  uint4 ta[GUX], tb[GUX];
   auto fill = [&](uint4* t, const uint4* src) {
 #pragma unroll
-    for (int u = 0; u < GU; ++u) t[u] = ld_stream(src + u * 64);
+    for (int u = 0; u < GUX; ++u) t[u] = ld_stream(src + u * 64);
   };
   fill(ta, wp);
-  fill(tb, wp + GU * 64);
+  fill(tb, wp + GUX * 64);
   if (att) {
     xv[0] = att_merge(p, tid * 4, rq);
 #pragma unroll
     for (int j = 1; j < NJ; ++j) {
-      att_request(p, tid * 4 + j * XSTRIDE, rq);
-      xv[j] = att_merge(p, tid * 4 + j * XSTRIDE, rq);
+      xv[j] = make_float4(0.f, 0.f, 0.f, 0.f);
+      if (inside(j)) {
+        att_request(p, tid * 4 + j * XSTRIDE, rq);
+        xv[j] = att_merge(p, tid * 4 + j * XSTRIDE, rq);
+      }
     }
   }
 #pragma unroll
   for (int j = 0; j < NJ; ++j) {
     const float4 x = xv[j], gg = gv[j];
     ss += x.x * x.x + x.y * x.y + x.z * x.z + x.w * x.w;
-    *(float4*)(xs + tid * 4 + j * XSTRIDE) = make_float4(x.x * gg.x, x.y * gg.y, x.z * gg.z, x.w * gg.w);
+    if (inside(j)) *(float4*)(xs + tid * 4 + j * XSTRIDE) = make_float4(x.x * gg.x, x.y * gg.y, x.z * gg.z, x.w * gg.w);
   }
   for (int o = 1; o < 64; o <<= 1) ss += __shfl_xor(ss, o);
   if (lane == 0) ssr[wave] = ss;
@@ -564,7 +574,7 @@ __global__ void __launch_bounds__(1024) gemv_rows_k(GemmP p) {
   float dummy[1] = {0.f};
   auto use = [&](const uint4* t, int gi, float* acc) {
 #pragma unroll
-    for (int u = 0; u < GU; ++u) valu_tile<KPL, 1>(t[u], lo_t + gi * GU + u, g, xs, p, false, acc, dummy);
+    for (int u = 0; u < GUX; ++u) valu_tile<KPL, 1>(t[u], lo_t + gi * GUX + u, g, xs, p, false, acc, dummy);
   };
   // the finished row block: partial sums of the waves through LDS, then wave 0 alone runs the epilogue on its own
   // LDS patch while the other waves go on with the next row block (the patch is free again by then: wave 0 comes
@@ -595,13 +605,13 @@ __global__ void __launch_bounds__(1024) gemv_rows_k(GemmP p) {
     for (int gi = 0; gi < NG; gi += 2) {
       use(ta, gi, acc);
       __builtin_amdgcn_sched_barrier(0);
-      if (gi + 2 < NG) fill(ta, wp + (size_t)(gi + 2) * GU * 64);
+      if (gi + 2 < NG) fill(ta, wp + (size_t)(gi + 2) * GUX * 64);
       else if (more) fill(ta, wn);
       __builtin_amdgcn_sched_barrier(0);
       use(tb, gi + 1, acc);
       __builtin_amdgcn_sched_barrier(0);
-      if (gi + 3 < NG) fill(tb, wp + (size_t)(gi + 3) * GU * 64);
-      else if (more) fill(tb, wn + GU * 64);
+      if (gi + 3 < NG) fill(tb, wp + (size_t)(gi + 3) * GUX * 64);
+      else if (more) fill(tb, wn + GUX * 64);
       __builtin_amdgcn_sched_barrier(0);
     }
     finish(acc[0], nb);
@@ -2394,33 +2404,33 @@ static hipError_t launch_valu_e(const GemmP& p, int waves, hipStream_t s) {
   return hipGetLastError();
 }
 
-// The several-row-blocks-per-work-group form: bf16, one row, KT = 128 or 256, at least one row block per
+// The several-row-blocks-per-work-group form: bf16, one row, KT = 128, 160 or 256, at least one row block per
 // work-group of a grid of ROWS_GRID; p.rows_form == 1 keeps the other kernel.
 constexpr int ROWS_GRID = 256;   // one work-group per compute unit of the MI355X
-template <int NG, int EPI>
+template <int NG, int EPI, int GUX = GU>
 static hipError_t launch_rows_e(const GemmP& p, hipStream_t s) {
   const size_t lds = (size_t)p.KT * 32 * sizeof(float);
   static size_t raised = 0;
   if (lds > 48 * 1024 && lds > raised) {
-    hipError_t e = hipFuncSetAttribute((const void*)gemv_rows_k<NG, EPI>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+    hipError_t e = hipFuncSetAttribute((const void*)gemv_rows_k<NG, EPI, GUX>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
     if (e != hipSuccess) return e;
     raised = lds;
   }
   const dim3 grid(p.NB < ROWS_GRID ? p.NB : ROWS_GRID), block(64 * ROWS_WAVES);
   if (p.ev_start && p.ev_stop)
-    hipExtLaunchKernelGGL((gemv_rows_k<NG, EPI>), grid, block, (uint32_t)lds, s, p.ev_start, p.ev_stop, 0, p);
+    hipExtLaunchKernelGGL((gemv_rows_k<NG, EPI, GUX>), grid, block, (uint32_t)lds, s, p.ev_start, p.ev_stop, 0, p);
   else
-    hipLaunchKernelGGL((gemv_rows_k<NG, EPI>), grid, block, lds, s, p);
+    hipLaunchKernelGGL((gemv_rows_k<NG, EPI, GUX>), grid, block, lds, s, p);
   return hipGetLastError();
 }
-template <int NG>
+template <int NG, int GUX = GU>
 static hipError_t launch_rows(const GemmP& p, int epi, hipStream_t s) {
   switch (epi) {
-    case EPI_STORE: return launch_rows_e<NG, EPI_STORE>(p, s);
-    case EPI_RESID: return launch_rows_e<NG, EPI_RESID>(p, s);
-    case EPI_QKV: return launch_rows_e<NG, EPI_QKV>(p, s);
-    case EPI_SWIGLU: return launch_rows_e<NG, EPI_SWIGLU>(p, s);
-    case EPI_ARGMAX: return launch_rows_e<NG, EPI_ARGMAX>(p, s);
+    case EPI_STORE: return launch_rows_e<NG, EPI_STORE, GUX>(p, s);
+    case EPI_RESID: return launch_rows_e<NG, EPI_RESID, GUX>(p, s);
+    case EPI_QKV: return launch_rows_e<NG, EPI_QKV, GUX>(p, s);
+    case EPI_SWIGLU: return launch_rows_e<NG, EPI_SWIGLU, GUX>(p, s);
+    case EPI_ARGMAX: return launch_rows_e<NG, EPI_ARGMAX, GUX>(p, s);
     default: return hipErrorInvalidValue;
   }
 }
@@ -2451,7 +2461,7 @@ static hipError_t launch_valu_k(const GemmP& p, int epi, int waves, hipStream_t 
 }
 
 bool gemv_rows_applies(const GemmP& p) {
-  return p.wdtype == 1 && p.M == 1 && p.rows_form != 1 && p.NB >= ROWS_GRID && !p.XsOut && (p.KT == 128 || p.KT == 256);
+  return p.wdtype == 1 && p.M == 1 && p.rows_form != 1 && p.NB >= ROWS_GRID && !p.XsOut && (p.KT == 128 || p.KT == 160 || p.KT == 256);
 }
 bool gemm_mfma_rows_applies(const GemmP& p, int epi, int col_blocks) {
   // (not with the residual epilogue: that instantiation does not fit 128 registers, and its matrices have one row
@@ -2465,7 +2475,8 @@ hipError_t launch_gemm_valu(const GemmP& p, int epi, int waves, hipStream_t s) {
   if (p.att_S > 0 && (p.att_S > ATT_SMAX || p.att_S > p.att_stride || p.K < 4 || p.att_hd % 4 || p.K % p.att_hd ||
                       !p.att_PM || !p.att_PL || !p.att_PA))
     return hipErrorInvalidValue;
-  if (gemv_rows_applies(p)) return p.KT == 128 ? launch_rows<2>(p, epi, s) : launch_rows<4>(p, epi, s);
+  if (gemv_rows_applies(p))
+    return p.KT == 128 ? launch_rows<2>(p, epi, s) : p.KT == 160 ? launch_rows<2, 5>(p, epi, s) : launch_rows<4>(p, epi, s);
   return p.wdtype == 1 ? launch_valu_k<8>(p, epi, waves, s) : launch_valu_k<4>(p, epi, waves, s);
 }
 
