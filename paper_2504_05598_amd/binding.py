@@ -420,8 +420,8 @@ class DelContext:
         _check(load_library().del_profile_enable(self.ctx, int(on)), self.ctx)
 
     def _rows_name(self, e):
-        ng = self._rows_ng(e)
-        return f"gemv_rows_k<2,{e.epilogue},5>" if ng == "2,5" else f"gemv_rows_k<{ng},{e.epilogue}>"
+        ng = self._rows_ng(e)   # template arguments as the profiler prints them: groups, epilogue, tiles per group
+        return f"gemv_rows_k<2,{e.epilogue},5>" if ng == "2,5" else f"gemv_rows_k<{ng},{e.epilogue},4>"
 
     def _rows_ng(self, e):
         """Template argument NG of gemv_rows_k (k tiles = 64 * NG): the input width is the model width,
