@@ -119,13 +119,14 @@ struct del_ctx {
   bool verify_flash = true;   // passes of 2..16 rows: attention on the matrix cores, split over the context
   int verify_flash_waves = 1024;   // waves (splits x query heads) that kernel aims for
   float* pval = nullptr; int* pidx = nullptr; float* psum = nullptr;
-  float* conf_dev = nullptr;   // [Rmax] shadow confidences, then [d_max+1] draft confidences
-  float* conf_host = nullptr;  // pinned mirror
+  float* conf_dev = nullptr;   // [Rmax] shadow confidences, then [d_max+1] draft confidences (inside the result block)
+  float* conf_host = nullptr;  // pinned mirror (inside the host result block)
   int* step_host = nullptr;    // pinned: (token id, confidence bits) of the last draft step; bytes 8..15: the
                                // (sequence number, confidence) word a draft step's head writes for the polling host
   unsigned note_seq = 0;
   int* state = nullptr; int* draft_ids = nullptr; int* shadow_ids = nullptr; int* result = nullptr;
   int* ids_dev = nullptr; int* result_host = nullptr;
+  size_t res_ints = 0, res_words = 0;   // ints of a round's result block / all its 32-bit words (ints, then confidences)
   float* logits_dbg = nullptr; float* sink = nullptr;
   // speculative sampling: logits and fixed-point weights of the draft rows [0, d_max] and of the
   // target rows [d_max+1, 2*d_max+1], one SampRow each, and the round's uniform numbers
@@ -582,12 +583,11 @@ void free_all(del_ctx* c) {
   void* ptrs[] = {c->arena, c->embed_t, (c->head_t != c->embed_t) ? c->head_t : nullptr, c->gains, c->kc, c->vc,
                   c->rope, c->hid, c->q, c->attn, c->act, c->xs_layer, c->xs_shadow, c->rowscale, c->xs_h, c->xs_attn,
                   c->xs_h1, c->xs_act, c->ssq_h, c->ssq_h1, c->PM, c->PL,
-                  c->PA, c->pval, c->pidx, c->psum, c->conf_dev, c->state, c->draft_ids, c->shadow_ids, c->result, c->ids_dev,
+                  c->PA, c->pval, c->pidx, c->psum, c->state, c->draft_ids, c->shadow_ids, c->result, c->ids_dev,
                   c->logits_dbg, c->sink, c->stage, c->slog, c->swf, c->srows, c->unif_dev, c->rowscale_w, c->vct};
   for (void* p : ptrs)
     if (p) (void)hipFree(p);
-  if (c->result_host) (void)hipHostFree(c->result_host);
-  if (c->conf_host) (void)hipHostFree(c->conf_host);
+  if (c->result_host) (void)hipHostFree(c->result_host);   // conf_host and conf_dev point into the result blocks
   if (c->step_host) (void)hipHostFree(c->step_host);
   for (auto& e : c->ev)
     if (e) (void)hipEventDestroy(e);
@@ -839,17 +839,21 @@ del_status del_create(const del_config* cfg, void* hip_stream, del_ctx** out) {
   CK(dmalloc(&ctx->pval, (size_t)Rmax * ctx->NBv * 4));
   CK(dmalloc(&ctx->pidx, (size_t)Rmax * ctx->NBv * 4));
   CK(dmalloc(&ctx->psum, (size_t)Rmax * ctx->NBv * 4));
-  CK(dmalloc(&ctx->conf_dev, (size_t)(Rmax + cfg->d_max + 1) * 4));
-  CK(hipHostMalloc((void**)&ctx->conf_host, (size_t)(Rmax + cfg->d_max + 1) * 4, hipHostMallocDefault));
   CK(hipHostMalloc((void**)&ctx->step_host, 16, hipHostMallocDefault));
   memset(ctx->step_host, 0, 16);
   CK(dmalloc(&ctx->state, 16));
   CK(hipMemsetAsync(ctx->state, 0, 16, ctx->stream));
   CK(dmalloc(&ctx->draft_ids, (size_t)(cfg->d_max + 1) * 4));
   CK(dmalloc(&ctx->shadow_ids, (size_t)Rmax * 4));
-  CK(dmalloc(&ctx->result, (size_t)(3 + cfg->d_max + 1 + Rmax) * 4));
+  // a round's results in one block, so that one copy brings them to the host: the counts, drafted and shadow ids
+  // (ints), then the shadow and draft confidences (floats); the same layout in pinned host memory
+  ctx->res_ints = (size_t)(3 + cfg->d_max + 1 + Rmax);
+  ctx->res_words = ctx->res_ints + (size_t)(Rmax + cfg->d_max + 1);
+  CK(dmalloc(&ctx->result, ctx->res_words * 4));
+  ctx->conf_dev = reinterpret_cast<float*>(ctx->result + ctx->res_ints);
   CK(dmalloc(&ctx->ids_dev, (size_t)ctx->Tcap * 4));
-  CK(hipHostMalloc((void**)&ctx->result_host, (size_t)(3 + cfg->d_max + 1 + Rmax) * 4, hipHostMallocDefault));
+  CK(hipHostMalloc((void**)&ctx->result_host, ctx->res_words * 4, hipHostMallocDefault));
+  ctx->conf_host = reinterpret_cast<float*>(ctx->result_host + ctx->res_ints);
   CK(dmalloc(&ctx->logits_dbg, (size_t)ctx->NBv * 16 * 4));
   CK(dmalloc(&ctx->sink, 16));
   {
@@ -1184,10 +1188,7 @@ static del_status round_impl(del_ctx* ctx, int E, int gamma, double tau, int32_t
       del_status st2 = shadow_head(ctx, m);
       if (st2 != DEL_OK) return st2;
       HIPCHK(launch_accept(ctx->state, ctx->draft_ids, ctx->shadow_ids, L, m, E, gamma, ctx->result, s));
-      const size_t nres = (size_t)3 + gamma + (size_t)L * m;
-      HIPCHK(hipMemcpyAsync(ctx->result_host, ctx->result, nres * 4, hipMemcpyDeviceToHost, s));
-      HIPCHK(hipMemcpyAsync(ctx->conf_host, ctx->conf_dev, (size_t)L * m * 4, hipMemcpyDeviceToHost, s));
-      HIPCHK(hipMemcpyAsync(ctx->conf_host + Rmax, dconf, (size_t)(gamma + 1) * 4, hipMemcpyDeviceToHost, s));
+      HIPCHK(hipMemcpyAsync(ctx->result_host, ctx->result, ctx->res_words * 4, hipMemcpyDeviceToHost, s));   // ids + confidences
       return DEL_OK;
     });
     if (st != DEL_OK) return st;
@@ -1309,11 +1310,7 @@ static del_status round_sample_impl(del_ctx* ctx, int E, int gamma, double tau, 
     HIPCHK(launch_samp_accept(ctx->slog, ctx->swf, ctx->srows, ctx->slog + (size_t)VB * ld, ctx->swf + (size_t)VB * ld,
                               ctx->srows + VB, ld, ld, V, gamma, ctx->draft_ids, ctx->unif_dev + cap,
                               ctx->unif_dev + 2 * cap, ctx->state, ctx->shadow_ids, L * m, ctx->result, s));
-    const size_t nres = (size_t)3 + gamma + (size_t)L * m;
-    HIPCHK(hipMemcpyAsync(ctx->result_host, ctx->result, nres * 4, hipMemcpyDeviceToHost, s));
-    HIPCHK(hipMemcpyAsync(ctx->conf_host, ctx->conf_dev, (size_t)L * m * 4, hipMemcpyDeviceToHost, s));
-    if (dynamic)
-      HIPCHK(hipMemcpyAsync(ctx->conf_host + Rmax, dconf, (size_t)(gamma + 1) * 4, hipMemcpyDeviceToHost, s));
+    HIPCHK(hipMemcpyAsync(ctx->result_host, ctx->result, ctx->res_words * 4, hipMemcpyDeviceToHost, s));   // ids + confidences
   }
   HIPCHK(hipEventRecord(ctx->ev[3], s));
   del_status fst = finish_round(ctx, E, gamma, stopped, true, out_tokens, n_out);
