@@ -88,7 +88,7 @@ struct AttnP {
   int kvdtype;
   int n_q, n_kv, hd, Tcap, m;
   const int* state; int row_off;
-  int ctx_len1;                 // as in GemmP (one-row register kernel only)
+  int ctx_len1;                 // as in GemmP
   float* PM; float* PL; float* PA;  // partials [(mi*n_q+h)][nch_max] (+[hd])
   int nch_max;
   int ct;                       // cache rows per work-group (16, 32, 48 or 64)

@@ -1489,7 +1489,7 @@ __global__ void __launch_bounds__(256) attn_partial_k(AttnP p) {
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int c = blockIdx.x, kvh = blockIdx.y;
   const int ct = p.ct;
-  const int T0 = p.state[0] + p.row_off;
+  const int T0 = (p.ctx_len1 ? p.ctx_len1 - 1 : p.state[0]) + p.row_off;
   const int T_end = T0 + p.m;
   const int t0 = c * ct;
   if (t0 >= T_end) return;
@@ -1823,7 +1823,7 @@ __global__ void __launch_bounds__(256) attn_flash_k(AttnP p) {
   const int r0 = blockIdx.x * 64 + wave * 16;
   if (r0 >= p.m) return;                       // wave-uniform; the kernel has no barriers
   const int nrow = min(16, p.m - r0);
-  const int T0 = p.state[0] + p.row_off;       // cache position of token row 0
+  const int T0 = (p.ctx_len1 ? p.ctx_len1 - 1 : p.state[0]) + p.row_off;       // cache position of token row 0
   const int pos = T0 + r0 + qi;                // this lane's query attends cache rows <= pos
   const int t_end = T0 + r0 + nrow;            // cache rows this wave needs: [0, t_end)
   // queries: row r0 + qi (a ragged last block re-reads its last row; those results are dropped)
@@ -1942,7 +1942,7 @@ __global__ void __launch_bounds__(256) attn_flash_split_k(AttnP p, int S, int rp
   if (split >= S) return;                      // wave-uniform; the kernel has no barriers
   const int h = blockIdx.y, kvh = h / (p.n_q / p.n_kv);
   const int nrow = p.m;                        // <= 16, checked by the launcher
-  const int T0 = p.state[0] + p.row_off;       // cache position of token row 0
+  const int T0 = (p.ctx_len1 ? p.ctx_len1 - 1 : p.state[0]) + p.row_off;       // cache position of token row 0
   const int pos = T0 + qi;                     // this lane's query attends cache rows <= pos
   const int t_end = T0 + nrow;                 // cache rows the pass needs: [0, t_end)
   // rows per split: whole tiles of 32, at least what the launcher planned for (attn_combine_k derives the
@@ -2057,7 +2057,7 @@ __global__ void __launch_bounds__(128) attn_combine_k(AttnP p) {
   const int row = blockIdx.x;  // mi * n_q + h
   const int d = threadIdx.x;
   if (d >= p.hd) return;
-  const int T_end = p.state[0] + p.row_off + p.m;
+  const int T_end = (p.ctx_len1 ? p.ctx_len1 - 1 : p.state[0]) + p.row_off + p.m;
   int nch = p.nsplit > 0 ? p.nsplit : (T_end + p.ct - 1) / p.ct;   // partials per row
   if (p.rps > 0) {   // matrix-core kernel, split by spans of rows: only the spans that reach into the context
     const int rps = max(p.rps, ((T_end + p.nsplit - 1) / p.nsplit + 31) / 32 * 32);
