@@ -59,3 +59,14 @@ def test_llama13b_rounds_against_oracle_records():
 @pytest.mark.timeout(1100)
 def test_llama70b_rounds_against_oracle_records():
     _replay("llama70b", 3, False)
+
+
+@pytest.mark.timeout(600)
+@pytest.mark.parametrize("splits", ["1", "8"])
+def test_llama7b_records_with_other_context_splits_of_the_one_row_attention(splits, monkeypatch):
+    """The draft rows' attention is split over the context and its partials are merged by the output
+    projection: one split (nothing to merge) and eight (the most the merge takes) instead of the default four,
+    against the same records."""
+    monkeypatch.setenv("DEL_ATTN_SPLITS", splits)
+    rep = _replay("llama7b", 20, True)
+    assert len(rep.tokens) >= 256
