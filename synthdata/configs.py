@@ -99,6 +99,11 @@ CONFIGS = {
     # (the shapes for which the one-row GEMV takes several row blocks per work-group), ragged vocabulary
     "wide_d4096": ModelConfig("wide_d4096", 3, 4096, 32, 8, 128, 4096, 4111, 1e4, False, "bf16", 0.6,
                               40, 40, 6, 16, norm_gain_std=0.1),
+    # d_model of the 13B shape on three layers: 160 k tiles per row (the one-row GEMV then takes groups of 5 tiles),
+    # as many kv heads as query heads, the feed-forward width equal to d_model so that the down projection takes
+    # the same kernel
+    "wide_d5120": ModelConfig("wide_d5120", 3, 5120, 40, 40, 128, 5120, 4111, 1e4, False, "bf16", 0.6,
+                              40, 40, 6, 18, norm_gain_std=0.1),
     "mini_fp32": ModelConfig("mini_fp32", 3, 192, 6, 2, 32, 520, 3000, 1e4, False, "fp32", 0.6,
                              21, 24, 5, 13, norm_gain_std=0.1),
 }

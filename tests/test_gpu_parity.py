@@ -332,6 +332,27 @@ def test_model_width_4096_both_forms_of_the_one_row_gemv(rows_form, monkeypatch)
     ctx.close()
 
 
+def test_model_width_5120_one_row_gemv_with_groups_of_five_tiles():
+    """d_model 5120 (160 k tiles per row): the draft path's GEMVs, the down projection included, run the
+    several-row-blocks kernel with groups of 5 tiles, and the output projection merges the attention partials of
+    40 heads; greedy, draft-exiting and fixed-schedule rounds in lock-step with the oracle."""
+    from gpu_harness import lockstep
+    cfg, ctx, oracle = _setup("wide_d5120")
+    prompt = gen_prompt(cfg).tolist()
+    rep = lockstep(cfg, oracle, ctx, prompt, cfg.gen_len)
+    _check_report(rep, "wide_d5120")
+    rep = lockstep(cfg, oracle, ctx, prompt, 24, dynamic=True)
+    _check_report(rep, "wide_d5120 dynamic")
+    rep = lockstep(cfg, oracle, ctx, prompt, 32, schedule=(2, 3))
+    _check_report(rep, "wide_d5120 E=2 gamma=3")
+    ctx.profile_enable(True)
+    lockstep(cfg, oracle, ctx, prompt, 12, schedule=(2, 2))
+    names = {e["kernel"] for e in ctx.profile_read()}
+    ctx.profile_enable(False)
+    assert {"gemv_rows_k<2,2,5>", "gemv_rows_k<2,1,5>", "gemv_rows_k<2,3,5>", "gemv_rows_k<2,4,5>"} <= names, names
+    ctx.close()
+
+
 def test_paper_d_max_18_rounds_of_more_than_16_rows():
     """Appendix B.2's d_max = 18: rounds whose verify pass has up to 19 rows (more than one block of 16
     token rows), fixed long schedules and the DEL-driven run, on the matrix-core and on the vector path."""
